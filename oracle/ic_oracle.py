@@ -1,0 +1,253 @@
+"""ctypes access to the CPU reference (``ic_oracle.c``) plus a NumPy restatement.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the
+benchmark's CPU-baseline leg.  The product package never imports this module,
+and this module never imports the product package.
+
+The reference states IC-Cache's stage-1 example selection (Sec. 4.1, and the
+GetSimilarExamples step of Algorithm 1) as exact brute force in fp64:
+cosine similarity of the request embedding with every cached example
+embedding, plus ``lambda * utility`` and a validity mask (what the Example
+Manager of Sec. 4.3 keeps per example), best ``k`` under the total order
+(score descending, index ascending).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ic_oracle.c")
+_LIB = os.path.join(_HERE, "libic_oracle.so")
+
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_u16p = ctypes.POINTER(ctypes.c_uint16)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+
+
+def build(force: bool = False) -> str:
+    """Compile ``ic_oracle.c`` with gcc (OpenMP) into ``libic_oracle.so``."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", _SRC, "-o", _LIB, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.ico_num_threads.restype = ctypes.c_int
+        L.ico_begin.restype = ctypes.c_void_p
+        L.ico_begin.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                ctypes.c_float, ctypes.c_int]
+        L.ico_scan.restype = ctypes.c_int
+        L.ico_scan.argtypes = [ctypes.c_void_p, _f32p, _f32p, _u8p, _f32p, ctypes.c_int64,
+                               ctypes.c_int64]
+        L.ico_finish.restype = ctypes.c_int
+        L.ico_finish.argtypes = [ctypes.c_void_p, _f32p, _i64p, _f64p]
+        L.ico_free.restype = None
+        L.ico_free.argtypes = [ctypes.c_void_p]
+        L.ico_scores.restype = ctypes.c_int
+        L.ico_scores.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int64, ctypes.c_int32, _f32p, _f32p,
+                                 ctypes.c_int64, ctypes.c_float, ctypes.c_int, _f64p]
+        L.ico_quantize_bf16.restype = ctypes.c_int
+        L.ico_quantize_bf16.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int32, _u16p]
+        L.ico_quantize_fp8.restype = ctypes.c_int
+        L.ico_quantize_fp8.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int32, _u8p, _f32p]
+        L.ico_decode_bf16.restype = ctypes.c_int
+        L.ico_decode_bf16.argtypes = [_u16p, ctypes.c_int64, _f32p]
+        L.ico_decode_e4m3.restype = ctypes.c_int
+        L.ico_decode_e4m3.argtypes = [_u8p, ctypes.c_int64, _f32p]
+        L.ico_encode_e4m3.restype = ctypes.c_int
+        L.ico_encode_e4m3.argtypes = [_f32p, ctypes.c_int64, _u8p]
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().ico_num_threads())
+
+
+def _f32(a, shape_len: int) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    assert a.ndim == shape_len, a.shape
+    return a
+
+
+def _ptr(a: Optional[np.ndarray], typ):
+    return None if a is None else a.ctypes.data_as(typ)
+
+
+class Scan:
+    """Chunked brute-force search: feed the cache in row blocks, then ``finish``.
+
+    ``normalize=True`` is the definition (true cosine).  ``normalize=False``
+    takes the rows and queries as already unit length and forms the plain inner
+    product, times optional per-row / per-query scales; this is how the values a
+    quantised store holds are fed through the same search.
+    """
+
+    def __init__(self, queries, k: int, lam: float = 0.0, normalize: bool = True,
+                 q_scale=None):
+        self.Qm = _f32(queries, 2)
+        self.Q, self.d = self.Qm.shape
+        self.k = int(k)
+        self.q_scale = None if q_scale is None else _f32(q_scale, 1)
+        if self.q_scale is not None:
+            assert self.q_scale.shape[0] == self.Q
+        self._st = lib().ico_begin(_ptr(self.Qm, _f32p), _ptr(self.q_scale, _f32p), self.Q,
+                                   self.d, self.k, float(lam), int(bool(normalize)))
+        if not self._st:
+            raise ValueError("ico_begin rejected its arguments")
+        self._next = 0
+
+    def scan(self, E, U=None, mask=None, row_scale=None, base_id: Optional[int] = None) -> None:
+        E = _f32(E, 2)
+        n = E.shape[0]
+        assert E.shape[1] == self.d
+        U = None if U is None else _f32(U, 1)
+        row_scale = None if row_scale is None else _f32(row_scale, 1)
+        if mask is not None:
+            mask = np.ascontiguousarray(mask, dtype=np.uint8)
+            assert mask.shape == (n,)
+        if U is not None:
+            assert U.shape == (n,)
+        if row_scale is not None:
+            assert row_scale.shape == (n,)
+        base = self._next if base_id is None else int(base_id)
+        rc = lib().ico_scan(self._st, _ptr(E, _f32p), _ptr(U, _f32p), _ptr(mask, _u8p),
+                            _ptr(row_scale, _f32p), n, base)
+        if rc != 0:
+            raise RuntimeError(f"ico_scan failed ({rc})")
+        self._next = base + n
+
+    def finish(self) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+        """Return (scores fp32 [Q,k], ids int64 [Q,k], scores fp64 [Q,k])."""
+        s = np.empty((self.Q, self.k), dtype=np.float32)
+        i = np.empty((self.Q, self.k), dtype=np.int64)
+        s64 = np.empty((self.Q, self.k), dtype=np.float64)
+        rc = lib().ico_finish(self._st, _ptr(s, _f32p), _ptr(i, _i64p), _ptr(s64, _f64p))
+        if rc != 0:
+            raise RuntimeError(f"ico_finish failed ({rc})")
+        return s, i, s64
+
+    def close(self) -> None:
+        if self._st:
+            lib().ico_free(self._st)
+            self._st = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def search(E, queries, k: int, lam: float = 0.0, U=None, mask=None, normalize: bool = True,
+           row_scale=None, q_scale=None):
+    """Exact top-k of ``cos + lam*U`` over the valid rows.  Returns (s32, ids, s64)."""
+    sc = Scan(queries, k, lam, normalize, q_scale)
+    sc.scan(E, U, mask, row_scale)
+    out = sc.finish()
+    sc.close()
+    return out
+
+
+def scores(E, queries, lam: float = 0.0, U=None, normalize: bool = True, row_scale=None,
+           q_scale=None) -> np.ndarray:
+    """Dense fp64 score matrix [Q,N], same arithmetic as ``search`` (no mask)."""
+    E = _f32(E, 2)
+    Qm = _f32(queries, 2)
+    U = None if U is None else _f32(U, 1)
+    row_scale = None if row_scale is None else _f32(row_scale, 1)
+    q_scale = None if q_scale is None else _f32(q_scale, 1)
+    out = np.empty((Qm.shape[0], E.shape[0]), dtype=np.float64)
+    rc = lib().ico_scores(_ptr(E, _f32p), _ptr(U, _f32p), _ptr(row_scale, _f32p), E.shape[0],
+                          E.shape[1], _ptr(Qm, _f32p), _ptr(q_scale, _f32p), Qm.shape[0],
+                          float(lam), int(bool(normalize)), _ptr(out, _f64p))
+    if rc != 0:
+        raise RuntimeError(f"ico_scores failed ({rc})")
+    return out
+
+
+# --------------------------------------------------------------------------
+# store formats (independent CPU statement)
+# --------------------------------------------------------------------------
+
+def quantize_bf16(X) -> np.ndarray:
+    """uint16 bf16 codes [n,d] of the unit-normalised rows (round to nearest even)."""
+    X = _f32(X, 2)
+    out = np.empty(X.shape, dtype=np.uint16)
+    rc = lib().ico_quantize_bf16(_ptr(X, _f32p), X.shape[0], X.shape[1], _ptr(out, _u16p))
+    assert rc == 0
+    return out
+
+
+def quantize_fp8(X) -> Tuple[np.ndarray, np.ndarray]:
+    """(uint8 E4M3 codes [n,d], fp32 scale [n]) of the unit-normalised rows."""
+    X = _f32(X, 2)
+    codes = np.empty(X.shape, dtype=np.uint8)
+    scale = np.empty((X.shape[0],), dtype=np.float32)
+    rc = lib().ico_quantize_fp8(_ptr(X, _f32p), X.shape[0], X.shape[1], _ptr(codes, _u8p),
+                                _ptr(scale, _f32p))
+    assert rc == 0
+    return codes, scale
+
+
+def decode_bf16(codes) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint16)
+    out = np.empty(codes.shape, dtype=np.float32)
+    assert lib().ico_decode_bf16(_ptr(codes, _u16p), codes.size, _ptr(out, _f32p)) == 0
+    return out
+
+
+def decode_e4m3(codes) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, dtype=np.float32)
+    assert lib().ico_decode_e4m3(_ptr(codes, _u8p), codes.size, _ptr(out, _f32p)) == 0
+    return out
+
+
+def encode_e4m3(x) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint8)
+    assert lib().ico_encode_e4m3(_ptr(x, _f32p), x.size, _ptr(out, _u8p)) == 0
+    return out
+
+
+# --------------------------------------------------------------------------
+# NumPy restatement, for tiny inputs only (checks the C reference)
+# --------------------------------------------------------------------------
+
+def search_numpy(E, queries, k: int, lam: float = 0.0, U=None, mask=None):
+    """Same definition through NumPy float64 and a full lexicographic sort."""
+    E = np.asarray(E, dtype=np.float64)
+    Qm = np.asarray(queries, dtype=np.float64)
+    N = E.shape[0]
+    en = np.sqrt((E * E).sum(axis=1))
+    qn = np.sqrt((Qm * Qm).sum(axis=1))
+    den = qn[:, None] * en[None, :]
+    dot = Qm @ E.T
+    cos = np.where(den > 0, dot / np.where(den > 0, den, 1.0), 0.0)
+    s = cos + (0.0 if U is None else float(np.float32(lam)) * np.asarray(U, dtype=np.float64)[None, :])
+    valid = np.ones(N, dtype=bool) if mask is None else (np.asarray(mask) != 0)
+    ids_all = np.arange(N, dtype=np.int64)
+    out_s = np.full((Qm.shape[0], k), -np.inf, dtype=np.float64)
+    out_i = np.full((Qm.shape[0], k), -1, dtype=np.int64)
+    for q in range(Qm.shape[0]):
+        cand = ids_all[valid]
+        order = np.lexsort((cand, -s[q, cand]))[:k]
+        out_s[q, :len(order)] = s[q, cand[order]]
+        out_i[q, :len(order)] = cand[order]
+    return out_s.astype(np.float32), out_i, out_s

@@ -1,0 +1,356 @@
+"""Pins for the CPU reference: closed forms, hand-built caches, invariants.
+
+The paper prints no retrieval value, so the reference is pinned by what the
+definition (Sec. 4.1, stage 1: cosine similarity of embeddings, keep the most
+similar; utility and validity per Sec. 4.3) and arithmetic fix.  Each test is
+aimed at one plausible mistake: a transposed operand, a dropped norm, a wrong
+tie rule, a sign slip in the utility term, an off-by-one in k or in the mask.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(path):
+    out = []
+    with open(path) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                out.append(line.split())
+    return out
+
+
+# ---------------------------------------------------------------- closed forms
+
+def test_planar_angles_golden(oracle):
+    """cos of known angles; rows have arbitrary lengths (cosine, not dot product)."""
+    rows = _rows(os.path.join(GOLD, "angles_2d.txt"))
+    ang = np.array([float(r[0]) for r in rows])
+    want = np.array([float(r[1]) for r in rows])
+    lengths = np.linspace(0.25, 7.0, len(ang))
+    # shuffle so that index order is not angle order
+    perm = np.array([4, 0, 7, 2, 8, 1, 6, 3, 5])
+    E = np.stack([lengths * np.cos(np.radians(ang)), lengths * np.sin(np.radians(ang))], 1)[perm]
+    q = np.array([[3.0, 0.0]], dtype=np.float32)
+    s32, ids, s64 = oracle.search(E.astype(np.float32), q, k=len(ang))
+    # ranking = increasing angle
+    assert list(ids[0]) == [int(np.where(perm == j)[0][0]) for j in range(len(ang))]
+    assert np.allclose(s64[0], want, atol=2e-7)  # fp32 rounding of the hand-made rows
+    assert s32.dtype == np.float32 and np.allclose(s32[0], want, atol=2e-7)
+
+
+def test_signed_basis_cache(oracle):
+    """Rows +e_0..+e_{d-1}, then -e_0..-e_{d-1}; query e_j."""
+    d, j, k = 12, 5, 2 * 12
+    E = np.concatenate([np.eye(d), -np.eye(d)]).astype(np.float32)
+    q = np.zeros((1, d), np.float32)
+    q[0, j] = 2.5
+    s32, ids, s64 = oracle.search(E, q, k=k)
+    assert ids[0, 0] == j and s64[0, 0] == 1.0
+    # all other rows score exactly 0 and come in index order; -e_j is last with -1
+    zeros = [i for i in range(2 * d) if i not in (j, d + j)]
+    assert list(ids[0, 1:-1]) == zeros
+    assert np.all(s64[0, 1:-1] == 0.0)
+    assert ids[0, -1] == d + j and s64[0, -1] == -1.0
+
+
+def test_transposed_operands_would_fail(oracle):
+    """Non-square, asymmetric case: result depends on which side is the query."""
+    E = np.array([[1, 0, 0], [0, 1, 0], [1, 1, 0], [0, 0, 1]], np.float32)
+    Q = np.array([[1, 1, 0], [0, 0, 2]], np.float32)
+    s32, ids, s64 = oracle.search(E, Q, k=2)
+    assert list(ids[0]) == [2, 0] and list(ids[1]) == [3, 0]
+    assert math.isclose(s64[0, 0], 1.0, abs_tol=1e-15)
+    assert math.isclose(s64[0, 1], 1 / math.sqrt(2), abs_tol=1e-15)
+    assert s64[1, 0] == 1.0 and s64[1, 1] == 0.0
+
+
+def test_duplicates_rank_by_index(oracle):
+    rng = np.random.default_rng(1)
+    v = rng.standard_normal(16).astype(np.float32)
+    other = rng.standard_normal((5, 16)).astype(np.float32)
+    E = np.stack([other[0], v, other[1], v, v, other[2], 3 * v, other[3], other[4]])
+    s32, ids, s64 = oracle.search(E, v[None], k=4)
+    assert list(ids[0]) == [1, 3, 4, 6]           # scale 3*v ties with v: same cosine
+    assert np.allclose(s64[0], 1.0, atol=1e-15)
+
+
+def test_zero_rows_and_zero_query(oracle):
+    E = np.array([[0, 0], [1, 0], [0, 0], [-1, 0]], np.float32)
+    U = np.array([0.5, 0.0, 0.25, 0.0], np.float32)
+    s32, ids, s64 = oracle.search(E, np.array([[1, 0]], np.float32), k=4, lam=1.0, U=U)
+    assert list(ids[0]) == [1, 0, 2, 3]
+    assert list(s64[0]) == [1.0, 0.5, 0.25, -1.0]
+    s32, ids, s64 = oracle.search(E, np.array([[0, 0]], np.float32), k=2, lam=1.0, U=U)
+    assert list(ids[0]) == [0, 2] and list(s64[0]) == [0.5, 0.25]
+
+
+# ---------------------------------------------------------------- utility term
+
+def _rand_case(seed, N=300, d=24, Q=5):
+    rng = np.random.default_rng(seed)
+    E = rng.standard_normal((N, d)).astype(np.float32)
+    Qm = rng.standard_normal((Q, d)).astype(np.float32)
+    U = rng.random(N).astype(np.float32)
+    mask = (rng.random(N) < 0.8).astype(np.uint8)
+    return E, Qm, U, mask
+
+
+def test_lambda_zero_is_pure_cosine(oracle):
+    E, Qm, U, mask = _rand_case(2)
+    a = oracle.search(E, Qm, k=17, lam=0.0, U=U)
+    b = oracle.search(E, Qm, k=17)
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+
+
+def test_large_lambda_orders_by_utility(oracle):
+    E, Qm, U, mask = _rand_case(3)
+    U = np.round(U * 8) / 8       # many equal utilities: ties fall back on cosine
+    _, ids, s64 = oracle.search(E, Qm, k=40, lam=1.0e6, U=U.astype(np.float32))
+    for q in range(Qm.shape[0]):
+        got_u = U[ids[q]]
+        assert np.all(np.diff(got_u) <= 0)
+        assert got_u[0] == U.max()
+
+
+def test_utility_value_and_sign(oracle):
+    """One row, closed form: s = cos + lambda*u, with negative lambda too."""
+    E = np.array([[1, 1]], np.float32)
+    q = np.array([[1, 0]], np.float32)
+    U = np.array([0.75], np.float32)
+    for lam in (0.5, -0.5, 0.1):
+        _, ids, s64 = oracle.search(E, q, k=1, lam=lam, U=U)
+        want = 1 / math.sqrt(2) + float(np.float32(lam)) * 0.75
+        assert math.isclose(s64[0, 0], want, abs_tol=1e-15)
+
+
+def test_raising_utility_never_lowers_rank(oracle):
+    E, Qm, U, mask = _rand_case(4)
+    k = E.shape[0]
+    _, ids0, _ = oracle.search(E, Qm, k=k, lam=0.3, U=U)
+    U2 = U.copy()
+    U2[123] += 0.4
+    _, ids1, _ = oracle.search(E, Qm, k=k, lam=0.3, U=U2)
+    for q in range(Qm.shape[0]):
+        assert list(ids1[q]).index(123) <= list(ids0[q]).index(123)
+
+
+# ---------------------------------------------------------------- mask / k / padding
+
+def test_mask_equals_search_on_filtered_cache(oracle):
+    E, Qm, U, mask = _rand_case(5)
+    keep = np.flatnonzero(mask)
+    a = oracle.search(E, Qm, k=25, lam=0.2, U=U, mask=mask)
+    b = oracle.search(E[keep], Qm, k=25, lam=0.2, U=U[keep])
+    assert np.array_equal(a[1], keep[b[1]])
+    assert np.array_equal(a[2], b[2])
+    assert not np.isin(a[1], np.flatnonzero(mask == 0)).any()
+
+
+def test_fewer_valid_rows_than_k_pads(oracle):
+    E, Qm, U, mask = _rand_case(6, N=10)
+    mask = np.array([0, 1, 0, 0, 1, 0, 0, 1, 0, 0], np.uint8)
+    s32, ids, s64 = oracle.search(E, Qm, k=6, mask=mask)
+    assert np.all(ids[:, 3:] == -1) and np.all(np.isneginf(s32[:, 3:]))
+    assert np.all(np.sort(ids[:, :3], axis=1) == np.array([1, 4, 7]))
+    s32, ids, _ = oracle.search(E, Qm, k=3, mask=np.zeros(10, np.uint8))
+    assert np.all(ids == -1) and np.all(np.isneginf(s32))
+
+
+def test_prefix_property(oracle):
+    E, Qm, U, mask = _rand_case(7)
+    big = oracle.search(E, Qm, k=50, lam=0.1, U=U, mask=mask)
+    for kk in (1, 2, 13, 49):
+        small = oracle.search(E, Qm, k=kk, lam=0.1, U=U, mask=mask)
+        assert np.array_equal(small[1], big[1][:, :kk])
+        assert np.array_equal(small[2], big[2][:, :kk])
+
+
+def test_k_equals_n_is_full_sort(oracle):
+    E, Qm, U, mask = _rand_case(8, N=64)
+    _, ids, s64 = oracle.search(E, Qm, k=64)
+    assert np.all(np.sort(ids, axis=1) == np.arange(64))
+    assert np.all(np.diff(s64, axis=1) <= 0)
+
+
+# ---------------------------------------------------------------- structure invariants
+
+def test_batch_independence_and_permutation(oracle):
+    E, Qm, U, mask = _rand_case(9)
+    full = oracle.search(E, Qm, k=9, lam=0.05, U=U, mask=mask)
+    for q in range(Qm.shape[0]):
+        one = oracle.search(E, Qm[q:q + 1], k=9, lam=0.05, U=U, mask=mask)
+        assert np.array_equal(one[1][0], full[1][q]) and np.array_equal(one[2][0], full[2][q])
+    perm = np.random.default_rng(0).permutation(E.shape[0])
+    p = oracle.search(E[perm], Qm, k=9, lam=0.05, U=U[perm], mask=mask[perm])
+    assert np.array_equal(perm[p[1]], full[1])       # no exact ties in random data
+
+
+def test_scale_invariance(oracle):
+    E, Qm, U, mask = _rand_case(10)
+    a = oracle.search(E, Qm, k=11)
+    rs = (2.0 ** np.random.default_rng(1).integers(-6, 7, E.shape[0])).astype(np.float32)
+    b = oracle.search(E * rs[:, None], Qm * np.float32(8.0), k=11)   # powers of two: exact
+    assert np.array_equal(a[1], b[1]) and np.allclose(a[2], b[2], atol=1e-15)
+
+
+def test_chunked_scan_equals_one_shot(oracle):
+    E, Qm, U, mask = _rand_case(11, N=1000)
+    one = oracle.search(E, Qm, k=20, lam=0.3, U=U, mask=mask)
+    sc = oracle.Scan(Qm, 20, 0.3)
+    for lo, hi in ((0, 1), (1, 130), (130, 130), (130, 777), (777, 1000)):
+        sc.scan(E[lo:hi], U[lo:hi], mask[lo:hi])
+    got = sc.finish()
+    assert np.array_equal(one[1], got[1]) and np.array_equal(one[2], got[2])
+
+
+def test_unit_vector_scores_in_range_and_self_match(oracle):
+    rng = np.random.default_rng(12)
+    E = rng.standard_normal((500, 48)).astype(np.float32)
+    E /= np.linalg.norm(E, axis=1, keepdims=True)
+    S = oracle.scores(E, E[:20])
+    assert S.min() >= -1 - 1e-12 and S.max() <= 1 + 1e-12
+    _, ids, s64 = oracle.search(E, E[:20], k=1)
+    assert list(ids[:, 0]) == list(range(20)) and np.allclose(s64[:, 0], 1.0, atol=1e-12)
+
+
+def test_against_numpy_restatement(oracle):
+    for seed in range(4):
+        E, Qm, U, mask = _rand_case(20 + seed, N=1500, d=33, Q=7)
+        a = oracle.search(E, Qm, k=31, lam=0.15, U=U, mask=mask)
+        b = oracle.search_numpy(E, Qm, k=31, lam=0.15, U=U, mask=mask)
+        assert np.array_equal(a[1], b[1])
+        assert np.allclose(a[2], b[2], atol=1e-13)
+
+
+def test_scores_matrix_matches_search_and_closed_form(oracle):
+    E, Qm, U, mask = _rand_case(13, N=200)
+    S = oracle.scores(E, Qm, lam=0.25, U=U)
+    # independent closed form through numpy longdouble sums
+    El, Ql = E.astype(np.longdouble), Qm.astype(np.longdouble)
+    want = (Ql @ El.T) / np.outer(np.sqrt((Ql * Ql).sum(1)), np.sqrt((El * El).sum(1)))
+    want = want + np.longdouble(np.float32(0.25)) * U.astype(np.longdouble)[None]
+    assert np.allclose(S, want.astype(np.float64), atol=1e-14)
+    _, ids, s64 = oracle.search(E, Qm, k=5, lam=0.25, U=U)
+    for q in range(Qm.shape[0]):
+        assert np.array_equal(s64[q], S[q, ids[q]])
+
+
+def test_inner_product_mode_with_scales(oracle):
+    """normalize=False: s = qs*rs*<q,e> + lam*u, no division by norms."""
+    E = np.array([[2, 0], [0, 3], [1, 1]], np.float32)
+    q = np.array([[1, 2]], np.float32)
+    rs = np.array([0.5, 1.0, 2.0], np.float32)
+    qs = np.array([0.25], np.float32)
+    U = np.array([1.0, 0.0, 0.0], np.float32)
+    _, ids, s64 = oracle.search(E, q, k=3, lam=1.0, U=U, normalize=False, row_scale=rs, q_scale=qs)
+    # dots 2, 6, 3 -> scaled 0.25, 1.5, 1.5 ; +u -> 1.25, 1.5, 1.5
+    assert list(ids[0]) == [1, 2, 0] and list(s64[0]) == [1.5, 1.5, 1.25]
+
+
+# ---------------------------------------------------------------- store formats
+
+def test_bf16_rounding_golden(oracle):
+    rows = _rows(os.path.join(GOLD, "bf16_ties.txt"))
+    bits = np.array([int(r[0], 16) for r in rows], dtype=np.uint32)
+    want = np.array([int(r[1], 16) for r in rows], dtype=np.uint16)
+    vals = bits.view(np.float32)
+    # quantize_bf16 normalises rows; use 1-element rows through decode/encode of the raw value:
+    # a row [v, w] with w chosen so the norm is exactly representable is awkward, so the
+    # raw rounding is checked through rows that are already unit length: [v] -> v/|v| = +-1.
+    # The raw RNE table is therefore checked through the decode side plus a torch cross-check.
+    import torch
+    t = torch.from_numpy(vals.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(t, want)            # the table itself agrees with an independent RNE
+    dec = oracle.decode_bf16(want)
+    assert np.array_equal(dec.view(np.uint32), want.astype(np.uint32) << 16)
+
+
+def test_bf16_quantiser_matches_independent_rne(oracle):
+    import torch
+    rng = np.random.default_rng(14)
+    X = rng.standard_normal((200, 96)).astype(np.float32) * 3
+    codes = oracle.quantize_bf16(X)
+    unit = (X.astype(np.float64) / np.sqrt((X.astype(np.float64) ** 2).sum(1, keepdims=True))).astype(np.float32)
+    want = torch.from_numpy(unit).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(codes, want)
+    err = np.abs(oracle.decode_bf16(codes).astype(np.float64) - unit)
+    assert np.all(err <= 2.0 ** -8 * np.abs(unit))      # half an ulp of an 8-bit significand
+
+
+def test_e4m3_decode_golden_and_roundtrip(oracle):
+    rows = _rows(os.path.join(GOLD, "e4m3_codes.txt"))
+    codes = np.array([int(r[0], 16) for r in rows], dtype=np.uint8)
+    want = np.array([float(r[1]) for r in rows], dtype=np.float32)
+    assert np.array_equal(oracle.decode_e4m3(codes), want)
+    # every finite code encodes back to itself; -0 keeps its sign bit
+    allc = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    vals = oracle.decode_e4m3(allc)
+    assert np.array_equal(oracle.encode_e4m3(vals), allc)
+    mags = oracle.decode_e4m3(np.arange(0, 0x7F, dtype=np.uint8))
+    assert np.all(np.diff(mags) > 0) and mags[-1] == 448.0
+
+
+def test_e4m3_encode_rounding(oracle):
+    import torch
+    enc = oracle.encode_e4m3
+    # ties to even: 1.0625 is halfway 1.0(0x38, even) / 1.125(0x39); 1.1875 halfway 0x39/0x3A
+    assert list(enc(np.array([1.0625, 1.1875, -1.0625], np.float32))) == [0x38, 0x3A, 0xB8]
+    # just off the tie
+    assert list(enc(np.array([1.0625001, 1.0624999], np.float32))) == [0x39, 0x38]
+    # saturation and subnormals
+    assert list(enc(np.array([448.0, 449.0, 1e9, -1e9, 464.0], np.float32))) == [0x7E, 0x7E, 0x7E, 0xFE, 0x7E]
+    assert list(enc(np.array([2.0 ** -9, 2.0 ** -10, 1.5 * 2.0 ** -9, 0.9 * 2.0 ** -10], np.float32))) == [0x01, 0x00, 0x02, 0x00]
+    # independent check against torch's float8_e4m3fn cast on values inside the finite range
+    rng = np.random.default_rng(15)
+    x = (rng.standard_normal(20000) * np.exp(rng.uniform(-8, 6, 20000))).astype(np.float32)
+    x = np.clip(x, -448, 448)
+    t = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(enc(x), t)
+
+
+def test_fp8_quantiser_scale_and_error_bound(oracle):
+    rng = np.random.default_rng(16)
+    X = rng.standard_normal((300, 128)).astype(np.float32)
+    X[7] = 0.0
+    codes, scale = oracle.quantize_fp8(X)
+    unit = X.astype(np.float64)
+    nrm = np.sqrt((unit ** 2).sum(1, keepdims=True))
+    unit = np.where(nrm > 0, unit / np.where(nrm > 0, nrm, 1), 0).astype(np.float32)
+    amax = np.abs(unit).max(1)
+    assert scale[7] == 1.0 and np.all(codes[7] == 0)
+    ok = amax > 0
+    assert np.array_equal(scale[ok], (amax[ok].astype(np.float64) / 448.0).astype(np.float32))
+    # the largest element of each row lands on +-448
+    top = np.abs(oracle.decode_e4m3(codes)).max(1)
+    assert np.all(top[ok] == 448.0)
+    deq = oracle.decode_e4m3(codes).astype(np.float64) * scale[:, None].astype(np.float64)
+    # relative error <= 2^-4 for normal codes, absolute 2^-10*scale below the normal range
+    err = np.abs(deq - unit)
+    bound = np.maximum(np.abs(unit) * 2.0 ** -4, scale[:, None] * 2.0 ** -10) * (1 + 1e-6)
+    assert np.all(err <= bound)
+
+
+def test_quantisation_score_error_bounds(oracle):
+    """Score error of the stored formats stays inside the stated tolerances."""
+    import workloads
+    import torch
+    cfg = workloads.C1.scaled(N=4000, Q=16)
+    wl = workloads.Workload(cfg, "cpu")
+    E = wl.rows(0, cfg.N)[0].numpy()
+    Qm = wl.queries().numpy()
+    exact = oracle.scores(E, Qm)
+    eb = oracle.decode_bf16(oracle.quantize_bf16(E))
+    qb = oracle.decode_bf16(oracle.quantize_bf16(Qm))
+    sb = oracle.scores(eb, qb, normalize=False)
+    assert np.abs(sb - exact).max() < 4e-3          # worst case 2 * 2^-9, far below 2e-2
+    c, s = oracle.quantize_fp8(E)
+    cq, sq = oracle.quantize_fp8(Qm)
+    s8 = oracle.scores(oracle.decode_e4m3(c), oracle.decode_e4m3(cq), normalize=False,
+                       row_scale=s, q_scale=sq)
+    assert np.abs(s8 - exact).max() < 6e-2 / 4      # fp8 rows and fp8 queries, margin 4x
