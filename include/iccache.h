@@ -1,0 +1,148 @@
+/*
+ * iccache.h -- C ABI of the MI355X example-selection library.
+ *
+ * The library implements stage 1 of IC-Cache's Example Selector (Sec. 4.1,
+ * "Two-Stage Scalable Example Selection"; GetSimilarExamples in Algorithm 1):
+ * a batch of request embeddings is compared with every cached example embedding
+ * by cosine similarity and the most similar examples are returned.  Two
+ * per-example inputs model what the Example Manager (Sec. 4.3) maintains: a
+ * utility value that is blended into the score, and a validity flag (evicted
+ * rows, rows outside the caller's sharing domain).
+ *
+ *   score(q, i) = cos(query_q, example_i) + lambda * utility_i
+ *   result_q    = the k valid examples with the highest score, ordered by
+ *                 (score descending, id ascending)
+ *
+ * Conventions
+ *   - Every pointer named *_dev is DEVICE memory on the GPU that was current
+ *     when the index was created; everything else is host memory.
+ *   - The caller owns every buffer it passes (arena, inputs, outputs) and keeps
+ *     it alive until the stream has drained.  The library owns only the small
+ *     host-side handle.  It never allocates or frees device memory.
+ *   - All work is enqueued on the index's stream and is asynchronous; calls on
+ *     one index are ordered.  No call synchronises the host except
+ *     ic_index_scan_time_ms.
+ *   - Example ids are append order: 0-based, dense, stable.
+ *   - Errors are returned as ic_status; nothing throws or aborts.  On error the
+ *     outputs are untouched.  Inputs must be finite.
+ */
+#ifndef ICCACHE_H
+#define ICCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ic_index ic_index; /* opaque */
+
+typedef enum {
+    IC_OK = 0,
+    IC_ERR_INVALID_ARG = 1, /* NULL where forbidden, size out of range, misaligned arena */
+    IC_ERR_OOM = 2,         /* host allocation of the handle failed                       */
+    IC_ERR_CAPACITY = 3,    /* arena too small, or append beyond capacity_rows            */
+    IC_ERR_DEVICE = 4,      /* a HIP call failed                                          */
+    IC_ERR_UNSUPPORTED = 5  /* valid request outside what the kernels cover               */
+} ic_status;
+
+/* Store formats (one per index).  Rows are unit-normalised on append. */
+typedef enum {
+    IC_STORE_BF16 = 0,     /* bfloat16, round to nearest even                              */
+    IC_STORE_FP8_E4M3 = 1  /* OCP FP8 E4M3 (max 448) with one fp32 scale per row           */
+} ic_dtype;
+
+#define IC_MAX_K 128        /* largest k accepted by ic_search                             */
+#define IC_MAX_DIM 1024     /* largest embedding dimension for bf16 (2048 for fp8)         */
+#define IC_ARENA_ALIGN 256  /* required alignment of the arena pointer, bytes              */
+
+/*
+ * Bytes of device memory an index needs: the embedding store (rows padded to a
+ * multiple of 128 B), per-row scale and utility arrays, the prepared query
+ * block, and the top-k workspace for searches of up to max_queries queries per
+ * call with k <= max_k.  Returns 0 if an argument is out of range.
+ */
+size_t ic_workspace_bytes(int32_t d, ic_dtype store, int64_t capacity_rows,
+                          int64_t max_queries, int32_t max_k);
+
+/*
+ * Create an empty index over caller-owned device memory.
+ *   out            receives the handle
+ *   d              embedding dimension, 1 .. IC_MAX_DIM (2*IC_MAX_DIM for fp8)
+ *   capacity_rows  most rows the store will ever hold (>= 1)
+ *   max_queries    largest Q a single ic_search will be given (>= 1); larger
+ *                  batches are still accepted and are processed in pieces
+ *   max_k          largest k a search will use, 1 .. IC_MAX_K
+ *   arena_dev      device memory, IC_ARENA_ALIGN-aligned, arena_bytes >=
+ *                  ic_workspace_bytes(d, store, capacity_rows, max_queries, max_k)
+ *   stream         hipStream_t (NULL = default stream) used by every later call
+ * Errors: INVALID_ARG, CAPACITY (arena too small), OOM, DEVICE.
+ */
+ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t capacity_rows,
+                          int64_t max_queries, int32_t max_k, void *arena_dev,
+                          size_t arena_bytes, void *stream);
+
+/*
+ * Append n examples (the update_cache step of the client API, Sec. 3; step 4 of
+ * the workflow).  emb_dev is [n, d] fp32 row-major; each row is divided by its
+ * Euclidean norm (a zero row stays zero) and stored in the index's format.
+ * util_dev is [n] fp32 or NULL (utility 0).  *first_id (host, may be NULL)
+ * receives the id of the first appended row.  Cost is O(n); the existing store
+ * is not touched.  Appended rows are visible to every later search.
+ * Errors: INVALID_ARG, CAPACITY (n would exceed capacity_rows), DEVICE.
+ */
+ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *util_dev,
+                          int64_t n, int64_t *first_id);
+
+/*
+ * Top-k selection for Q queries (GetSimilarExamples, Algorithm 1).
+ *   q_dev           [Q, d] fp32 row-major; rows need not be unit length
+ *   k               1 .. max_k given at creation
+ *   lambda          weight of the stored utility (0 = pure cosine)
+ *   mask_dev        [size] uint8, nonzero = valid, shared by all queries; NULL =
+ *                   all rows valid.  size is the index size at the time of call.
+ *   out_scores_dev  [Q, k] fp32; out_ids_dev [Q, k] int64.  Rows are sorted by
+ *                   (score descending, id ascending).  If fewer than k valid rows
+ *                   exist the tail is (score = -inf, id = -1).
+ * Q == 0 is a no-op.  Errors: INVALID_ARG, DEVICE.
+ */
+ic_status ic_search(const ic_index *index, const float *q_dev, int64_t Q, int32_t k,
+                    float lambda, const uint8_t *mask_dev, float *out_scores_dev,
+                    int64_t *out_ids_dev);
+
+/* Release the handle.  Device memory belongs to the caller and is not touched. */
+ic_status ic_index_destroy(ic_index *index);
+
+/* ---- helpers ---------------------------------------------------------- */
+
+/* Number of rows appended so far (-1 for a NULL handle). */
+int64_t ic_index_size(const ic_index *index);
+
+/* Replace the stream used by later calls. */
+ic_status ic_index_set_stream(ic_index *index, void *stream);
+
+/*
+ * Device views of the store for inspection: first row, row stride in bytes,
+ * per-row scale (NULL for bf16) and utility arrays.  Any out pointer may be NULL.
+ */
+ic_status ic_index_store_view(const ic_index *index, const void **rows_dev,
+                              int64_t *row_stride_bytes, const float **scale_dev,
+                              const float **util_dev);
+
+/*
+ * Kernel timing for benchmarks.  While enabled, every ic_search brackets its
+ * scan kernel (similarity + fused partial top-k) with events on the index's
+ * stream.  ic_index_scan_time_ms waits for the last search to finish and
+ * returns the scan time summed over that search's launches.
+ */
+ic_status ic_index_set_timing(ic_index *index, int enable);
+ic_status ic_index_scan_time_ms(ic_index *index, float *ms);
+
+/* Static description of a status code. */
+const char *ic_status_string(ic_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ICCACHE_H */

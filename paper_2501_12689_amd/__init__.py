@@ -1,0 +1,21 @@
+"""MI355X-native example selection for IC-Cache (stage 1 of the Example Selector).
+
+The work is done by hand-written HIP kernels behind a C ABI (``include/iccache.h``,
+built into ``libiccache.so``).  This package is the thin Python binding: it
+marshals torch tensors (device memory, streams) into that ABI and nothing else.
+There is no CPU or PyTorch fallback: if the library is missing, calls raise.
+"""
+from .binding import (  # noqa: F401
+    IC_MAX_K,
+    STORE_BF16,
+    STORE_FP8_E4M3,
+    ICError,
+    Index,
+    ic_index_append,
+    ic_index_create,
+    ic_index_destroy,
+    ic_search,
+    ic_workspace_bytes,
+    lib_path,
+    load_library,
+)

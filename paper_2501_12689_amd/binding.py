@@ -1,0 +1,205 @@
+"""ctypes binding for ``libiccache.so``: same entry points as ``include/iccache.h``.
+
+Argument marshalling only.  Tensors supply device pointers; the current torch
+stream supplies the ``hipStream_t``.  Every step of the search runs in the
+library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libiccache.so")
+
+STORE_BF16 = 0
+STORE_FP8_E4M3 = 1
+IC_MAX_K = 128
+IC_ARENA_ALIGN = 256
+
+EXPORTS = (
+    "ic_workspace_bytes", "ic_index_create", "ic_index_append", "ic_search", "ic_index_destroy",
+    "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing",
+    "ic_index_scan_time_ms", "ic_status_string",
+)
+
+_lib = None
+
+
+class ICError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().ic_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (ic_status {status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load ``libiccache.so`` (built by ``paper_2501_12689_amd.build``); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2501_12689_amd.build`; "
+            "there is no fallback path")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.ic_workspace_bytes.restype = ctypes.c_size_t
+    L.ic_workspace_bytes.argtypes = [i32, ctypes.c_int, i64, i64, i32]
+    L.ic_index_create.restype = ctypes.c_int
+    L.ic_index_create.argtypes = [ctypes.POINTER(vp), i32, ctypes.c_int, i64, i64, i32, vp,
+                                  ctypes.c_size_t, vp]
+    L.ic_index_append.restype = ctypes.c_int
+    L.ic_index_append.argtypes = [vp, vp, vp, i64, ctypes.POINTER(i64)]
+    L.ic_search.restype = ctypes.c_int
+    L.ic_search.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp]
+    L.ic_index_destroy.restype = ctypes.c_int
+    L.ic_index_destroy.argtypes = [vp]
+    L.ic_index_size.restype = i64
+    L.ic_index_size.argtypes = [vp]
+    L.ic_index_set_stream.restype = ctypes.c_int
+    L.ic_index_set_stream.argtypes = [vp, vp]
+    L.ic_index_store_view.restype = ctypes.c_int
+    L.ic_index_store_view.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                      ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    L.ic_index_set_timing.restype = ctypes.c_int
+    L.ic_index_set_timing.argtypes = [vp, ctypes.c_int]
+    L.ic_index_scan_time_ms.restype = ctypes.c_int
+    L.ic_index_scan_time_ms.argtypes = [vp, ctypes.POINTER(f32)]
+    L.ic_status_string.restype = ctypes.c_char_p
+    L.ic_status_string.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise ICError(status, where)
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+    return t.data_ptr()
+
+
+# ---- the four calls of the ABI, on raw handles --------------------------------
+
+def ic_workspace_bytes(d: int, store: int, capacity_rows: int, max_queries: int, max_k: int) -> int:
+    return int(load_library().ic_workspace_bytes(d, store, capacity_rows, max_queries, max_k))
+
+
+def ic_index_create(d: int, store: int, capacity_rows: int, max_queries: int, max_k: int,
+                    arena: torch.Tensor, stream: Optional[int] = None) -> int:
+    """Returns the opaque handle.  ``arena`` is a uint8 GPU tensor the caller keeps alive."""
+    L = load_library()
+    ptr = _dev_ptr(arena, torch.uint8, "arena")
+    if stream is None:
+        stream = torch.cuda.current_stream(arena.device).cuda_stream
+    h = ctypes.c_void_p()
+    _check(L.ic_index_create(ctypes.byref(h), d, store, capacity_rows, max_queries, max_k, ptr,
+                             arena.numel(), stream), "ic_index_create")
+    return h.value
+
+
+def ic_index_append(handle: int, emb: torch.Tensor, util: Optional[torch.Tensor] = None) -> int:
+    """Append ``emb`` [n,d] fp32 (and ``util`` [n] fp32); returns the first new id."""
+    L = load_library()
+    first = ctypes.c_int64(-1)
+    n = emb.shape[0] if emb is not None else 0
+    _check(L.ic_index_append(handle, _dev_ptr(emb, torch.float32, "emb"),
+                             _dev_ptr(util, torch.float32, "util"), n, ctypes.byref(first)),
+           "ic_index_append")
+    return first.value
+
+
+def ic_search(handle: int, queries: torch.Tensor, k: int, lam: float = 0.0,
+              mask: Optional[torch.Tensor] = None, out_scores: Optional[torch.Tensor] = None,
+              out_ids: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Top-k of ``cos + lam*utility`` over valid rows: (scores fp32 [Q,k], ids int64 [Q,k])."""
+    L = load_library()
+    Q = queries.shape[0]
+    if out_scores is None:
+        out_scores = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
+    if out_ids is None:
+        out_ids = torch.empty((Q, k), dtype=torch.int64, device=queries.device)
+    _check(L.ic_search(handle, _dev_ptr(queries, torch.float32, "queries"), Q, k, float(lam),
+                       _dev_ptr(mask, torch.uint8, "mask"),
+                       _dev_ptr(out_scores, torch.float32, "out_scores"),
+                       _dev_ptr(out_ids, torch.int64, "out_ids")), "ic_search")
+    return out_scores, out_ids
+
+
+def ic_index_destroy(handle: int) -> None:
+    _check(load_library().ic_index_destroy(handle), "ic_index_destroy")
+
+
+# ---- convenience owner of (arena, handle) -----------------------------------
+
+class Index:
+    """Owns the arena tensor and the handle; methods forward to the ABI calls."""
+
+    def __init__(self, d: int, capacity_rows: int, store: int = STORE_BF16, max_queries: int = 64,
+                 max_k: int = 64, device="cuda:0"):
+        self.d, self.store, self.capacity = d, store, capacity_rows
+        self.device = torch.device(device)
+        nbytes = ic_workspace_bytes(d, store, capacity_rows, max_queries, max_k)
+        if nbytes == 0:
+            raise ICError(1, "ic_workspace_bytes")
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        assert self.arena.data_ptr() % IC_ARENA_ALIGN == 0
+        self.handle = ic_index_create(d, store, capacity_rows, max_queries, max_k, self.arena)
+
+    def append(self, emb, util=None) -> int:
+        return ic_index_append(self.handle, emb, util)
+
+    def search(self, queries, k, lam=0.0, mask=None, out_scores=None, out_ids=None):
+        return ic_search(self.handle, queries, k, lam, mask, out_scores, out_ids)
+
+    def __len__(self) -> int:
+        return int(load_library().ic_index_size(self.handle))
+
+    def set_timing(self, enable: bool) -> None:
+        _check(load_library().ic_index_set_timing(self.handle, int(enable)), "ic_index_set_timing")
+
+    def scan_time_ms(self) -> float:
+        ms = ctypes.c_float(0)
+        _check(load_library().ic_index_scan_time_ms(self.handle, ctypes.byref(ms)),
+               "ic_index_scan_time_ms")
+        return float(ms.value)
+
+    def store_view(self):
+        """(rows uint8 [n, row_bytes], scale fp32 [n] | None, util fp32 [n]) as views of the arena."""
+        L = load_library()
+        rows, stride = ctypes.c_void_p(), ctypes.c_int64()
+        scale, util = ctypes.c_void_p(), ctypes.c_void_p()
+        _check(L.ic_index_store_view(self.handle, ctypes.byref(rows), ctypes.byref(stride),
+                                     ctypes.byref(scale), ctypes.byref(util)), "ic_index_store_view")
+        base = self.arena.data_ptr()
+        n, rb = len(self), stride.value
+        r = self.arena[rows.value - base: rows.value - base + n * rb].view(n, rb)
+        u = self.arena[util.value - base: util.value - base + 4 * n].view(torch.float32)
+        s = None
+        if scale.value:
+            s = self.arena[scale.value - base: scale.value - base + 4 * n].view(torch.float32)
+        return r, s, u
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            ic_index_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

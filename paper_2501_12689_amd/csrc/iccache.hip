@@ -1,0 +1,352 @@
+// Host side of the C ABI declared in include/iccache.h: argument checks, the
+// layout of the caller's arena, and kernel launches.  No device memory is
+// allocated here and nothing synchronises the host except the timing query.
+#include "../../include/iccache.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+#include "ic_common.h"
+#include "ic_merge.h"
+#include "ic_quantize.h"
+#include "ic_scan_stream.h"
+
+namespace {
+
+constexpr int64_t kAlign = IC_ARENA_ALIGN;
+constexpr int kMaxRowBytes = 2048;     // widest row the streaming scan holds in registers
+constexpr int kQueryChunkMax = 8192;   // queries per pass over the store
+constexpr int kSliceBudgetMax = 1024;  // most workgroups a scan launch may use
+constexpr int kSliceBudgetDefault = 512;
+constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on queries x slices
+constexpr int64_t kListSlots = kRegionSlots / 8 + kQueryChunkMax;
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+inline int region_cap(int k) {
+    int c = (int)round_up(2 * (int64_t)k, 64);
+    if (c < 64) c = 64;
+    if (c > ic::kMaxCap) c = ic::kMaxCap;
+    return c;
+}
+
+struct Layout {
+    int esize = 0, row_bytes = 0, q_chunk = 0;
+    int64_t cap_pad = 0;
+    size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
+           off_counts = 0, off_list_a = 0, off_list_b = 0, total = 0;
+};
+
+bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int32_t max_k, Layout &L) {
+    if (store != IC_STORE_BF16 && store != IC_STORE_FP8_E4M3) return false;
+    if (d < 1 || capacity < 1 || max_q < 1 || max_k < 1 || max_k > IC_MAX_K) return false;
+    if (capacity > (int64_t)1 << 31) return false;
+    L.esize = (store == IC_STORE_BF16) ? 2 : 1;
+    const int64_t rb = round_up((int64_t)d * L.esize, 128);
+    if (rb > kMaxRowBytes) return false;
+    L.row_bytes = (int)rb;
+    L.cap_pad = round_up(capacity, 16);
+    L.q_chunk = (int)std::min<int64_t>(round_up(max_q, 64), kQueryChunkMax);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = (size_t)round_up((int64_t)(off + bytes), kAlign);
+        return at;
+    };
+    L.off_rows = take((size_t)L.cap_pad * (size_t)L.row_bytes);
+    L.off_scale = take(store == IC_STORE_FP8_E4M3 ? (size_t)L.cap_pad * 4 : 0);
+    L.off_util = take((size_t)L.cap_pad * 4);
+    L.off_qbuf = take((size_t)L.q_chunk * (size_t)L.row_bytes);
+    L.off_qscale = take((size_t)L.q_chunk * 4);
+    L.off_regions = take((size_t)kRegionSlots * (size_t)region_cap(max_k) * 8);
+    L.off_counts = take((size_t)kRegionSlots * 4);
+    L.off_list_a = take((size_t)kListSlots * (size_t)max_k * 8);
+    L.off_list_b = take((size_t)kListSlots * (size_t)max_k * 8);
+    L.total = off;
+    return true;
+}
+
+using ScanFn = void (*)(dim3, hipStream_t, const ic::ScanArgs &);
+
+template <int ET, int QG, int CPW>
+void launch_scan(dim3 grid, hipStream_t st, const ic::ScanArgs &a) {
+    hipLaunchKernelGGL((ic::scan_stream<ET, QG, CPW>), grid, dim3(256), 0, st, a);
+}
+
+#define IC_SCAN_ROW(ET, QG)                                                                     \
+    {                                                                                           \
+        launch_scan<ET, QG, 1>, launch_scan<ET, QG, 2>, launch_scan<ET, QG, 3>,                  \
+            launch_scan<ET, QG, 4>, launch_scan<ET, QG, 5>, launch_scan<ET, QG, 6>,              \
+            launch_scan<ET, QG, 7>, launch_scan<ET, QG, 8>                                       \
+    }
+// [element type][query groups: 1, 2, 4][chunks per wavefront - 1]
+const ScanFn kScanTable[2][3][8] = {
+    {IC_SCAN_ROW(0, 1), IC_SCAN_ROW(0, 2), IC_SCAN_ROW(0, 4)},
+    {IC_SCAN_ROW(1, 1), IC_SCAN_ROW(1, 2), IC_SCAN_ROW(1, 4)},
+};
+#undef IC_SCAN_ROW
+
+}  // namespace
+
+struct ic_index {
+    int32_t d;
+    ic_dtype store;
+    int64_t capacity;
+    int64_t max_q;
+    int32_t max_k;
+    Layout L;
+    int64_t n;
+    hipStream_t stream;
+    int slice_budget;
+    uint8_t *rows;
+    float *scale;
+    float *util;
+    uint8_t *qbuf;
+    float *qscale;
+    uint64_t *regions;
+    int32_t *counts;
+    uint64_t *list_a;
+    uint64_t *list_b;
+    bool timing;
+    std::vector<hipEvent_t> events;  // pairs (start, stop)
+    size_t events_used;
+};
+
+extern "C" {
+
+const char *ic_status_string(ic_status s) {
+    switch (s) {
+        case IC_OK: return "ok";
+        case IC_ERR_INVALID_ARG: return "invalid argument";
+        case IC_ERR_OOM: return "out of host memory";
+        case IC_ERR_CAPACITY: return "capacity exceeded";
+        case IC_ERR_DEVICE: return "HIP call failed";
+        case IC_ERR_UNSUPPORTED: return "unsupported configuration";
+    }
+    return "unknown status";
+}
+
+size_t ic_workspace_bytes(int32_t d, ic_dtype store, int64_t capacity_rows, int64_t max_queries,
+                          int32_t max_k) {
+    Layout L;
+    if (!make_layout(d, store, capacity_rows, max_queries, max_k, L)) return 0;
+    return L.total;
+}
+
+ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t capacity_rows,
+                          int64_t max_queries, int32_t max_k, void *arena_dev, size_t arena_bytes,
+                          void *stream) {
+    if (!out || !arena_dev) return IC_ERR_INVALID_ARG;
+    if (((uintptr_t)arena_dev % kAlign) != 0) return IC_ERR_INVALID_ARG;
+    Layout L;
+    if (!make_layout(d, store, capacity_rows, max_queries, max_k, L)) return IC_ERR_INVALID_ARG;
+    if (arena_bytes < L.total) return IC_ERR_CAPACITY;
+    ic_index *ix = new (std::nothrow) ic_index();
+    if (!ix) return IC_ERR_OOM;
+    ix->d = d;
+    ix->store = store;
+    ix->capacity = capacity_rows;
+    ix->max_q = max_queries;
+    ix->max_k = max_k;
+    ix->L = L;
+    ix->n = 0;
+    ix->stream = (hipStream_t)stream;
+    ix->slice_budget = kSliceBudgetDefault;
+    if (const char *e = std::getenv("IC_SLICE_BUDGET")) {  // benchmark sweeps only
+        int v = std::atoi(e);
+        if (v >= 1 && v <= kSliceBudgetMax) ix->slice_budget = v;
+    }
+    uint8_t *base = (uint8_t *)arena_dev;
+    ix->rows = base + L.off_rows;
+    ix->scale = (store == IC_STORE_FP8_E4M3) ? (float *)(base + L.off_scale) : nullptr;
+    ix->util = (float *)(base + L.off_util);
+    ix->qbuf = base + L.off_qbuf;
+    ix->qscale = (float *)(base + L.off_qscale);
+    ix->regions = (uint64_t *)(base + L.off_regions);
+    ix->counts = (int32_t *)(base + L.off_counts);
+    ix->list_a = (uint64_t *)(base + L.off_list_a);
+    ix->list_b = (uint64_t *)(base + L.off_list_b);
+    ix->timing = false;
+    ix->events_used = 0;
+    *out = ix;
+    return IC_OK;
+}
+
+ic_status ic_index_destroy(ic_index *index) {
+    if (!index) return IC_ERR_INVALID_ARG;
+    for (hipEvent_t e : index->events) (void)hipEventDestroy(e);
+    delete index;
+    return IC_OK;
+}
+
+int64_t ic_index_size(const ic_index *index) { return index ? index->n : -1; }
+
+ic_status ic_index_set_stream(ic_index *index, void *stream) {
+    if (!index) return IC_ERR_INVALID_ARG;
+    index->stream = (hipStream_t)stream;
+    return IC_OK;
+}
+
+ic_status ic_index_store_view(const ic_index *index, const void **rows_dev, int64_t *row_stride_bytes,
+                              const float **scale_dev, const float **util_dev) {
+    if (!index) return IC_ERR_INVALID_ARG;
+    if (rows_dev) *rows_dev = index->rows;
+    if (row_stride_bytes) *row_stride_bytes = index->L.row_bytes;
+    if (scale_dev) *scale_dev = index->scale;
+    if (util_dev) *util_dev = index->util;
+    return IC_OK;
+}
+
+ic_status ic_index_set_timing(ic_index *index, int enable) {
+    if (!index) return IC_ERR_INVALID_ARG;
+    index->timing = enable != 0;
+    index->events_used = 0;
+    return IC_OK;
+}
+
+ic_status ic_index_scan_time_ms(ic_index *index, float *ms) {
+    if (!index || !ms) return IC_ERR_INVALID_ARG;
+    float total = 0.f;
+    for (size_t i = 0; i + 1 < index->events_used; i += 2) {
+        if (hipEventSynchronize(index->events[i + 1]) != hipSuccess) return IC_ERR_DEVICE;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, index->events[i], index->events[i + 1]) != hipSuccess)
+            return IC_ERR_DEVICE;
+        total += t;
+    }
+    *ms = total;
+    return IC_OK;
+}
+
+ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *util_dev, int64_t n,
+                          int64_t *first_id) {
+    if (!index || n < 0 || (n > 0 && !emb_dev)) return IC_ERR_INVALID_ARG;
+    if (index->n + n > index->capacity) return IC_ERR_CAPACITY;
+    if (first_id) *first_id = index->n;
+    if (n == 0) return IC_OK;
+    const int64_t at = index->n;
+    const int grid = (int)std::min<int64_t>((n + 3) / 4, 65536);
+    uint8_t *dst = index->rows + at * (int64_t)index->L.row_bytes;
+    float *util_dst = index->util + at;
+    if (index->store == IC_STORE_BF16) {
+        hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, index->stream, emb_dev, n, n,
+                           index->d, index->L.row_bytes, dst, (float *)nullptr, util_dev, util_dst);
+    } else {
+        hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, index->stream, emb_dev, n, n,
+                           index->d, index->L.row_bytes, dst, index->scale + at, util_dev, util_dst);
+    }
+    if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
+    index->n += n;
+    return IC_OK;
+}
+
+ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
+                    const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
+    ic_index *index = const_cast<ic_index *>(cindex);
+    if (!index || Q < 0 || k < 1 || k > index->max_k) return IC_ERR_INVALID_ARG;
+    if (Q == 0) return IC_OK;
+    if (!q_dev || !out_scores_dev || !out_ids_dev) return IC_ERR_INVALID_ARG;
+
+    const Layout &L = index->L;
+    const int et = (index->store == IC_STORE_BF16) ? 0 : 1;
+    const int nchunks = L.row_bytes / 64;
+    const int cpw = (nchunks + ic::kScanWaves - 1) / ic::kScanWaves;
+    const int cap = region_cap(k);
+    const int64_t n = index->n;
+    const int64_t ntiles = (n + 15) / 16;
+    hipStream_t st = index->stream;
+    if (index->timing) index->events_used = 0;
+
+    for (int64_t q0 = 0; q0 < Q; q0 += L.q_chunk) {
+        const int qc = (int)std::min<int64_t>(L.q_chunk, Q - q0);
+        const int qg_idx = qc <= 16 ? 0 : (qc <= 32 ? 1 : 2);
+        const int qb_rows = 16 << qg_idx;
+        const int nqb = (qc + qb_rows - 1) / qb_rows;
+        const int q_pad = nqb * qb_rows;
+
+        // a2: unit-normalise the queries and write them in the store's format
+        {
+            const int grid = (q_pad + 3) / 4;
+            const float *src = q_dev + q0 * (int64_t)index->d;
+            if (et == 0)
+                hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
+                                   (int64_t)q_pad, index->d, L.row_bytes, index->qbuf, (float *)nullptr,
+                                   (const float *)nullptr, (float *)nullptr);
+            else
+                hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
+                                   (int64_t)q_pad, index->d, L.row_bytes, index->qbuf, index->qscale,
+                                   (const float *)nullptr, (float *)nullptr);
+        }
+
+        // a3-a5: similarity, score epilogue and per-slice partial top-k
+        int S = 0;
+        if (n > 0) {
+            int64_t s = std::max<int64_t>(1, index->slice_budget / nqb);
+            S = (int)std::min<int64_t>(s, ntiles);
+            ic::ScanArgs a;
+            a.store = index->rows;
+            a.n = n;
+            a.row_bytes = L.row_bytes;
+            a.row_scale = index->scale;
+            a.util = (lambda != 0.0f) ? index->util : nullptr;
+            a.mask = mask_dev;
+            a.lambda = lambda;
+            a.qbuf = index->qbuf;
+            a.q_scale = index->qscale;
+            a.Q = qc;
+            a.k = k;
+            a.cap = cap;
+            a.S = S;
+            a.regions = index->regions;
+            a.counts = index->counts;
+            if (index->timing) {
+                while (index->events.size() < index->events_used + 2) {
+                    hipEvent_t e;
+                    if (hipEventCreate(&e) != hipSuccess) return IC_ERR_DEVICE;
+                    index->events.push_back(e);
+                }
+                (void)hipEventRecord(index->events[index->events_used], st);
+            }
+            kScanTable[et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
+            if (index->timing) {
+                (void)hipEventRecord(index->events[index->events_used + 1], st);
+                index->events_used += 2;
+            }
+        }
+
+        // a6: merge the S candidate regions of every query
+        ic::MergeArgs m;
+        m.k = k;
+        m.out_scores = out_scores_dev + q0 * (int64_t)k;
+        m.out_ids = out_ids_dev + q0 * (int64_t)k;
+        m.src = index->regions;
+        m.q_stride = (int64_t)S * cap;
+        m.seg_stride = cap;
+        m.seg_cap = cap;
+        m.seg_counts = index->counts;
+        m.nseg = S;
+        m.segs_per_wg = ic::kMergeKeys / cap;
+        uint64_t *ping = index->list_a, *pong = index->list_b;
+        for (;;) {
+            const int G = std::max(1, (m.nseg + m.segs_per_wg - 1) / m.segs_per_wg);
+            m.dst = (G == 1) ? nullptr : ping;
+            hipLaunchKernelGGL(ic::merge_lists, dim3(qc, G), dim3(256), 0, st, m);
+            if (G == 1) break;
+            m.src = ping;
+            m.q_stride = (int64_t)G * k;
+            m.seg_stride = k;
+            m.seg_cap = k;
+            m.seg_counts = nullptr;
+            m.nseg = G;
+            m.segs_per_wg = ic::kMergeKeys / k;
+            std::swap(ping, pong);
+        }
+    }
+    if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
+    return IC_OK;
+}
+
+}  // extern "C"
