@@ -131,13 +131,15 @@ ic_status ic_index_store_view(const ic_index *index, const void **rows_dev,
                               const float **util_dev);
 
 /*
- * Kernel timing for benchmarks.  While enabled, every ic_search brackets its
- * scan kernel (similarity + fused partial top-k) with events on the index's
- * stream.  ic_index_scan_time_ms waits for the last search to finish and
- * returns the scan time summed over that search's launches.
+ * Kernel timing for benchmarks.  While enabled, every ic_search brackets each
+ * launch of its scan kernel (similarity + fused partial top-k) with events on
+ * the index's stream; nothing waits.  ic_index_set_timing (either value) also
+ * forgets the launches recorded so far.  ic_index_scan_time_ms waits for the
+ * recorded launches to finish and returns their summed duration and, if
+ * launches is not NULL, their number (at most 32768 launches are kept).
  */
 ic_status ic_index_set_timing(ic_index *index, int enable);
-ic_status ic_index_scan_time_ms(ic_index *index, float *ms);
+ic_status ic_index_scan_time_ms(ic_index *index, float *ms, int64_t *launches);
 
 /* Static description of a status code. */
 const char *ic_status_string(ic_status s);

@@ -72,7 +72,7 @@ def load_library() -> ctypes.CDLL:
     L.ic_index_set_timing.restype = ctypes.c_int
     L.ic_index_set_timing.argtypes = [vp, ctypes.c_int]
     L.ic_index_scan_time_ms.restype = ctypes.c_int
-    L.ic_index_scan_time_ms.argtypes = [vp, ctypes.POINTER(f32)]
+    L.ic_index_scan_time_ms.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(i64)]
     L.ic_status_string.restype = ctypes.c_char_p
     L.ic_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -171,11 +171,12 @@ class Index:
     def set_timing(self, enable: bool) -> None:
         _check(load_library().ic_index_set_timing(self.handle, int(enable)), "ic_index_set_timing")
 
-    def scan_time_ms(self) -> float:
-        ms = ctypes.c_float(0)
-        _check(load_library().ic_index_scan_time_ms(self.handle, ctypes.byref(ms)),
+    def scan_time_ms(self) -> Tuple[float, int]:
+        """(summed scan-kernel time in ms, number of launches) since timing was switched on."""
+        ms, cnt = ctypes.c_float(0), ctypes.c_int64(0)
+        _check(load_library().ic_index_scan_time_ms(self.handle, ctypes.byref(ms), ctypes.byref(cnt)),
                "ic_index_scan_time_ms")
-        return float(ms.value)
+        return float(ms.value), int(cnt.value)
 
     def store_view(self):
         """(rows uint8 [n, row_bytes], scale fp32 [n] | None, util fp32 [n]) as views of the arena."""

@@ -21,6 +21,7 @@ constexpr int kMaxRowBytes = 2048;     // widest row the streaming scan holds in
 constexpr int kQueryChunkMax = 8192;   // queries per pass over the store
 constexpr int kSliceBudgetMax = 1024;  // most workgroups a scan launch may use
 constexpr int kSliceBudgetDefault = 512;
+constexpr size_t kMaxTimedEvents = 1 << 16;  // event pairs kept while timing is on
 constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on queries x slices
 constexpr int64_t kListSlots = kRegionSlots / 8 + kQueryChunkMax;
 
@@ -207,7 +208,7 @@ ic_status ic_index_set_timing(ic_index *index, int enable) {
     return IC_OK;
 }
 
-ic_status ic_index_scan_time_ms(ic_index *index, float *ms) {
+ic_status ic_index_scan_time_ms(ic_index *index, float *ms, int64_t *launches) {
     if (!index || !ms) return IC_ERR_INVALID_ARG;
     float total = 0.f;
     for (size_t i = 0; i + 1 < index->events_used; i += 2) {
@@ -218,6 +219,7 @@ ic_status ic_index_scan_time_ms(ic_index *index, float *ms) {
         total += t;
     }
     *ms = total;
+    if (launches) *launches = (int64_t)(index->events_used / 2);
     return IC_OK;
 }
 
@@ -258,7 +260,6 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
     const int64_t n = index->n;
     const int64_t ntiles = (n + 15) / 16;
     hipStream_t st = index->stream;
-    if (index->timing) index->events_used = 0;
 
     for (int64_t q0 = 0; q0 < Q; q0 += L.q_chunk) {
         const int qc = (int)std::min<int64_t>(L.q_chunk, Q - q0);
@@ -302,7 +303,8 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
             a.S = S;
             a.regions = index->regions;
             a.counts = index->counts;
-            if (index->timing) {
+            const bool timed = index->timing && index->events_used + 2 <= kMaxTimedEvents;
+            if (timed) {
                 while (index->events.size() < index->events_used + 2) {
                     hipEvent_t e;
                     if (hipEventCreate(&e) != hipSuccess) return IC_ERR_DEVICE;
@@ -311,7 +313,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
                 (void)hipEventRecord(index->events[index->events_used], st);
             }
             kScanTable[et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
-            if (index->timing) {
+            if (timed) {
                 (void)hipEventRecord(index->events[index->events_used + 1], st);
                 index->events_used += 2;
             }
