@@ -17,15 +17,17 @@
 //     mapping for the B operand, so every product pairs equal coordinates.
 //   * The 4 partial 16x16 score tiles are exchanged through LDS and summed in a
 //     fixed order by wavefront g < QG, which owns query group g from then on:
-//     score = dot * scales + lambda * utility, -inf for invalid rows.
-//   * Selection: each query has a candidate region of `cap` keys in global
-//     memory (private to this workgroup) and a threshold key in LDS.  A score
-//     that beats the threshold is appended; when the region is full the owning
-//     wavefront ranks its keys, keeps the best k (sorted) and raises the
-//     threshold to the k-th.  Only candidates that beat the k-th best so far are
-//     ever written, so the score matrix never leaves registers.
-//   * At the end the region sizes are written out; a merge kernel combines the
-//     S regions of every query.
+//     score = dot * scales + bias, where bias = lambda * utility, or -inf for an
+//     invalid row (make_bias prepares it once per search).
+//   * Selection: each query has a candidate region of `cap` keys and a
+//     threshold key in LDS.  A score that beats the threshold is appended; when
+//     the region is full the owning wavefront ranks its keys, keeps the best k
+//     (sorted) and raises the threshold to the k-th.  Only candidates that beat
+//     the k-th best so far are ever kept, so the score matrix never leaves
+//     registers, and the rare path touches LDS only: it never waits on the row
+//     loads that are in flight.
+//   * At the end the regions and their sizes are written out; a merge kernel
+//     combines the S regions of every query.
 #pragma once
 #include "ic_common.h"
 
@@ -33,77 +35,94 @@ namespace ic {
 
 struct ScanArgs {
     const uint8_t *store;    // [n] rows, row_bytes apart
-    int64_t n;               // rows in the index
+    int64_t n;               // rows in the index (>= 1)
     int row_bytes;           // multiple of 128
-    const float *row_scale;  // [n] (fp8) or NULL
-    const float *util;       // [>= round_up(n,4)] or NULL when lambda == 0
-    const uint8_t *mask;     // [n] or NULL
-    float lambda;
+    const float *row_scale;  // fp8: [round_up(n,16)] fp32.  bf16: unused
+    // Additive term of the score, read as bias[i * bias_stride]: lambda * utility for valid
+    // rows and -inf for invalid ones ([round_up(n,16)] fp32, stride 1, written by make_bias),
+    // or four zeros with stride 0 when the search has neither utility weight nor mask, so
+    // that the load in the main loop is unconditional.
+    const float *bias;
+    int bias_stride;
     const uint8_t *qbuf;     // prepared queries, [gridDim.y * QG*16] rows, row_bytes apart
     const float *q_scale;    // per prepared query (fp8) or NULL
     int Q;                   // real queries in qbuf
     int k;
-    int cap;                 // region capacity: multiple of 64, k < cap <= 256
+    int cap;                 // region capacity: multiple of 64, k < cap <= kMaxCap
     int S;                   // slices == gridDim.x
     uint64_t *regions;       // [Q][S][cap] keys
     int32_t *counts;         // [Q][S] keys in use
 };
 
 constexpr int kScanWaves = 4;
-constexpr int kMaxCap = 256;
+constexpr int kMaxCap = 192;
 
-// Keep the best k of a full region (sorted, best first) and publish the new
-// threshold.  Runs on one whole wavefront; `scr` is that wavefront's LDS
-// scratch of kMaxCap keys.  Keys are unique, so rank = number of greater keys
-// is a permutation.
-__device__ __forceinline__ void compact_region(uint64_t *region, int c, int k, uint64_t *scr,
-                                               uint64_t *thr_slot, uint32_t *cnt_slot, int lane) {
+// Dynamic LDS of scan_stream for a block of QG*16 queries with region capacity cap.
+__host__ __device__ constexpr size_t scan_lds_bytes(int qg, int cap) {
+    return (size_t)2 * kScanWaves * qg * 64 * 16   // partial score tiles, double buffered
+           + (size_t)qg * 16 * cap * 8             // candidate regions
+           + (size_t)qg * 16 * (8 + 4);            // threshold keys, region sizes
+}
+
+// Score bias of every row for one search: lambda * utility where the row is valid, -inf
+// where the mask excludes it and for the padding rows [n, n_pad).  util or mask may be NULL.
+__global__ __launch_bounds__(256) void make_bias(const float *__restrict__ util,
+                                                 const uint8_t *__restrict__ mask, int64_t n,
+                                                 int64_t n_pad, float lambda, float *__restrict__ bias) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t step = (int64_t)gridDim.x * 256;
+    for (; i < n_pad; i += step) {
+        float b = -INFINITY;
+        if (i < n && (!mask || mask[i] != 0)) b = util ? lambda * util[i] : 0.0f;
+        bias[i] = b;
+    }
+}
+
+// Keep the best k keys of a full region (sorted, best first) and publish the new
+// threshold.  Runs on one whole wavefront, in LDS only.  Keys are unique, so
+// rank = number of greater keys is a permutation of 0..c-1.
+__device__ __forceinline__ void compact_region(uint64_t *reg, int c, int k, uint64_t *thr_slot,
+                                               uint32_t *cnt_slot, int lane) {
     uint64_t mine[kMaxCap / 64];
+    int rank[kMaxCap / 64];
 #pragma unroll
     for (int t = 0; t < kMaxCap / 64; ++t) {
         const int idx = lane + 64 * t;
-        mine[t] = 0;
-        if (idx < c) {
-            mine[t] = __hip_atomic_load(region + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            scr[idx] = mine[t];
-        }
+        mine[t] = (idx < c) ? reg[idx] : 0ull;
+        rank[t] = 0;
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    int rank[kMaxCap / 64];
-#pragma unroll
-    for (int t = 0; t < kMaxCap / 64; ++t) rank[t] = 0;
     for (int i = 0; i < c; ++i) {
-        const uint64_t other = scr[i];
+        const uint64_t other = reg[i];
 #pragma unroll
         for (int t = 0; t < kMaxCap / 64; ++t) rank[t] += (other > mine[t]) ? 1 : 0;
     }
+    __builtin_amdgcn_wave_barrier();  // every lane has read the region before any lane rewrites it
 #pragma unroll
     for (int t = 0; t < kMaxCap / 64; ++t) {
         const int idx = lane + 64 * t;
         if (idx < c && rank[t] < k) {
-            region[rank[t]] = mine[t];
+            reg[rank[t]] = mine[t];
             if (rank[t] == k - 1) *thr_slot = mine[t];
         }
     }
     if (lane == 0) *cnt_slot = (uint32_t)(c < k ? c : k);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
 template <int ET, int QG, int CPW>
 __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     constexpr int QB = QG * 16;
-    __shared__ f32x4 part[2][kScanWaves][QG][64];
-    __shared__ uint64_t thr_key[QB];
-    __shared__ uint32_t cnt[QB];
-    __shared__ uint64_t scratch[kScanWaves][kMaxCap];
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
+    uint8_t *lds_raw = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
+    typedef f32x4 PartTile[kScanWaves][QG][64];
+    PartTile *part = reinterpret_cast<PartTile *>(lds_raw);                      // [2]
+    uint64_t *regs = reinterpret_cast<uint64_t *>(lds_raw + 2 * sizeof(PartTile));  // [QB][cap]
+    uint64_t *thr_key = regs + QB * a.cap;                                        // [QB]
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(thr_key + QB);                   // [QB]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int w = tid >> 6;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, kept scalar
     const int r16 = lane & 15;  // row within tile (A operand) / query within group (B, D)
     const int c4 = lane >> 4;   // 16-byte column within a 64-byte chunk; D rows 4*c4 .. 4*c4+3
     const int s = blockIdx.x;
@@ -116,6 +135,13 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
         cnt[tid] = 0u;
     }
 
+    // Byte offset of each chunk this wavefront owns.  When the row has fewer chunks than
+    // 4*CPW the surplus slots re-read the last chunk against a zero query fragment, which
+    // keeps the main loop free of branches.
+    int coff[CPW];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) coff[c] = (chunk0 + c < nchunks ? chunk0 + c : nchunks - 1) * 64;
+
     // query fragments owned by this wavefront, resident for the whole kernel
     i32x4 qf[QG][CPW];
 #pragma unroll
@@ -123,18 +149,18 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
         const uint8_t *qrow = a.qbuf + (int64_t)(qb * QB + g * 16 + r16) * a.row_bytes + c4 * 16;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
-            qf[g][c] = i32x4{0, 0, 0, 0};
-            if (chunk0 + c < nchunks) qf[g][c] = *reinterpret_cast<const i32x4 *>(qrow + (chunk0 + c) * 64);
+            qf[g][c] = *reinterpret_cast<const i32x4 *>(qrow + coff[c]);
+            if (chunk0 + c >= nchunks) qf[g][c] = i32x4{0, 0, 0, 0};
         }
     }
 
     // selection state of the query this lane serves in the epilogue (wave g == w)
-    const int jl = w * 16 + r16;            // query within block (meaningful when w < QG)
-    const int jq = qb * QB + jl;            // query within this launch
+    const int jl = (w < QG ? w : 0) * 16 + r16;  // query within block
+    const int jq = qb * QB + jl;                 // query within this launch
     const bool q_live = (w < QG) && (jq < a.Q);
     float q_scale = 1.0f;
     if (ET == 1 && q_live) q_scale = a.q_scale[jq];
-    uint64_t *region = a.regions + ((int64_t)(q_live ? jq : 0) * a.S + s) * a.cap;
+    uint64_t *region = regs + jl * a.cap;
     float thr_s = -INFINITY;
     uint64_t thr_k = kKeyFloor;
 
@@ -142,67 +168,62 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
 
     const int64_t ntiles = (a.n + 15) >> 4;
     const int64_t last_row = a.n - 1;
-    const uint8_t *lane_base = a.store + chunk0 * 64 + c4 * 16;
+    const int64_t S = a.S;
 
-    i32x4 rows[3][CPW];
-    auto load_tile = [&](int64_t t, i32x4 *dst) {
-        int64_t r = t * 16 + r16;
+    // Everything a tile needs from global memory, requested two tiles ahead.  The loads
+    // are unconditional (indices are clamped), so the only waits in the loop are counted
+    // waits for the oldest stage.
+    struct Stage {
+        i32x4 rows[CPW];
+        f32x4 bias;
+        f32x4 rsc;
+    };
+    Stage st[3];
+    auto load_stage = [&](int64_t t, Stage &x) {
+        const int64_t tt = t < ntiles ? t : ntiles - 1;
+        int64_t r = tt * 16 + r16;
         if (r > last_row) r = last_row;  // ragged tail: re-read a valid row, masked out later
-        const uint8_t *p = lane_base + r * (int64_t)a.row_bytes;
+        const uint8_t *p = a.store + r * (int64_t)a.row_bytes + c4 * 16;
 #pragma unroll
-        for (int c = 0; c < CPW; ++c)
-            if (chunk0 + c < nchunks) dst[c] = *reinterpret_cast<const i32x4 *>(p + c * 64);
+        for (int c = 0; c < CPW; ++c) x.rows[c] = *reinterpret_cast<const i32x4 *>(p + coff[c]);
+        const int64_t i0 = tt * 16 + c4 * 4;
+        x.bias = *reinterpret_cast<const f32x4 *>(a.bias + i0 * a.bias_stride);
+        if (ET == 1) x.rsc = *reinterpret_cast<const f32x4 *>(a.row_scale + i0);
     };
 
+    // The loop body is unrolled by three so that the stage buffers are addressed statically.
+    // Tiles past the end of the slice (when its tile count is not a multiple of three) are
+    // processed like any other: their loads are clamped and all their rows fall past
+    // last_row, so they contribute no candidate.
     int64_t t = s;
-    if (t < ntiles) load_tile(t, rows[0]);
-    if (t + a.S < ntiles) load_tile(t + a.S, rows[1]);
+    load_stage(t, st[0]);
+    load_stage(t + S, st[1]);
     int pb = 0;
+    const int64_t my_tiles = (s < ntiles) ? (ntiles - s + S - 1) / S : 0;
 
-    while (t < ntiles) {
+    for (int64_t it = 0; it < my_tiles; it += 3) {
 #pragma unroll
         for (int b = 0; b < 3; ++b) {
-            if (t < ntiles) {
-                if (t + 2 * (int64_t)a.S < ntiles) load_tile(t + 2 * (int64_t)a.S, rows[(b + 2) % 3]);
-
-                // epilogue inputs for this tile, requested early
-                const int64_t i0 = t * 16 + c4 * 4;
-                f32x4 bias = {0.f, 0.f, 0.f, 0.f};
-                f32x4 rsc = {1.f, 1.f, 1.f, 1.f};
-                uint32_t valid = 0;
-                if (w < QG) {
-                    if (a.util) {
-                        const f32x4 u = *reinterpret_cast<const f32x4 *>(a.util + i0);
-                        bias = u * a.lambda;
-                    }
-                    if (ET == 1) rsc = *reinterpret_cast<const f32x4 *>(a.row_scale + i0);
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int64_t i = i0 + v;
-                        bool ok = i < a.n;
-                        if (ok && a.mask) ok = a.mask[i] != 0;
-                        valid |= (ok ? 1u : 0u) << v;
-                    }
-                }
+            {
+                load_stage(t + 2 * S, st[(b + 2) % 3]);
+                const Stage &cur = st[b];
 
                 f32x4 acc[QG];
 #pragma unroll
                 for (int g = 0; g < QG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int c = 0; c < CPW; ++c) {
-                    if (chunk0 + c < nchunks) {
 #pragma unroll
-                        for (int g = 0; g < QG; ++g) {
-                            if (ET == 0) {
-                                acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8, rows[b][c]),
-                                    __builtin_bit_cast(bf16x8, qf[g][c]), acc[g], 0, 0, 0);
-                            } else {
-                                const i64x2 ra = __builtin_bit_cast(i64x2, rows[b][c]);
-                                const i64x2 qa = __builtin_bit_cast(i64x2, qf[g][c]);
-                                acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ra.x, qa.x, acc[g], 0, 0, 0);
-                                acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ra.y, qa.y, acc[g], 0, 0, 0);
-                            }
+                    for (int g = 0; g < QG; ++g) {
+                        if (ET == 0) {
+                            acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8, cur.rows[c]), __builtin_bit_cast(bf16x8, qf[g][c]),
+                                acc[g], 0, 0, 0);
+                        } else {
+                            const i64x2 ra = __builtin_bit_cast(i64x2, cur.rows[c]);
+                            const i64x2 qa = __builtin_bit_cast(i64x2, qf[g][c]);
+                            acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ra.x, qa.x, acc[g], 0, 0, 0);
+                            acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ra.y, qa.y, acc[g], 0, 0, 0);
                         }
                     }
                 }
@@ -216,19 +237,23 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                     sum += part[pb][2][w][lane];
                     sum += part[pb][3][w][lane];
 
+                    const int64_t i0 = t * 16 + c4 * 4;
                     uint64_t key[4];
                     uint32_t pend = 0;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        float sc = (ET == 1) ? sum[v] * (rsc[v] * q_scale) + bias[v] : sum[v] + bias[v];
-                        if (!((valid >> v) & 1u)) sc = -INFINITY;
+                        float sc = (ET == 1) ? sum[v] * (cur.rsc[v] * q_scale) + cur.bias[v]
+                                             : sum[v] + cur.bias[v];
+                        if (i0 + v > last_row) sc = -INFINITY;
                         key[v] = 0;
                         if (q_live && sc >= thr_s) {
                             key[v] = make_key(sc, (uint32_t)(i0 + v));
                             if (key[v] > thr_k) pend |= 1u << v;
                         }
                     }
-                    // rare path: at least one lane of this wavefront has a candidate
+                    // rare path: at least one lane of this wavefront has a candidate.
+                    // LDS operations of one wavefront execute in issue order, so the
+                    // region sizes read below include every append made above.
                     while (__ballot(pend != 0) != 0ull) {
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
@@ -240,23 +265,19 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                                 }
                             }
                         }
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                         __builtin_amdgcn_wave_barrier();
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                        const bool full = q_live && cnt[jl] >= (uint32_t)a.cap;
+                        const uint32_t have =
+                            __hip_atomic_load(&cnt[jl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                        const bool full = q_live && have >= (uint32_t)a.cap;
                         const uint32_t fullmask = (uint32_t)(__ballot(full) & 0xFFFFull);
                         if (fullmask) {
-                            __threadfence();  // appended keys reach L2 before they are read back
                             for (int j = 0; j < 16; ++j) {
                                 if ((fullmask >> j) & 1u) {
-                                    const int qq = qb * QB + w * 16 + j;
-                                    uint64_t *reg = a.regions + ((int64_t)qq * a.S + s) * a.cap;
-                                    compact_region(reg, a.cap, a.k, scratch[w], &thr_key[w * 16 + j],
-                                                   &cnt[w * 16 + j], lane);
+                                    const int ql = w * 16 + j;
+                                    compact_region(regs + ql * a.cap, a.cap, a.k, &thr_key[ql], &cnt[ql], lane);
                                 }
                             }
-                            __threadfence();
-                            thr_k = thr_key[jl];
+                            thr_k = __hip_atomic_load(&thr_key[jl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
                             thr_s = key_score(thr_k);
 #pragma unroll
                             for (int v = 0; v < 4; ++v)
@@ -265,14 +286,23 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                     }
                 }
                 pb ^= 1;
-                t += a.S;
+                t += S;
             }
         }
     }
 
-    if (q_live && c4 == 0) {
-        const uint32_t c = cnt[jl];
-        a.counts[(int64_t)jq * a.S + s] = (int32_t)(c < (uint32_t)a.cap ? c : (uint32_t)a.cap);
+    // hand the regions to the merge kernel
+    if (w < QG) {
+        for (int j = 0; j < 16; ++j) {
+            const int ql = w * 16 + j;
+            const int qq = qb * QB + ql;
+            if (qq >= a.Q) break;
+            uint32_t c = __hip_atomic_load(&cnt[ql], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            if (c > (uint32_t)a.cap) c = (uint32_t)a.cap;
+            uint64_t *out = a.regions + ((int64_t)qq * a.S + s) * a.cap;
+            for (int idx = lane; idx < (int)c; idx += 64) out[idx] = regs[ql * a.cap + idx];
+            if (lane == 0) a.counts[(int64_t)qq * a.S + s] = (int32_t)c;
+        }
     }
 }
 

@@ -20,25 +20,22 @@ constexpr int64_t kAlign = IC_ARENA_ALIGN;
 constexpr int kMaxRowBytes = 2048;     // widest row the streaming scan holds in registers
 constexpr int kQueryChunkMax = 8192;   // queries per pass over the store
 constexpr int kSliceBudgetMax = 1024;  // most workgroups a scan launch may use
-constexpr int kSliceBudgetDefault = 512;
+constexpr int kComputeUnitsDefault = 256;   // MI355X
+constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxTimedEvents = 1 << 16;  // event pairs kept while timing is on
 constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on queries x slices
 constexpr int64_t kListSlots = kRegionSlots / 8 + kQueryChunkMax;
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-inline int region_cap(int k) {
-    int c = (int)round_up(2 * (int64_t)k, 64);
-    if (c < 64) c = 64;
-    if (c > ic::kMaxCap) c = ic::kMaxCap;
-    return c;
-}
+// Candidates a scan workgroup keeps per query between compactions.
+inline int region_cap(int k) { return k <= 32 ? 64 : (k <= 64 ? 128 : ic::kMaxCap); }
 
 struct Layout {
     int esize = 0, row_bytes = 0, q_chunk = 0;
     int64_t cap_pad = 0;
     size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
-           off_counts = 0, off_list_a = 0, off_list_b = 0, total = 0;
+           off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, total = 0;
 };
 
 bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int32_t max_k, Layout &L) {
@@ -66,15 +63,27 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_counts = take((size_t)kRegionSlots * 4);
     L.off_list_a = take((size_t)kListSlots * (size_t)max_k * 8);
     L.off_list_b = take((size_t)kListSlots * (size_t)max_k * 8);
+    L.off_consts = take(64);
+    L.off_bias = take((size_t)L.cap_pad * 4);
     L.total = off;
     return true;
+}
+
+// 64 zero bytes: the score bias of a search that has neither utility weight nor mask.
+__global__ void init_consts(uint32_t *c) {
+    if (threadIdx.x < 16) c[threadIdx.x] = 0u;
 }
 
 using ScanFn = void (*)(dim3, hipStream_t, const ic::ScanArgs &);
 
 template <int ET, int QG, int CPW>
 void launch_scan(dim3 grid, hipStream_t st, const ic::ScanArgs &a) {
-    hipLaunchKernelGGL((ic::scan_stream<ET, QG, CPW>), grid, dim3(256), 0, st, a);
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    static const hipError_t allowed = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(&ic::scan_stream<ET, QG, CPW>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::scan_lds_bytes(QG, ic::kMaxCap));
+    (void)allowed;
+    hipLaunchKernelGGL((ic::scan_stream<ET, QG, CPW>), grid, dim3(256), ic::scan_lds_bytes(QG, a.cap), st, a);
 }
 
 #define IC_SCAN_ROW(ET, QG)                                                                     \
@@ -101,7 +110,8 @@ struct ic_index {
     Layout L;
     int64_t n;
     hipStream_t stream;
-    int slice_budget;
+    int slice_budget;  // 0 = derive from occupancy; otherwise forced (benchmark sweeps)
+    int compute_units;
     uint8_t *rows;
     float *scale;
     float *util;
@@ -111,6 +121,9 @@ struct ic_index {
     int32_t *counts;
     uint64_t *list_a;
     uint64_t *list_b;
+    uint8_t *consts;
+    float *bias;
+    bool consts_ready;  // written by the first search (creation launches nothing)
     bool timing;
     std::vector<hipEvent_t> events;  // pairs (start, stop)
     size_t events_used;
@@ -155,11 +168,17 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->L = L;
     ix->n = 0;
     ix->stream = (hipStream_t)stream;
-    ix->slice_budget = kSliceBudgetDefault;
+    ix->slice_budget = 0;
     if (const char *e = std::getenv("IC_SLICE_BUDGET")) {  // benchmark sweeps only
         int v = std::atoi(e);
         if (v >= 1 && v <= kSliceBudgetMax) ix->slice_budget = v;
     }
+    ix->compute_units = kComputeUnitsDefault;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        ix->compute_units = cus;
+    (void)hipGetLastError();
     uint8_t *base = (uint8_t *)arena_dev;
     ix->rows = base + L.off_rows;
     ix->scale = (store == IC_STORE_FP8_E4M3) ? (float *)(base + L.off_scale) : nullptr;
@@ -170,8 +189,11 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->counts = (int32_t *)(base + L.off_counts);
     ix->list_a = (uint64_t *)(base + L.off_list_a);
     ix->list_b = (uint64_t *)(base + L.off_list_b);
+    ix->consts = base + L.off_consts;
+    ix->bias = (float *)(base + L.off_bias);
     ix->timing = false;
     ix->events_used = 0;
+    ix->consts_ready = false;
     *out = ix;
     return IC_OK;
 }
@@ -261,6 +283,21 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
     const int64_t ntiles = (n + 15) / 16;
     hipStream_t st = index->stream;
 
+    if (!index->consts_ready) {
+        hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)index->consts);
+        index->consts_ready = true;
+    }
+
+    // a4 (first half): per-row additive term, once per search
+    const bool use_bias = (lambda != 0.0f) || mask_dev != nullptr;
+    if (use_bias && n > 0) {
+        const int64_t n_pad = round_up(n, 16);
+        const int grid = (int)std::min<int64_t>((n_pad + 255) / 256, 4096);
+        hipLaunchKernelGGL(ic::make_bias, dim3(grid), dim3(256), 0, st,
+                           (lambda != 0.0f) ? (const float *)index->util : (const float *)nullptr, mask_dev,
+                           n, n_pad, lambda, index->bias);
+    }
+
     for (int64_t q0 = 0; q0 < Q; q0 += L.q_chunk) {
         const int qc = (int)std::min<int64_t>(L.q_chunk, Q - q0);
         const int qg_idx = qc <= 16 ? 0 : (qc <= 32 ? 1 : 2);
@@ -285,16 +322,23 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
         // a3-a5: similarity, score epilogue and per-slice partial top-k
         int S = 0;
         if (n > 0) {
-            int64_t s = std::max<int64_t>(1, index->slice_budget / nqb);
+            // one workgroup per slice and query block; by default as many as are resident at once
+            // (two per compute unit by registers, fewer when the candidate regions fill the LDS)
+            int budget = index->slice_budget;
+            if (budget == 0) {
+                const size_t lds = ic::scan_lds_bytes(1 << qg_idx, cap);
+                const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
+                budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
+            }
+            int64_t s = std::max<int64_t>(1, budget / nqb);
             S = (int)std::min<int64_t>(s, ntiles);
             ic::ScanArgs a;
             a.store = index->rows;
             a.n = n;
             a.row_bytes = L.row_bytes;
             a.row_scale = index->scale;
-            a.util = (lambda != 0.0f) ? index->util : nullptr;
-            a.mask = mask_dev;
-            a.lambda = lambda;
+            a.bias = use_bias ? index->bias : (const float *)index->consts;
+            a.bias_stride = use_bias ? 1 : 0;
             a.qbuf = index->qbuf;
             a.q_scale = index->qscale;
             a.Q = qc;

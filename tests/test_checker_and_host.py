@@ -94,13 +94,13 @@ def test_workspace_bytes_arithmetic():
     w = pkg.ic_workspace_bytes
     base = w(768, pkg.STORE_BF16, 1_000_000, 64, 64)
     more = w(768, pkg.STORE_BF16, 2_000_000, 64, 64)
-    # one more million rows: 1536 B row + 4 B utility each (up to alignment)
-    assert abs((more - base) - 1_000_000 * (1536 + 4)) <= 1024
+    # one more million rows: 1536 B row + 4 B utility + 4 B score bias each (up to alignment)
+    assert abs((more - base) - 1_000_000 * (1536 + 4 + 4)) <= 1024
     f8 = w(1024, pkg.STORE_FP8_E4M3, 2_000_000, 64, 64) - w(1024, pkg.STORE_FP8_E4M3, 1_000_000, 64, 64)
-    assert abs(f8 - 1_000_000 * (1024 + 4 + 4)) <= 1024
+    assert abs(f8 - 1_000_000 * (1024 + 4 + 4 + 4)) <= 1024      # + per-row scale
     # rows pad to 128 B: d = 100 bf16 -> 256 B
     a = w(100, pkg.STORE_BF16, 1 << 20, 64, 64) - w(100, pkg.STORE_BF16, 1 << 19, 64, 64)
-    assert abs(a - (1 << 19) * (256 + 4)) <= 1024
+    assert abs(a - (1 << 19) * (256 + 4 + 4)) <= 1024
     for bad in [(0, 0, 10, 1, 1), (1025, 0, 10, 1, 1), (2049, 1, 10, 1, 1), (64, 2, 10, 1, 1),
                 (64, 0, 0, 1, 1), (64, 0, 10, 0, 1), (64, 0, 10, 1, 0), (64, 0, 10, 1, 129)]:
         assert w(*bad) == 0, bad
