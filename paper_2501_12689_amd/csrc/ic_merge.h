@@ -23,8 +23,9 @@ struct MergeArgs {
     int segs_per_wg;           // segs_per_wg * seg_cap <= kMergeKeys
     int k;
     uint64_t *dst;             // non-final: lists [Q][gridDim.y][k]
-    float *out_scores;         // final: [Q][k]
-    int64_t *out_ids;          // final: [Q][k]
+    float *out_scores;         // final: [Q][k], or NULL
+    int64_t *out_ids;          // final: [Q][k], or NULL
+    uint64_t *kth_out;         // final: [Q] key of the k-th best (0 if there are fewer), or NULL
 };
 
 __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
@@ -80,12 +81,13 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
         const uint64_t key = buf[r];
         if (a.dst) {
             a.dst[((int64_t)q * gridDim.y + g) * a.k + r] = key;
-        } else {
+        } else if (a.out_scores) {
             const bool none = key <= kKeyFloor;
             a.out_scores[(int64_t)q * a.k + r] = none ? -INFINITY : key_score(key);
             a.out_ids[(int64_t)q * a.k + r] = none ? (int64_t)-1 : (int64_t)key_id(key);
         }
     }
+    if (!a.dst && a.kth_out && tid == 0) a.kth_out[q] = buf[a.k - 1];
 }
 
 }  // namespace ic

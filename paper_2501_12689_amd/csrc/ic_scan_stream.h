@@ -15,8 +15,8 @@
 //     r at chunk offset 16*c, which is exactly the A-operand layout of
 //     v_mfma_f32_16x16x32 (row r, 8 consecutive k).  Queries use the same byte
 //     mapping for the B operand, so every product pairs equal coordinates.
-//   * The 4 partial 16x16 score tiles are exchanged through LDS and summed in a
-//     fixed order by wavefront g < QG, which owns query group g from then on:
+//   * The 4 partial 16x16 score tiles are exchanged through LDS (one buffer,
+//     two barriers per tile) and summed in a fixed order by wavefront g < QG, which owns query group g from then on:
 //     score = dot * scales + bias, where bias = lambda * utility, or -inf for an
 //     invalid row (make_bias prepares it once per search).
 //   * Selection: each query has a candidate region of `cap` keys and a
@@ -28,6 +28,11 @@
 //     loads that are in flight.
 //   * At the end the regions and their sizes are written out; a merge kernel
 //     combines the S regions of every query.
+//   * Pilot variant (PILOT = true).  The same kernel run over every tile_mul-th tile keeps,
+//     per query, only the best score of its slice.  With S >= k slices the k-th
+//     largest of those S maxima is a score that at least k rows reach, i.e. a
+//     valid starting threshold for the full scan, which then appends only the few
+//     rows that beat it instead of warming its thresholds up slice by slice.
 #pragma once
 #include "ic_common.h"
 
@@ -48,10 +53,13 @@ struct ScanArgs {
     const float *q_scale;    // per prepared query (fp8) or NULL
     int Q;                   // real queries in qbuf
     int k;
-    int cap;                 // region capacity: multiple of 64, k < cap <= kMaxCap
+    int cap;                 // region capacity: multiple of 16, k < cap <= kMaxCap
     int S;                   // slices == gridDim.x
     uint64_t *regions;       // [Q][S][cap] keys
     int32_t *counts;         // [Q][S] keys in use
+    int tile_mul;            // the kernel visits tiles 0, tile_mul, 2*tile_mul, ... (1 = all)
+    uint64_t *pilot_out;     // PILOT kernels: [Q][S] keys (best score of the slice, id = slice)
+    const uint64_t *thr_init;  // full scan: per query, key of a score that >= k rows reach, or NULL
 };
 
 constexpr int kScanWaves = 4;
@@ -59,9 +67,9 @@ constexpr int kMaxCap = 192;
 
 // Dynamic LDS of scan_stream for a block of QG*16 queries with region capacity cap.
 __host__ __device__ constexpr size_t scan_lds_bytes(int qg, int cap) {
-    return (size_t)2 * kScanWaves * qg * 64 * 16   // partial score tiles, double buffered
-           + (size_t)qg * 16 * cap * 8             // candidate regions
-           + (size_t)qg * 16 * (8 + 4);            // threshold keys, region sizes
+    return (size_t)kScanWaves * qg * 64 * 16   // partial score tiles
+           + (size_t)qg * 16 * cap * 8         // candidate regions
+           + (size_t)qg * 16 * (8 + 4);        // threshold keys, region sizes
 }
 
 // Score bias of every row for one search: lambda * utility where the row is valid, -inf
@@ -78,27 +86,34 @@ __global__ __launch_bounds__(256) void make_bias(const float *__restrict__ util,
     }
 }
 
-// Keep the best k keys of a full region (sorted, best first) and publish the new
-// threshold.  Runs on one whole wavefront, in LDS only.  Keys are unique, so
-// rank = number of greater keys is a permutation of 0..c-1.
+// Keep the best k keys of a full region of c keys (c a multiple of 4, at most 64*NT; the
+// survivors end up sorted, best first) and publish the k-th as the new threshold.  Runs on
+// one whole wavefront, in LDS only.  Keys are unique, so rank = number of greater keys is a
+// permutation of 0..c-1.
+template <int NT>
 __device__ __forceinline__ void compact_region(uint64_t *reg, int c, int k, uint64_t *thr_slot,
                                                uint32_t *cnt_slot, int lane) {
-    uint64_t mine[kMaxCap / 64];
-    int rank[kMaxCap / 64];
+    typedef __attribute__((ext_vector_type(2))) uint64_t u64x2;
+    uint64_t mine[NT];
+    int rank[NT];
 #pragma unroll
-    for (int t = 0; t < kMaxCap / 64; ++t) {
+    for (int t = 0; t < NT; ++t) {
         const int idx = lane + 64 * t;
         mine[t] = (idx < c) ? reg[idx] : 0ull;
         rank[t] = 0;
     }
-    for (int i = 0; i < c; ++i) {
-        const uint64_t other = reg[i];
+#pragma unroll 2
+    for (int i = 0; i < c; i += 4) {
+        const u64x2 o01 = *reinterpret_cast<const u64x2 *>(reg + i);
+        const u64x2 o23 = *reinterpret_cast<const u64x2 *>(reg + i + 2);
 #pragma unroll
-        for (int t = 0; t < kMaxCap / 64; ++t) rank[t] += (other > mine[t]) ? 1 : 0;
+        for (int t = 0; t < NT; ++t)
+            rank[t] += (int)(o01.x > mine[t]) + (int)(o01.y > mine[t]) + (int)(o23.x > mine[t]) +
+                       (int)(o23.y > mine[t]);
     }
     __builtin_amdgcn_wave_barrier();  // every lane has read the region before any lane rewrites it
 #pragma unroll
-    for (int t = 0; t < kMaxCap / 64; ++t) {
+    for (int t = 0; t < NT; ++t) {
         const int idx = lane + 64 * t;
         if (idx < c && rank[t] < k) {
             reg[rank[t]] = mine[t];
@@ -109,14 +124,14 @@ __device__ __forceinline__ void compact_region(uint64_t *reg, int c, int k, uint
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int ET, int QG, int CPW>
+template <int ET, int QG, int CPW, bool PILOT>
 __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     constexpr int QB = QG * 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds_raw = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
     typedef f32x4 PartTile[kScanWaves][QG][64];
-    PartTile *part = reinterpret_cast<PartTile *>(lds_raw);                      // [2]
-    uint64_t *regs = reinterpret_cast<uint64_t *>(lds_raw + 2 * sizeof(PartTile));  // [QB][cap]
+    PartTile &part = *reinterpret_cast<PartTile *>(lds_raw);
+    uint64_t *regs = reinterpret_cast<uint64_t *>(lds_raw + sizeof(PartTile));  // [QB][cap]
     uint64_t *thr_key = regs + QB * a.cap;                                        // [QB]
     uint32_t *cnt = reinterpret_cast<uint32_t *>(thr_key + QB);                   // [QB]
 
@@ -130,8 +145,15 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     const int nchunks = a.row_bytes >> 6;
     const int chunk0 = w * CPW;
 
-    if (tid < QB) {
-        thr_key[tid] = kKeyFloor;
+    // Starting threshold of a query: nothing, or "any row whose score reaches the pilot's
+    // score" (the key just below the smallest key with that score).
+    auto start_threshold = [&](int q) -> uint64_t {
+        if (!a.thr_init || q >= a.Q) return kKeyFloor;
+        const uint64_t t0 = a.thr_init[q];
+        return t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
+    };
+    if (tid < QB && !PILOT) {
+        thr_key[tid] = start_threshold(qb * QB + tid);
         cnt[tid] = 0u;
     }
 
@@ -161,12 +183,14 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     float q_scale = 1.0f;
     if (ET == 1 && q_live) q_scale = a.q_scale[jq];
     uint64_t *region = regs + jl * a.cap;
-    float thr_s = -INFINITY;
-    uint64_t thr_k = kKeyFloor;
+    uint64_t thr_k = q_live ? start_threshold(jq) : kKeyFloor;
+    float thr_s = thr_k > kKeyFloor ? key_score(thr_k + 1ull) : -INFINITY;
+    float best = -INFINITY;  // pilot mode: best score of this lane's rows
 
     __syncthreads();
 
-    const int64_t ntiles = (a.n + 15) >> 4;
+    const int64_t tile_mul = a.tile_mul;
+    const int64_t ntiles = (((a.n + 15) >> 4) + tile_mul - 1) / tile_mul;  // tiles this launch visits
     const int64_t last_row = a.n - 1;
     const int64_t S = a.S;
 
@@ -180,7 +204,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     };
     Stage st[3];
     auto load_stage = [&](int64_t t, Stage &x) {
-        const int64_t tt = t < ntiles ? t : ntiles - 1;
+        const int64_t tt = (t < ntiles ? t : ntiles - 1) * tile_mul;
         int64_t r = tt * 16 + r16;
         if (r > last_row) r = last_row;  // ragged tail: re-read a valid row, masked out later
         const uint8_t *p = a.store + r * (int64_t)a.row_bytes + c4 * 16;
@@ -198,7 +222,6 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     int64_t t = s;
     load_stage(t, st[0]);
     load_stage(t + S, st[1]);
-    int pb = 0;
     const int64_t my_tiles = (s < ntiles) ? (ntiles - s + S - 1) / S : 0;
 
     for (int64_t it = 0; it < my_tiles; it += 3) {
@@ -228,16 +251,19 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                     }
                 }
 #pragma unroll
-                for (int g = 0; g < QG; ++g) part[pb][w][g][lane] = acc[g];
+                for (int g = 0; g < QG; ++g) part[w][g][lane] = acc[g];
                 __syncthreads();
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+                if (w < QG) {
+                    sum = part[0][w][lane];
+                    sum += part[1][w][lane];
+                    sum += part[2][w][lane];
+                    sum += part[3][w][lane];
+                }
+                __syncthreads();  // the partial tiles may be overwritten from here on
 
                 if (w < QG) {
-                    f32x4 sum = part[pb][0][w][lane];
-                    sum += part[pb][1][w][lane];
-                    sum += part[pb][2][w][lane];
-                    sum += part[pb][3][w][lane];
-
-                    const int64_t i0 = t * 16 + c4 * 4;
+                    const int64_t i0 = t * tile_mul * 16 + c4 * 4;
                     uint64_t key[4];
                     uint32_t pend = 0;
 #pragma unroll
@@ -245,52 +271,64 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                         float sc = (ET == 1) ? sum[v] * (cur.rsc[v] * q_scale) + cur.bias[v]
                                              : sum[v] + cur.bias[v];
                         if (i0 + v > last_row) sc = -INFINITY;
+                        if (PILOT) {
+                            best = fmaxf(best, sc);
+                            continue;
+                        }
                         key[v] = 0;
                         if (q_live && sc >= thr_s) {
                             key[v] = make_key(sc, (uint32_t)(i0 + v));
                             if (key[v] > thr_k) pend |= 1u << v;
                         }
                     }
-                    // rare path: at least one lane of this wavefront has a candidate.
-                    // LDS operations of one wavefront execute in issue order, so the
-                    // region sizes read below include every append made above.
+                    // Rare path: at least one lane of this wavefront has a candidate.  A lane
+                    // claims as many slots of its query's region as it has candidates with one
+                    // LDS atomic and fills the ones that exist; what does not fit stays pending
+                    // until the region has been compacted.
                     while (__ballot(pend != 0) != 0ull) {
+                        if (pend) {
+                            uint32_t slot = atomicAdd(&cnt[jl], (uint32_t)__popc(pend));
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            if ((pend >> v) & 1u) {
-                                const uint32_t pos = atomicAdd(&cnt[jl], 1u);
-                                if (pos < (uint32_t)a.cap) {
-                                    region[pos] = key[v];
+                            for (int v = 0; v < 4; ++v) {
+                                if (((pend >> v) & 1u) && slot < (uint32_t)a.cap) {
+                                    region[slot++] = key[v];
                                     pend &= ~(1u << v);
                                 }
                             }
                         }
+                        uint64_t over = __ballot(pend != 0);
+                        if (over == 0ull) break;
+                        // queries whose region overflowed: full by construction, compact them
+                        const uint32_t fullmask = (uint32_t)((over | (over >> 16) | (over >> 32) | (over >> 48)) & 0xFFFFull);
                         __builtin_amdgcn_wave_barrier();
-                        const uint32_t have =
-                            __hip_atomic_load(&cnt[jl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                        const bool full = q_live && have >= (uint32_t)a.cap;
-                        const uint32_t fullmask = (uint32_t)(__ballot(full) & 0xFFFFull);
-                        if (fullmask) {
-                            for (int j = 0; j < 16; ++j) {
-                                if ((fullmask >> j) & 1u) {
-                                    const int ql = w * 16 + j;
-                                    compact_region(regs + ql * a.cap, a.cap, a.k, &thr_key[ql], &cnt[ql], lane);
-                                }
+                        for (int j = 0; j < 16; ++j) {
+                            if ((fullmask >> j) & 1u) {
+                                const int ql = w * 16 + j;
+                                uint64_t *reg = regs + ql * a.cap;
+                                if (a.cap <= 64) compact_region<1>(reg, a.cap, a.k, &thr_key[ql], &cnt[ql], lane);
+                                else if (a.cap <= 128) compact_region<2>(reg, a.cap, a.k, &thr_key[ql], &cnt[ql], lane);
+                                else compact_region<3>(reg, a.cap, a.k, &thr_key[ql], &cnt[ql], lane);
                             }
-                            thr_k = __hip_atomic_load(&thr_key[jl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                            thr_s = key_score(thr_k);
-#pragma unroll
-                            for (int v = 0; v < 4; ++v)
-                                if (((pend >> v) & 1u) && !(key[v] > thr_k)) pend &= ~(1u << v);
                         }
+                        thr_k = __hip_atomic_load(&thr_key[jl], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                        thr_s = key_score(thr_k);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (((pend >> v) & 1u) && !(key[v] > thr_k)) pend &= ~(1u << v);
                     }
                 }
-                pb ^= 1;
                 t += S;
             }
         }
     }
 
+    if (PILOT) {
+        // best score of the slice per query: combine the four lanes that share a query
+        best = fmaxf(best, __shfl_xor(best, 16, kWave));
+        best = fmaxf(best, __shfl_xor(best, 32, kWave));
+        if (q_live && c4 == 0) a.pilot_out[(int64_t)jq * a.S + s] = make_key(best, (uint32_t)s);
+        return;
+    }
     // hand the regions to the merge kernel
     if (w < QG) {
         for (int j = 0; j < 16; ++j) {

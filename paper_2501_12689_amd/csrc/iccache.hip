@@ -20,6 +20,9 @@ constexpr int64_t kAlign = IC_ARENA_ALIGN;
 constexpr int kMaxRowBytes = 2048;     // widest row the streaming scan holds in registers
 constexpr int kQueryChunkMax = 8192;   // queries per pass over the store
 constexpr int kSliceBudgetMax = 1024;  // most workgroups a scan launch may use
+constexpr int kPilotSlices = 512;           // slices of the threshold pilot (>= IC_MAX_K)
+constexpr int kPilotMinQueries = 9;         // smaller batches select cheaply without a pilot
+constexpr int64_t kPilotMinTiles = (int64_t)kPilotSlices * 8 * 4;  // 8 tiles per slice at tile_mul 4
 constexpr int kComputeUnitsDefault = 256;   // MI355X
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxTimedEvents = 1 << 16;  // event pairs kept while timing is on
@@ -29,13 +32,15 @@ constexpr int64_t kListSlots = kRegionSlots / 8 + kQueryChunkMax;
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // Candidates a scan workgroup keeps per query between compactions.
-inline int region_cap(int k) { return k <= 32 ? 64 : (k <= 64 ? 128 : ic::kMaxCap); }
+// Sized so that, with 64 queries per workgroup, two workgroups fit the LDS of a compute unit
+// for k <= 64 (64 * 112 * 8 B = 56 KB of regions each).
+inline int region_cap(int k) { return k <= 32 ? 64 : (k <= 64 ? 112 : ic::kMaxCap); }
 
 struct Layout {
     int esize = 0, row_bytes = 0, q_chunk = 0;
     int64_t cap_pad = 0;
     size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
-           off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, total = 0;
+           off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, off_pilot = 0, off_thr = 0, total = 0;
 };
 
 bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int32_t max_k, Layout &L) {
@@ -65,6 +70,8 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_list_b = take((size_t)kListSlots * (size_t)max_k * 8);
     L.off_consts = take(64);
     L.off_bias = take((size_t)L.cap_pad * 4);
+    L.off_pilot = take((size_t)L.q_chunk * kPilotSlices * 8);
+    L.off_thr = take((size_t)L.q_chunk * 8);
     L.total = off;
     return true;
 }
@@ -76,26 +83,29 @@ __global__ void init_consts(uint32_t *c) {
 
 using ScanFn = void (*)(dim3, hipStream_t, const ic::ScanArgs &);
 
-template <int ET, int QG, int CPW>
+template <int ET, int QG, int CPW, bool PILOT>
 void launch_scan(dim3 grid, hipStream_t st, const ic::ScanArgs &a) {
     // more than 64 KB of dynamic LDS has to be allowed once per kernel
     static const hipError_t allowed = hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&ic::scan_stream<ET, QG, CPW>),
+        reinterpret_cast<const void *>(&ic::scan_stream<ET, QG, CPW, PILOT>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::scan_lds_bytes(QG, ic::kMaxCap));
     (void)allowed;
-    hipLaunchKernelGGL((ic::scan_stream<ET, QG, CPW>), grid, dim3(256), ic::scan_lds_bytes(QG, a.cap), st, a);
+    hipLaunchKernelGGL((ic::scan_stream<ET, QG, CPW, PILOT>), grid, dim3(256),
+                       ic::scan_lds_bytes(QG, PILOT ? 0 : a.cap), st, a);
 }
 
-#define IC_SCAN_ROW(ET, QG)                                                                     \
+#define IC_SCAN_ROW(ET, QG, P)                                                                  \
     {                                                                                           \
-        launch_scan<ET, QG, 1>, launch_scan<ET, QG, 2>, launch_scan<ET, QG, 3>,                  \
-            launch_scan<ET, QG, 4>, launch_scan<ET, QG, 5>, launch_scan<ET, QG, 6>,              \
-            launch_scan<ET, QG, 7>, launch_scan<ET, QG, 8>                                       \
+        launch_scan<ET, QG, 1, P>, launch_scan<ET, QG, 2, P>, launch_scan<ET, QG, 3, P>,         \
+            launch_scan<ET, QG, 4, P>, launch_scan<ET, QG, 5, P>, launch_scan<ET, QG, 6, P>,     \
+            launch_scan<ET, QG, 7, P>, launch_scan<ET, QG, 8, P>                                 \
     }
-// [element type][query groups: 1, 2, 4][chunks per wavefront - 1]
-const ScanFn kScanTable[2][3][8] = {
-    {IC_SCAN_ROW(0, 1), IC_SCAN_ROW(0, 2), IC_SCAN_ROW(0, 4)},
-    {IC_SCAN_ROW(1, 1), IC_SCAN_ROW(1, 2), IC_SCAN_ROW(1, 4)},
+// [pilot][element type][query groups: 1, 2, 4][chunks per wavefront - 1]
+const ScanFn kScanTable[2][2][3][8] = {
+    {{IC_SCAN_ROW(0, 1, false), IC_SCAN_ROW(0, 2, false), IC_SCAN_ROW(0, 4, false)},
+     {IC_SCAN_ROW(1, 1, false), IC_SCAN_ROW(1, 2, false), IC_SCAN_ROW(1, 4, false)}},
+    {{IC_SCAN_ROW(0, 1, true), IC_SCAN_ROW(0, 2, true), IC_SCAN_ROW(0, 4, true)},
+     {IC_SCAN_ROW(1, 1, true), IC_SCAN_ROW(1, 2, true), IC_SCAN_ROW(1, 4, true)}},
 };
 #undef IC_SCAN_ROW
 
@@ -123,6 +133,8 @@ struct ic_index {
     uint64_t *list_b;
     uint8_t *consts;
     float *bias;
+    uint64_t *pilot_keys;  // [q_chunk][kPilotSlices]
+    uint64_t *thr_init;    // [q_chunk]
     bool consts_ready;  // written by the first search (creation launches nothing)
     bool timing;
     std::vector<hipEvent_t> events;  // pairs (start, stop)
@@ -191,6 +203,8 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->list_b = (uint64_t *)(base + L.off_list_b);
     ix->consts = base + L.off_consts;
     ix->bias = (float *)(base + L.off_bias);
+    ix->pilot_keys = (uint64_t *)(base + L.off_pilot);
+    ix->thr_init = (uint64_t *)(base + L.off_thr);
     ix->timing = false;
     ix->events_used = 0;
     ix->consts_ready = false;
@@ -322,16 +336,6 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
         // a3-a5: similarity, score epilogue and per-slice partial top-k
         int S = 0;
         if (n > 0) {
-            // one workgroup per slice and query block; by default as many as are resident at once
-            // (two per compute unit by registers, fewer when the candidate regions fill the LDS)
-            int budget = index->slice_budget;
-            if (budget == 0) {
-                const size_t lds = ic::scan_lds_bytes(1 << qg_idx, cap);
-                const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
-                budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
-            }
-            int64_t s = std::max<int64_t>(1, budget / nqb);
-            S = (int)std::min<int64_t>(s, ntiles);
             ic::ScanArgs a;
             a.store = index->rows;
             a.n = n;
@@ -344,9 +348,47 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
             a.Q = qc;
             a.k = k;
             a.cap = cap;
-            a.S = S;
             a.regions = index->regions;
             a.counts = index->counts;
+            a.pilot_out = index->pilot_keys;
+            a.thr_init = nullptr;
+            a.tile_mul = 1;
+
+            // Threshold pilot: a pass over a strided sample of the tiles that keeps the best
+            // score per (query, slice); the k-th largest of a query's slice maxima is reached
+            // by at least k rows, so the full scan may start from it.
+            if (qc >= kPilotMinQueries && ntiles >= kPilotMinTiles) {
+                ic::ScanArgs p = a;
+                p.S = kPilotSlices;
+                p.tile_mul = (int)std::min<int64_t>(64, ntiles / (kPilotSlices * 8));
+                kScanTable[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
+                ic::MergeArgs m;
+                m.src = index->pilot_keys;
+                m.q_stride = kPilotSlices;
+                m.seg_stride = 1;
+                m.seg_cap = 1;
+                m.seg_counts = nullptr;
+                m.nseg = kPilotSlices;
+                m.segs_per_wg = kPilotSlices;
+                m.k = k;
+                m.dst = nullptr;
+                m.out_scores = nullptr;
+                m.out_ids = nullptr;
+                m.kth_out = index->thr_init;
+                hipLaunchKernelGGL(ic::merge_lists, dim3(qc, 1), dim3(256), 0, st, m);
+                a.thr_init = index->thr_init;
+            }
+
+            // one workgroup per slice and query block; by default as many as are resident at once
+            // (two per compute unit by registers, fewer when the candidate regions fill the LDS)
+            int budget = index->slice_budget;
+            if (budget == 0) {
+                const size_t lds = ic::scan_lds_bytes(1 << qg_idx, cap);
+                const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
+                budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
+            }
+            S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
+            a.S = S;
             const bool timed = index->timing && index->events_used + 2 <= kMaxTimedEvents;
             if (timed) {
                 while (index->events.size() < index->events_used + 2) {
@@ -356,7 +398,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
                 }
                 (void)hipEventRecord(index->events[index->events_used], st);
             }
-            kScanTable[et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
+            kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
             if (timed) {
                 (void)hipEventRecord(index->events[index->events_used + 1], st);
                 index->events_used += 2;
@@ -366,6 +408,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
         // a6: merge the S candidate regions of every query
         ic::MergeArgs m;
         m.k = k;
+        m.kth_out = nullptr;
         m.out_scores = out_scores_dev + q0 * (int64_t)k;
         m.out_ids = out_ids_dev + q0 * (int64_t)k;
         m.src = index->regions;

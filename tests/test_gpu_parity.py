@@ -162,6 +162,10 @@ CASES = [
     ("fp8", 20011, 1024, 32, 64, 100, 0.0, "none", 1.0),
     ("fp8", 15000, 1024, 32, 3, 100, 0.0, "none", 1.0),
     ("fp8", 8000, 300, 8, 40, 20, 0.2, "beta25", 0.9),
+    # large enough (>= 262144 rows, Q >= 9) for the threshold pilot to run before the full scan
+    ("bf16", 300000, 128, 64, 24, 32, 0.0, "none", 1.0),
+    ("bf16", 280001, 64, 16, 64, 64, 0.15, "uniform", 0.9),
+    ("fp8", 300000, 128, 64, 40, 100, 0.0, "none", 1.0),
 ]
 
 
@@ -216,6 +220,23 @@ def test_adversarial_ascending_order(pkg, oracle):
     for k in (1, 10, 100):
         s, i = _search(ix, Qm, k)
         parity.check_batch("bf16", s, i, E, None, None, Qm, k, 0.0, f"ascending k={k}")
+    ix.close()
+
+
+def test_pilot_threshold_with_ties_and_sorted_rows(pkg, oracle):
+    """Pilot-sized cache whose rows are sorted by ascending score and hold many exact duplicates."""
+    _say("pilot: ascending order + duplicates")
+    cfg = workloads.C1.scaled(N=270000, d=64, clusters=8, Q=12, k=20)
+    E, U, M, Qm = _inputs(cfg)
+    order = np.argsort(oracle.scores(E, Qm[:1])[0], kind="stable")
+    E = np.ascontiguousarray(E[order])
+    E[-50000::7] = E[-1]                      # ~7000 copies of the best row, spread over the tail
+    E[1000:1400] = Qm[3]                      # 400 exact copies of one query
+    ix = _build_index(pkg, "bf16", E, None, max_k=128)
+    for k in (20, 128):
+        s, i = _search(ix, Qm, k)
+        parity.check_batch("bf16", s, i, E, None, None, Qm, k, 0.0, f"pilot ties k={k}")
+    assert list(i[3, :128]) == list(range(1000, 1128))      # equal scores: lowest ids win
     ix.close()
 
 
