@@ -1,63 +1,83 @@
-// Cross-slice merge: combine the candidate lists that the scan kernels leave
-// per (query, slice) into the final top-k of each query (the "keep the most
-// similar examples" step of IC-Cache stage 1, Sec. 4.1).
+// Cross-slice merge: combine the candidate lists that the scan kernels leave per query into the
+// final top-k of each query (the "keep the most similar examples" step of IC-Cache stage 1,
+// Sec. 4.1).
 //
-// One workgroup takes up to kMergeKeys keys of one query (a group of segments),
-// sorts them in LDS with a bitonic network under the (score desc, id asc) key
-// order and writes the best k.  The host chains launches until one group per
-// query is left; the last launch decodes keys into (fp32 score, int64 id).
+// One workgroup takes a group of segments of one query (at most kMergeKeys keys in all), packs
+// their keys into LDS, sorts them with a bitonic network under the (score desc, id asc) key
+// order and writes the best k.  The network is sized to the keys actually present, so nearly
+// empty segments (the usual case once the scan starts from the pilot's threshold) cost little.
+// The host chains launches until one group per query is left; the last launch decodes keys into
+// (fp32 score, int64 id).
 #pragma once
 #include "ic_common.h"
 
 namespace ic {
 
 constexpr int kMergeKeys = 2048;
+constexpr int kMergeMaxSegs = 64;  // segments one workgroup can take
 
 struct MergeArgs {
-    const uint64_t *src;       // keys of query q start at src + q * q_stride
+    const uint64_t *src;        // keys of query q start at src + q * q_stride
     int64_t q_stride;
-    int seg_stride;            // keys between consecutive segments
-    int seg_cap;               // most keys in a segment (slots reserved per segment in LDS)
-    const int32_t *seg_counts; // [Q][nseg] keys in use, or NULL: every segment holds seg_cap keys
-    int nseg;                  // segments per query
-    int segs_per_wg;           // segs_per_wg * seg_cap <= kMergeKeys
+    int seg_stride;             // keys between consecutive segments
+    int seg_cap;                // most keys in a segment
+    // keys in use per segment, one of: seg_counts[q][nseg]; or total_counts[q] keys laid out
+    // contiguously over the segments (segment s holds keys [s*seg_cap, (s+1)*seg_cap) of them,
+    // anything beyond nseg*seg_cap is ignored); or, when both are NULL, seg_cap in every segment
+    const int32_t *seg_counts;
+    const int32_t *total_counts;
+    int nseg;                   // segments per query
+    int segs_per_wg;            // <= kMergeMaxSegs, segs_per_wg * seg_cap <= kMergeKeys
     int k;
-    uint64_t *dst;             // non-final: lists [Q][gridDim.y][k]
-    float *out_scores;         // final: [Q][k], or NULL
-    int64_t *out_ids;          // final: [Q][k], or NULL
-    uint64_t *kth_out;         // final: [Q] key of the k-th best (0 if there are fewer), or NULL
+    uint64_t *dst;              // non-final: lists [Q][gridDim.y][k]
+    float *out_scores;          // final: [Q][k], or NULL
+    int64_t *out_ids;           // final: [Q][k], or NULL
+    uint64_t *kth_out;          // final: [Q] key of the k-th best (0 if there are fewer), or NULL
+    const int32_t *only_flagged;  // if not NULL, queries whose block of 64 has flag 0 are left alone
 };
 
 __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     __shared__ uint64_t buf[kMergeKeys];
+    __shared__ int seg_cnt[kMergeMaxSegs];
+    __shared__ int seg_off[kMergeMaxSegs + 1];
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
     const int g = blockIdx.y;
+    if (a.only_flagged && a.only_flagged[q >> 6] == 0) return;
     const int seg0 = g * a.segs_per_wg;
-    const int used = a.segs_per_wg * a.seg_cap;
-    int P = 2;
-    while (P < used) P <<= 1;
-    if (P < a.k) {
-        while (P < a.k) P <<= 1;
-    }
 
-    const uint64_t *src = a.src + (int64_t)q * a.q_stride;
-    for (int e = tid; e < P; e += 256) {
-        uint64_t key = 0;
-        if (e < used) {
-            const int si = e / a.seg_cap;
-            const int idx = e - si * a.seg_cap;
-            const int seg = seg0 + si;
-            if (seg < a.nseg) {
-                int c = a.seg_cap;
-                if (a.seg_counts) {
-                    c = a.seg_counts[(int64_t)q * a.nseg + seg];
-                    c = c < a.seg_cap ? c : a.seg_cap;
-                }
-                if (idx < c) key = src[(int64_t)seg * a.seg_stride + idx];
-            }
+    if (tid < a.segs_per_wg) {
+        const int seg = seg0 + tid;
+        int c = 0;
+        if (seg < a.nseg) {
+            if (a.seg_counts) c = a.seg_counts[(int64_t)q * a.nseg + seg];
+            else if (a.total_counts) c = a.total_counts[q] - seg * a.seg_cap;
+            else c = a.seg_cap;
+            c = c < 0 ? 0 : (c > a.seg_cap ? a.seg_cap : c);
         }
-        buf[e] = key;
+        seg_cnt[tid] = c;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int acc = 0;
+        for (int s = 0; s < a.segs_per_wg; ++s) {
+            seg_off[s] = acc;
+            acc += seg_cnt[s];
+        }
+        seg_off[a.segs_per_wg] = acc;
+    }
+    __syncthreads();
+    const int total = seg_off[a.segs_per_wg];
+    int P = 2;
+    while (P < total || P < a.k) P <<= 1;
+
+    for (int e = total + tid; e < P; e += 256) buf[e] = 0;
+    const uint64_t *src = a.src + (int64_t)q * a.q_stride;
+    for (int s = 0; s < a.segs_per_wg; ++s) {
+        const int c = seg_cnt[s];
+        const uint64_t *sp = src + (int64_t)(seg0 + s) * a.seg_stride;
+        uint64_t *dp = buf + seg_off[s];
+        for (int idx = tid; idx < c; idx += 256) dp[idx] = sp[idx];
     }
 
     for (int size = 2; size <= P; size <<= 1) {

@@ -1,0 +1,393 @@
+// Large-batch scan: similarity of blocks of 256 queries with tiles of 256 cached rows as a
+// register-tiled MFMA contraction, fused with threshold selection.  This is the same O(N) step of
+// IC-Cache's stage-1 relevance selection (Sec. 4.1; GetSimilarExamples in Algorithm 1) as the
+// streaming scan, for batches large enough that the matrix cores, not HBM, bound the work.
+//
+// Shape of the computation
+//   * One output tile = 256 rows x 256 queries over the whole embedding dimension.  A workgroup
+//     (4 wavefronts, 2 x 2, each 128 x 128 = 4 x 4 MFMA tiles of 32x32, 256 accumulator registers)
+//     walks the dimension in stages of 128 bytes per row.  Both operands of a stage (512 rows x
+//     128 B = 64 KB) are copied from global memory straight into LDS (global_load_lds_dwordx4: no
+//     staging registers, no LDS store instructions); LDS is double buffered, one barrier per stage.
+//   * LDS layout: row-major, 128 B per row, the eight 16-byte granules of a row XOR-swizzled with
+//     the row index so that the 32 lanes of an operand read hit distinct banks.  A direct load
+//     writes lane l of a wavefront to (wave's LDS base + 16*l), i.e. 8 rows x 8 granules per
+//     instruction, so the swizzle is applied on the global side: lane l fetches granule
+//     (l%8) ^ (l/8) of its row.
+//   * Operand mapping: lane (r = lane%32, h = lane/32) reads granule 2*p + h of row r for step p;
+//     rows and queries use the same mapping, so each MFMA pairs equal coordinates (the order of
+//     the coordinates inside a dot product is free).  bf16: one v_mfma_f32_32x32x16_bf16 per
+//     granule pair; fp8: two v_mfma_f32_32x32x16_fp8_fp8 (8 bytes each).
+//   * Workgroups are persistent and XCD-aware: workgroup id modulo 8 is the XCD it runs on; an XCD
+//     owns a group of query blocks small enough to stay in its L2 and a class of row tiles, and
+//     walks query blocks fastest so that a row tile is used by consecutive tiles.
+//   * Selection: thresholds come from the pilot (a score that at least k rows reach, per query)
+//     and stay in registers.  A tile's 65,536 scores are compared 16 at a time (max, then one
+//     compare); a lane whose 16 scores reach the threshold copies them to an LDS list, the
+//     workgroup then tests those few blocks exactly, one score per thread, and parks what passes
+//     (about 17 candidates per tile) in a second LDS list.  That list
+//     is flushed to the queries' candidate lists in global memory (slot = atomic counter per
+//     query) while the next tile is being computed: the atomics are issued at the start of that
+//     tile and their results used after its last stage, so nobody waits for an L2 round trip.
+//     If a candidate list overflows, its block of 64 queries is flagged and redone by the
+//     streaming scan, so the result stays exact whatever the data.
+#pragma once
+#include "ic_common.h"
+
+namespace ic {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kGemmTile = 256;        // rows and queries per output tile
+constexpr int kGemmStageBytes = 128;  // bytes of every row per stage
+
+struct GemmArgs {
+    const uint8_t *store;    // [n] rows, row_bytes apart
+    int64_t n;
+    int row_bytes;           // multiple of 128
+    const float *row_scale;  // fp8: [round_up(n,256)]
+    const float *bias;       // [round_up(n,256)]: lambda*utility, -inf for invalid and padding rows
+    const uint8_t *qbuf;     // prepared queries, [nqb*256] rows
+    const float *q_scale;    // fp8: per prepared query
+    int Q;                   // real queries
+    const uint64_t *thr_init;  // [Q] key of a score that >= k rows reach (0: none)
+    uint64_t *glist;         // [Q][gcap] candidate keys
+    int gcap;
+    int32_t *gcount;         // [Q] candidates appended (may exceed gcap: the list overflowed)
+    int32_t *redo;           // [ceil(Q/64)] set to 1 when a list of the block overflowed
+    int nqb;                 // query blocks of 256
+    int64_t ntiles;          // row tiles of 256
+    int gq;                  // XCD mapping: query-block groups (1, 2, 4 or 8); 8/gq row classes
+};
+
+constexpr int kGemmPark = 512;        // candidates a workgroup can park per tile
+constexpr int kGemmHits = 96;         // blocks of 16 scores a workgroup can list per tile
+
+struct HitEntry {   // 16 scores of one lane's block that reached its query's threshold
+    f32x4 sc[4];
+    uint64_t thr;   // the query's pilot key
+    uint32_t q;
+    uint32_t row;   // row of score 0
+};
+
+constexpr size_t gemm_lds_bytes() {
+    return (size_t)2 * 2 * kGemmTile * kGemmStageBytes + 2 * kGemmTile * 4 + (size_t)kGemmPark * 12 + 16 +
+           (size_t)kGemmHits * sizeof(HitEntry);
+}
+
+template <int ET>
+__global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
+    uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
+    constexpr int kStage = 2 * kGemmTile * kGemmStageBytes;  // 64 KB: rows then queries
+    float *bias_t = reinterpret_cast<float *>(lds + 2 * kStage);
+    float *scale_t = bias_t + kGemmTile;
+    uint64_t *park_key = reinterpret_cast<uint64_t *>(scale_t + kGemmTile);  // [kGemmPark]
+    uint32_t *park_q = reinterpret_cast<uint32_t *>(park_key + kGemmPark);    // [kGemmPark]
+    uint32_t *park_n = park_q + kGemmPark;   // [0] parked candidates, [1] listed blocks
+    uint32_t *hit_n = park_n + 1;
+    HitEntry *hits = reinterpret_cast<HitEntry *>(park_n + 4);  // [kGemmHits]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w >> 1, wn = w & 1;
+    const int r32 = lane & 31, h = lane >> 5;
+    const int nst = a.row_bytes / kGemmStageBytes;
+
+    // ---- which tiles this workgroup walks
+    const int xcd = blockIdx.x & 7;
+    const int gr = 8 / a.gq;                          // row classes
+    const int qgroup = xcd % a.gq, rclass = xcd / a.gq;
+    const int nq_x = (a.nqb - qgroup + a.gq - 1) / a.gq;              // query blocks of this XCD
+    const int64_t nr_x = (a.ntiles - rclass + gr - 1) / gr;           // row tiles of this XCD
+    const int64_t work = (int64_t)nq_x * nr_x;
+    const int64_t step = gridDim.x >> 3;
+
+    // ---- copy plan: one direct load moves 8 rows x 128 B per wavefront; wavefront w covers rows
+    // 8w .. 8w+7 of every group of 32 rows; 16 loads per stage (8 for the rows, 8 for the queries)
+    const int crow = tid >> 3;                       // row within a group of 32
+    const int cg_src = (lane & 7) ^ ((lane >> 3) & 7);  // granule fetched, so that it lands swizzled
+    const uint32_t q_off = (uint32_t)(crow * a.row_bytes + cg_src * 16);
+
+    // ---- operand read plan: byte offset inside a stage of this lane's granule for step p
+    uint32_t frag_off[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) frag_off[p] = (uint32_t)(r32 * kGemmStageBytes + (((2 * p + h) ^ (r32 & 7)) * 16));
+    const uint32_t a_base = (uint32_t)(wm * 128 * kGemmStageBytes);
+    const uint32_t b_base = (uint32_t)((kGemmTile + wn * 128) * kGemmStageBytes);
+
+    typedef const void __attribute__((address_space(1))) *gptr_t;
+    typedef void __attribute__((address_space(3))) *lptr_t;
+    // Request quarter `part` (0..3) of stage ks of a tile into LDS buffer buf: 2 of the 8 row
+    // groups and 2 of the 8 query groups.  The quarters are issued between the MFMA steps of the
+    // previous stage so that the memory instructions hide behind the matrix work.  Completion is
+    // awaited with vmcnt.
+    auto load_quarter = [&](const uint8_t *rows_base, int last, const uint8_t *q_base, int ks, int buf, int part) {
+        uint8_t *dst = lds + buf * kStage + w * (8 * kGemmStageBytes);  // wave-uniform
+        const uint8_t *ra = rows_base + ks * kGemmStageBytes;           // uniform
+        const uint8_t *qa = q_base + ks * kGemmStageBytes;              // uniform
+        // address = uniform base (stage, row group) + one 32-bit per-thread offset shared by all groups
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int i = 2 * part + u;
+            if (last == kGemmTile - 1) {
+                __builtin_amdgcn_global_load_lds((gptr_t)(ra + (size_t)i * 32 * a.row_bytes + q_off),
+                                                 (lptr_t)(dst + i * 32 * kGemmStageBytes), 16, 0, 0);
+            } else {  // ragged last tile: rows past the end re-read the last valid row; their bias is -inf
+                int r = crow + 32 * i;
+                r = r < last ? r : last;
+                __builtin_amdgcn_global_load_lds((gptr_t)(ra + (uint32_t)(r * a.row_bytes + cg_src * 16)),
+                                                 (lptr_t)(dst + i * 32 * kGemmStageBytes), 16, 0, 0);
+            }
+            __builtin_amdgcn_global_load_lds((gptr_t)(qa + (size_t)i * 32 * a.row_bytes + q_off),
+                                             (lptr_t)(dst + (kGemmTile + i * 32) * kGemmStageBytes), 16, 0, 0);
+        }
+    };
+    auto load_stage = [&](const uint8_t *rows_base, int last, const uint8_t *q_base, int ks, int buf) {
+#pragma unroll
+        for (int part = 0; part < 4; ++part) load_quarter(rows_base, last, q_base, ks, buf, part);
+    };
+    auto await_stage = [&]() {  // every direct load issued so far has landed, and all wavefronts know it
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
+
+    // Everything a tile needs to address its operands.
+    struct Tile {
+        int qb;
+        int last;  // last valid row of the tile, relative to its first row (0 .. 255)
+        int64_t row0;
+        const uint8_t *rows_base;
+        const uint8_t *q_base;
+    };
+    auto locate = [&](int ql, int64_t rl, Tile &t) {  // ql-th query block, rl-th row tile of this XCD
+        t.qb = qgroup + a.gq * ql;
+        t.row0 = (rclass + gr * rl) * kGemmTile;
+        t.rows_base = a.store + t.row0 * a.row_bytes;
+        t.q_base = a.qbuf + (size_t)t.qb * kGemmTile * a.row_bytes;
+        const int64_t last = a.n - 1 - t.row0;
+        t.last = (int)(last < kGemmTile - 1 ? last : kGemmTile - 1);
+    };
+
+    // append one candidate to its query's list (slot from the query's atomic counter)
+    auto append_global = [&](uint32_t q, uint64_t key, int pos) {
+        if (pos < a.gcap) a.glist[(size_t)q * a.gcap + pos] = key;
+        else a.redo[q >> 6] = 1;
+    };
+    if (tid == 0) {
+        *park_n = 0u;
+        *hit_n = 0u;
+    }
+
+    // job = rl * nq_x + ql walks query blocks fastest; the pair is advanced without divisions
+    int64_t job = blockIdx.x >> 3;
+    const int step_q = nq_x > 0 ? (int)(step % nq_x) : 0;
+    const int64_t step_r = nq_x > 0 ? step / nq_x : 0;
+    int ql = nq_x > 0 ? (int)(job % nq_x) : 0;
+    int64_t rl = nq_x > 0 ? job / nq_x : 0;
+    Tile cur;
+    if (job < work) {
+        locate(ql, rl, cur);
+        load_stage(cur.rows_base, cur.last, cur.q_base, 0, 0);
+    }
+    for (; job < work; job += step) {
+        locate(ql, rl, cur);
+        const int qb = cur.qb;
+        const int64_t row0 = cur.row0;
+
+        f32x16 acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+        await_stage();  // stage 0 was requested before the previous tile's epilogue
+
+        // What the previous tile parked is flushed during this tile: slots are claimed (one atomic
+        // per candidate) at the start of the last stage, where no wait for direct loads follows,
+        // and the keys are written after it.
+        const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);
+        int fl_pos[2] = {-1, -1};
+
+        for (int ks = 0; ks < nst; ++ks) {
+            const int buf = ks & 1;
+            const bool more = ks + 1 < nst;
+            if (!more) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const uint32_t e = tid + 256 * u;
+                    if (e < parked) fl_pos[u] = atomicAdd(a.gcount + park_q[e], 1);
+                }
+            }
+            const uint8_t *sa = lds + buf * kStage + a_base;
+            const uint8_t *sb = lds + buf * kStage + b_base;
+            // operands of step p+1 are read while the 16 MFMAs of step p run
+            i32x4 fa[2][4], fb[2][4];
+            auto read_frags = [&](int p, i32x4 *xa, i32x4 *xb) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xa[i] = *reinterpret_cast<const i32x4 *>(sa + i * 32 * kGemmStageBytes + frag_off[p]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xb[j] = *reinterpret_cast<const i32x4 *>(sb + j * 32 * kGemmStageBytes + frag_off[p]);
+            };
+            read_frags(0, fa[0], fb[0]);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                if (more) load_quarter(cur.rows_base, cur.last, cur.q_base, ks + 1, buf ^ 1, p);
+                if (p + 1 < 4) read_frags(p + 1, fa[(p + 1) & 1], fb[(p + 1) & 1]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (ET == 0) {
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                __builtin_bit_cast(bf16x8, fa[p & 1][i]), __builtin_bit_cast(bf16x8, fb[p & 1][j]),
+                                acc[i][j], 0, 0, 0);
+                        } else {
+                            const i64x2 x = __builtin_bit_cast(i64x2, fa[p & 1][i]);
+                            const i64x2 y = __builtin_bit_cast(i64x2, fb[p & 1][j]);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.x, y.x, acc[i][j], 0, 0, 0);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.y, y.y, acc[i][j], 0, 0, 0);
+                        }
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (more) await_stage();
+            else __syncthreads();
+        }
+
+        // what the epilogue needs from global memory is requested only now, so that nothing but the
+        // accumulators and the operand pipeline lives in registers across the stages
+        uint64_t thr_raw[4];
+        float qs[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
+            if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
+            thr_raw[j] = a.thr_init[q];
+            qs[j] = (ET == 1) ? a.q_scale[q] : 1.0f;
+        }
+        f32x4 bias_r = {0.f, 0.f, 0.f, 0.f}, scale_r = {1.f, 1.f, 1.f, 1.f};
+        if (tid < 64) {
+            bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
+            if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t e = tid + 256 * u;
+            if (fl_pos[u] >= 0) append_global(park_q[e], park_key[e], fl_pos[u]);
+        }
+        if (tid < 64) {  // every wavefront is past the previous tile's epilogue (it has met this tile's barriers)
+            *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
+            if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
+        }
+        __syncthreads();   // the parked entries have been read by their flushers
+        if (tid == 0) {
+            *park_n = 0u;
+            *hit_n = 0u;
+        }
+        __syncthreads();
+
+        // request the next tile's first stage; it lands while this tile's scores are examined
+        ql += step_q;
+        rl += step_r;
+        if (ql >= nq_x) {
+            ql -= nq_x;
+            rl += 1;
+        }
+        const bool have_next = job + step < work;
+        Tile nxt;
+        if (have_next) locate(ql, rl, nxt);
+
+        // ---- epilogue: score = dot * scales + bias, compare with the query's threshold
+        // accumulator v of tile (i, j) is row wm*128 + i*32 + 8*(v/4) + 4*h + v%4, query column j*32 + r32
+        float thr_s[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
+            thr_s[j] = thr_raw[j] > kKeyFloor ? key_score(thr_raw[j]) : -INFINITY;
+            if (q >= a.Q) thr_s[j] = INFINITY;  // padding query: nothing passes
+        }
+        // pass 1: 16 blocks of 16 scores per lane.  A lane whose block reaches the query's
+        // threshold (about 17 lanes per tile) copies the block's scores to a small LDS list.
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            // a quarter of the next tile's first stage per block row: it lands while the scores are examined
+            if (have_next) load_quarter(nxt.rows_base, nxt.last, nxt.q_base, 0, 0, i);
+            f32x4 bs[4], rs[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int rr = wm * 128 + i * 32 + 8 * u + 4 * h;
+                bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
+                if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                f32x4 sc[4];
+                float best = -INFINITY;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
+                                              : acc[i][j][v] + bs[v >> 2][v & 3];
+                    sc[v >> 2][v & 3] = x;
+                    best = fmaxf(best, x);
+                }
+                if (best >= thr_s[j]) {
+                    const uint32_t slot = atomicAdd(hit_n, 1u);
+                    const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
+                    if (slot < (uint32_t)kGemmHits) {
+                        HitEntry &e = hits[slot];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) e.sc[u] = sc[u];
+                        e.q = (uint32_t)q;
+                        e.row = (uint32_t)(row0 + wm * 128 + i * 32 + 4 * h);  // row of score 0; score v: + 8*(v/4) + v%4
+                        e.thr = thr_raw[j];
+                    } else {
+                        a.redo[q >> 6] = 1;  // list full (never in practice): the block is redone exactly
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // pass 2: the listed blocks, one score per thread; what passes the exact key test is parked
+        {
+            const uint32_t nh = min(*hit_n, (uint32_t)kGemmHits);
+            const int v = tid & 15;
+            for (uint32_t e = tid >> 4; e < nh; e += 16) {
+                const HitEntry &he = hits[e];
+                const float x = he.sc[v >> 2][v & 3];
+                const uint64_t t0 = he.thr;
+                const uint64_t thr_k = t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
+                const uint64_t key = make_key(x, he.row + 8 * (v >> 2) + (v & 3));
+                if (key > thr_k && x > -INFINITY) {
+                    const uint32_t slot = atomicAdd(park_n, 1u);
+                    if (slot < (uint32_t)kGemmPark) {
+                        park_key[slot] = key;
+                        park_q[slot] = he.q;
+                    } else {
+                        a.redo[he.q >> 6] = 1;
+                    }
+                }
+            }
+        }
+    }
+
+    // the last tile's parked candidates
+    __syncthreads();
+    const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);
+    for (uint32_t e = tid; e < parked; e += 256) {
+        const uint32_t q = park_q[e];
+        append_global(q, park_key[e], atomicAdd(a.gcount + q, 1));
+    }
+}
+
+// Zero the per-query counters and the redo flags before a scan_gemm launch.
+__global__ void gemm_reset(int32_t *gcount, int nq, int32_t *redo, int nblk) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nq) gcount[i] = 0;
+    if (i < nblk) redo[i] = 0;
+}
+
+}  // namespace ic

@@ -60,6 +60,7 @@ struct ScanArgs {
     int tile_mul;            // the kernel visits tiles 0, tile_mul, 2*tile_mul, ... (1 = all)
     uint64_t *pilot_out;     // PILOT kernels: [Q][S] keys (best score of the slice, id = slice)
     const uint64_t *thr_init;  // full scan: per query, key of a score that >= k rows reach, or NULL
+    const int32_t *redo;     // if not NULL (QG == 4 only): query blocks whose flag is 0 are skipped
 };
 
 constexpr int kScanWaves = 4;
@@ -144,6 +145,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     const int qb = blockIdx.y;
     const int nchunks = a.row_bytes >> 6;
     const int chunk0 = w * CPW;
+    if (a.redo && a.redo[qb] == 0) return;  // whole workgroup: this block needs no second pass
 
     // Starting threshold of a query: nothing, or "any row whose score reaches the pilot's
     // score" (the key just below the smallest key with that score).

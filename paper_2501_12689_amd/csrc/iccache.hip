@@ -12,6 +12,7 @@
 #include "ic_common.h"
 #include "ic_merge.h"
 #include "ic_quantize.h"
+#include "ic_scan_gemm.h"
 #include "ic_scan_stream.h"
 
 namespace {
@@ -27,7 +28,10 @@ constexpr int kComputeUnitsDefault = 256;   // MI355X
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxTimedEvents = 1 << 16;  // event pairs kept while timing is on
 constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on queries x slices
-constexpr int64_t kListSlots = kRegionSlots / 8 + kQueryChunkMax;
+constexpr int kGemmMinQueries = 128;        // batches from here on use the MFMA-tiled scan
+constexpr int kGemmListSeg = ic::kMergeKeys;  // candidate lists are merged in segments of this many keys
+constexpr int kGemmListMax = 8 * kGemmListSeg;
+constexpr size_t kL2Share = 2u << 20;       // query-block bytes an XCD keeps resident in its L2
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -36,11 +40,23 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 // for k <= 64 (64 * 112 * 8 B = 56 KB of regions each).
 inline int region_cap(int k) { return k <= 32 ? 64 : (k <= 64 ? 112 : ic::kMaxCap); }
 
+// Keys of the per-query candidate list of the MFMA-tiled scan.  Starting from the pilot's
+// threshold about 64*k rows pass (the pilot sees every 64th tile); over 4096 queries with
+// k = 16 the largest list seen was 2.1 times that mean, so the list holds 128*k and never
+// fewer than 4096.  An overflow is still handled exactly (the block is redone).
+inline int gemm_list_cap(int k) {
+    int64_t c = round_up(std::min<int64_t>(std::max<int64_t>(128 * (int64_t)k, 2 * kGemmListSeg), kGemmListMax), kGemmListSeg);
+    return (int)c;
+}
+
 struct Layout {
     int esize = 0, row_bytes = 0, q_chunk = 0;
     int64_t cap_pad = 0;
     size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
-           off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, off_pilot = 0, off_thr = 0, total = 0;
+           off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, off_pilot = 0, off_thr = 0, off_glist = 0, off_gcount = 0,
+           off_redo = 0, total = 0;
+    int64_t list_slots = 0;
+    int q_rows = 0;  // rows of the prepared query block
 };
 
 bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int32_t max_k, Layout &L) {
@@ -51,8 +67,11 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     const int64_t rb = round_up((int64_t)d * L.esize, 128);
     if (rb > kMaxRowBytes) return false;
     L.row_bytes = (int)rb;
-    L.cap_pad = round_up(capacity, 16);
+    L.cap_pad = round_up(capacity, ic::kGemmTile);
     L.q_chunk = (int)std::min<int64_t>(round_up(max_q, 64), kQueryChunkMax);
+    L.q_rows = (int)round_up(L.q_chunk, ic::kGemmTile);
+    const bool gemm = L.q_chunk >= kGemmMinQueries;
+    L.list_slots = std::max<int64_t>(kRegionSlots / 8 + L.q_chunk, gemm ? (int64_t)L.q_chunk * (kGemmListMax / kGemmListSeg) : 0);
     size_t off = 0;
     auto take = [&](size_t bytes) {
         size_t at = off;
@@ -62,16 +81,19 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_rows = take((size_t)L.cap_pad * (size_t)L.row_bytes);
     L.off_scale = take(store == IC_STORE_FP8_E4M3 ? (size_t)L.cap_pad * 4 : 0);
     L.off_util = take((size_t)L.cap_pad * 4);
-    L.off_qbuf = take((size_t)L.q_chunk * (size_t)L.row_bytes);
-    L.off_qscale = take((size_t)L.q_chunk * 4);
+    L.off_qbuf = take((size_t)L.q_rows * (size_t)L.row_bytes);
+    L.off_qscale = take((size_t)L.q_rows * 4);
     L.off_regions = take((size_t)kRegionSlots * (size_t)region_cap(max_k) * 8);
     L.off_counts = take((size_t)kRegionSlots * 4);
-    L.off_list_a = take((size_t)kListSlots * (size_t)max_k * 8);
-    L.off_list_b = take((size_t)kListSlots * (size_t)max_k * 8);
+    L.off_list_a = take((size_t)L.list_slots * (size_t)max_k * 8);
+    L.off_list_b = take((size_t)L.list_slots * (size_t)max_k * 8);
     L.off_consts = take(64);
     L.off_bias = take((size_t)L.cap_pad * 4);
     L.off_pilot = take((size_t)L.q_chunk * kPilotSlices * 8);
     L.off_thr = take((size_t)L.q_chunk * 8);
+    L.off_glist = take(gemm ? (size_t)L.q_chunk * (size_t)gemm_list_cap(max_k) * 8 : 0);
+    L.off_gcount = take(gemm ? (size_t)L.q_chunk * 4 : 0);
+    L.off_redo = take(gemm ? (size_t)(L.q_chunk / 64 + 1) * 4 : 0);
     L.total = off;
     return true;
 }
@@ -109,6 +131,15 @@ const ScanFn kScanTable[2][2][3][8] = {
 };
 #undef IC_SCAN_ROW
 
+template <int ET>
+void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
+    static const hipError_t allowed =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::gemm_lds_bytes());
+    (void)allowed;
+    hipLaunchKernelGGL((ic::scan_gemm<ET>), dim3(grid), dim3(256), ic::gemm_lds_bytes(), st, a);
+}
+
 }  // namespace
 
 struct ic_index {
@@ -135,6 +166,10 @@ struct ic_index {
     float *bias;
     uint64_t *pilot_keys;  // [q_chunk][kPilotSlices]
     uint64_t *thr_init;    // [q_chunk]
+    uint64_t *glist;       // [q_chunk][gemm_list_cap(max_k)], NULL when max_queries < kGemmMinQueries
+    int32_t *gcount;       // [q_chunk]
+    int32_t *redo;         // [q_chunk/64 + 1]
+    int gemm_list_cap_override;  // tests: shrink the candidate lists to force the overflow path
     bool consts_ready;  // written by the first search (creation launches nothing)
     bool timing;
     std::vector<hipEvent_t> events;  // pairs (start, stop)
@@ -205,6 +240,15 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->bias = (float *)(base + L.off_bias);
     ix->pilot_keys = (uint64_t *)(base + L.off_pilot);
     ix->thr_init = (uint64_t *)(base + L.off_thr);
+    const bool gemm = L.q_chunk >= kGemmMinQueries;
+    ix->glist = gemm ? (uint64_t *)(base + L.off_glist) : nullptr;
+    ix->gcount = gemm ? (int32_t *)(base + L.off_gcount) : nullptr;
+    ix->redo = gemm ? (int32_t *)(base + L.off_redo) : nullptr;
+    ix->gemm_list_cap_override = 0;
+    if (const char *e = std::getenv("IC_GEMM_LIST_CAP")) {  // tests only
+        int v = std::atoi(e);
+        if (v >= 1 && v <= gemm_list_cap(max_k)) ix->gemm_list_cap_override = v;
+    }
     ix->timing = false;
     ix->events_used = 0;
     ix->consts_ready = false;
@@ -281,6 +325,60 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
     return IC_OK;
 }
 
+namespace {
+
+// Chain merge_lists launches from the given first level down to one group per query, then
+// write the final rows.  `m` describes the first level; out pointers are for this query block.
+void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_scores, int64_t *out_ids,
+               const int32_t *only_flagged) {
+    hipStream_t st = index->stream;
+    uint64_t *ping = index->list_a, *pong = index->list_b;
+    m.k = k;
+    m.kth_out = nullptr;
+    m.out_scores = out_scores;
+    m.out_ids = out_ids;
+    m.only_flagged = only_flagged;
+    for (;;) {
+        const int G = std::max(1, (m.nseg + m.segs_per_wg - 1) / m.segs_per_wg);
+        m.dst = (G == 1) ? nullptr : ping;
+        hipLaunchKernelGGL(ic::merge_lists, dim3(qc, G), dim3(256), 0, st, m);
+        if (G == 1) break;
+        m.src = ping;
+        m.q_stride = (int64_t)G * k;
+        m.seg_stride = k;
+        m.seg_cap = k;
+        m.seg_counts = nullptr;
+        m.total_counts = nullptr;
+        m.nseg = G;
+        m.segs_per_wg = std::min(ic::kMergeMaxSegs, ic::kMergeKeys / k);
+        std::swap(ping, pong);
+    }
+}
+
+struct Timer {  // brackets the dominant kernel of a search with events when timing is on
+    ic_index *index;
+    bool on;
+    explicit Timer(ic_index *ix) : index(ix), on(false) {}
+    bool start() {
+        on = index->timing && index->events_used + 2 <= kMaxTimedEvents;
+        if (!on) return true;
+        while (index->events.size() < index->events_used + 2) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return false;
+            index->events.push_back(e);
+        }
+        (void)hipEventRecord(index->events[index->events_used], index->stream);
+        return true;
+    }
+    void stop() {
+        if (!on) return;
+        (void)hipEventRecord(index->events[index->events_used + 1], index->stream);
+        index->events_used += 2;
+    }
+};
+
+}  // namespace
+
 ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
                     const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
     ic_index *index = const_cast<ic_index *>(cindex);
@@ -296,16 +394,22 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
     const int64_t n = index->n;
     const int64_t ntiles = (n + 15) / 16;
     hipStream_t st = index->stream;
+    const bool pilot_ok = ntiles >= kPilotMinTiles;
+    // batches large enough for the matrix cores to be the bound take the MFMA-tiled scan; it
+    // needs the pilot's thresholds and the per-query candidate lists
+    const bool gemm_ok = pilot_ok && index->glist != nullptr;
 
     if (!index->consts_ready) {
         hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)index->consts);
         index->consts_ready = true;
     }
 
-    // a4 (first half): per-row additive term, once per search
-    const bool use_bias = (lambda != 0.0f) || mask_dev != nullptr;
+    // a4 (first half): per-row additive term, once per search.  The tiled scan always reads it
+    // (it marks the padding rows of the last tile); the streaming scan only if it is not all zero.
+    const bool any_gemm = gemm_ok && std::min<int64_t>(Q, L.q_chunk) >= kGemmMinQueries;
+    const bool use_bias = (lambda != 0.0f) || mask_dev != nullptr || any_gemm;
     if (use_bias && n > 0) {
-        const int64_t n_pad = round_up(n, 16);
+        const int64_t n_pad = round_up(n, ic::kGemmTile);
         const int grid = (int)std::min<int64_t>((n_pad + 255) / 256, 4096);
         hipLaunchKernelGGL(ic::make_bias, dim3(grid), dim3(256), 0, st,
                            (lambda != 0.0f) ? (const float *)index->util : (const float *)nullptr, mask_dev,
@@ -314,10 +418,14 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
 
     for (int64_t q0 = 0; q0 < Q; q0 += L.q_chunk) {
         const int qc = (int)std::min<int64_t>(L.q_chunk, Q - q0);
-        const int qg_idx = qc <= 16 ? 0 : (qc <= 32 ? 1 : 2);
+        const bool gemm = gemm_ok && qc >= kGemmMinQueries;
+        const int qg_idx = gemm ? 2 : (qc <= 16 ? 0 : (qc <= 32 ? 1 : 2));
         const int qb_rows = 16 << qg_idx;
-        const int nqb = (qc + qb_rows - 1) / qb_rows;
-        const int q_pad = nqb * qb_rows;
+        const int nqb = (qc + qb_rows - 1) / qb_rows;                      // blocks of the streaming scan
+        const int nqb_gemm = (qc + ic::kGemmTile - 1) / ic::kGemmTile;     // blocks of the tiled scan
+        const int q_pad = gemm ? nqb_gemm * ic::kGemmTile : nqb * qb_rows;
+        float *out_s = out_scores_dev + q0 * (int64_t)k;
+        int64_t *out_i = out_ids_dev + q0 * (int64_t)k;
 
         // a2: unit-normalise the queries and write them in the store's format
         {
@@ -333,106 +441,131 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
                                    (const float *)nullptr, (float *)nullptr);
         }
 
-        // a3-a5: similarity, score epilogue and per-slice partial top-k
-        int S = 0;
-        if (n > 0) {
-            ic::ScanArgs a;
-            a.store = index->rows;
-            a.n = n;
-            a.row_bytes = L.row_bytes;
-            a.row_scale = index->scale;
-            a.bias = use_bias ? index->bias : (const float *)index->consts;
-            a.bias_stride = use_bias ? 1 : 0;
-            a.qbuf = index->qbuf;
-            a.q_scale = index->qscale;
-            a.Q = qc;
-            a.k = k;
-            a.cap = cap;
-            a.regions = index->regions;
-            a.counts = index->counts;
-            a.pilot_out = index->pilot_keys;
-            a.thr_init = nullptr;
-            a.tile_mul = 1;
-
-            // Threshold pilot: a pass over a strided sample of the tiles that keeps the best
-            // score per (query, slice); the k-th largest of a query's slice maxima is reached
-            // by at least k rows, so the full scan may start from it.
-            if (qc >= kPilotMinQueries && ntiles >= kPilotMinTiles) {
-                ic::ScanArgs p = a;
-                p.S = kPilotSlices;
-                p.tile_mul = (int)std::min<int64_t>(64, ntiles / (kPilotSlices * 8));
-                kScanTable[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
-                ic::MergeArgs m;
-                m.src = index->pilot_keys;
-                m.q_stride = kPilotSlices;
-                m.seg_stride = 1;
-                m.seg_cap = 1;
-                m.seg_counts = nullptr;
-                m.nseg = kPilotSlices;
-                m.segs_per_wg = kPilotSlices;
-                m.k = k;
-                m.dst = nullptr;
-                m.out_scores = nullptr;
-                m.out_ids = nullptr;
-                m.kth_out = index->thr_init;
-                hipLaunchKernelGGL(ic::merge_lists, dim3(qc, 1), dim3(256), 0, st, m);
-                a.thr_init = index->thr_init;
-            }
-
-            // one workgroup per slice and query block; by default as many as are resident at once
-            // (two per compute unit by registers, fewer when the candidate regions fill the LDS)
-            int budget = index->slice_budget;
-            if (budget == 0) {
-                const size_t lds = ic::scan_lds_bytes(1 << qg_idx, cap);
-                const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
-                budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
-            }
-            S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
-            a.S = S;
-            const bool timed = index->timing && index->events_used + 2 <= kMaxTimedEvents;
-            if (timed) {
-                while (index->events.size() < index->events_used + 2) {
-                    hipEvent_t e;
-                    if (hipEventCreate(&e) != hipSuccess) return IC_ERR_DEVICE;
-                    index->events.push_back(e);
-                }
-                (void)hipEventRecord(index->events[index->events_used], st);
-            }
-            kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
-            if (timed) {
-                (void)hipEventRecord(index->events[index->events_used + 1], st);
-                index->events_used += 2;
-            }
+        if (n == 0) {  // nothing to scan: the merge of zero segments writes the padding rows
+            ic::MergeArgs m{};
+            m.src = index->regions;
+            m.q_stride = 0;
+            m.seg_stride = cap;
+            m.seg_cap = cap;
+            m.seg_counts = index->counts;
+            m.nseg = 0;
+            m.segs_per_wg = 1;
+            run_merge(index, m, qc, k, out_s, out_i, nullptr);
+            continue;
         }
 
-        // a6: merge the S candidate regions of every query
-        ic::MergeArgs m;
-        m.k = k;
-        m.kth_out = nullptr;
-        m.out_scores = out_scores_dev + q0 * (int64_t)k;
-        m.out_ids = out_ids_dev + q0 * (int64_t)k;
+        // a3-a5: similarity, score epilogue and selection
+        ic::ScanArgs a;
+        a.store = index->rows;
+        a.n = n;
+        a.row_bytes = L.row_bytes;
+        a.row_scale = index->scale;
+        a.bias = use_bias ? index->bias : (const float *)index->consts;
+        a.bias_stride = use_bias ? 1 : 0;
+        a.qbuf = index->qbuf;
+        a.q_scale = index->qscale;
+        a.Q = qc;
+        a.k = k;
+        a.cap = cap;
+        a.regions = index->regions;
+        a.counts = index->counts;
+        a.pilot_out = index->pilot_keys;
+        a.thr_init = nullptr;
+        a.redo = nullptr;
+        a.tile_mul = 1;
+
+        // Threshold pilot: a pass over a strided sample of the tiles that keeps the best score
+        // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
+        // k rows, so the full scan may start from it.
+        if (pilot_ok && qc >= kPilotMinQueries) {
+            ic::ScanArgs p = a;
+            p.S = kPilotSlices;
+            p.tile_mul = (int)std::min<int64_t>(64, ntiles / (kPilotSlices * 8));
+            kScanTable[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
+            ic::MergeArgs m{};
+            m.src = index->pilot_keys;
+            m.q_stride = kPilotSlices;
+            m.seg_stride = kPilotSlices;
+            m.seg_cap = kPilotSlices;
+            m.nseg = 1;
+            m.segs_per_wg = 1;
+            m.k = k;
+            m.kth_out = index->thr_init;
+            hipLaunchKernelGGL(ic::merge_lists, dim3(qc, 1), dim3(256), 0, st, m);
+            a.thr_init = index->thr_init;
+        }
+
+        // slices of the streaming scan: one workgroup per slice and query block; by default as
+        // many as are resident at once (two per compute unit by registers, fewer when the
+        // candidate regions fill the LDS)
+        int budget = index->slice_budget;
+        if (budget == 0) {
+            const size_t lds = ic::scan_lds_bytes(1 << qg_idx, cap);
+            const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
+            budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
+        }
+        const int S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
+        a.S = S;
+        Timer timer(index);
+
+        if (gemm) {
+            const int gcap = index->gemm_list_cap_override ? index->gemm_list_cap_override : gemm_list_cap(k);
+            const int nblk64 = (qc + 63) / 64;
+            hipLaunchKernelGGL(ic::gemm_reset, dim3((qc + 255) / 256), dim3(256), 0, st, index->gcount, qc,
+                               index->redo, nblk64);
+            ic::GemmArgs g;
+            g.store = index->rows;
+            g.n = n;
+            g.row_bytes = L.row_bytes;
+            g.row_scale = index->scale;
+            g.bias = index->bias;
+            g.qbuf = index->qbuf;
+            g.q_scale = index->qscale;
+            g.Q = qc;
+            g.thr_init = index->thr_init;
+            g.glist = index->glist;
+            g.gcap = gcap;
+            g.gcount = index->gcount;
+            g.redo = index->redo;
+            g.nqb = nqb_gemm;
+            g.ntiles = (n + ic::kGemmTile - 1) / ic::kGemmTile;
+            g.gq = 1;  // query-block groups: enough that a group's blocks stay in an XCD's L2
+            while (g.gq < 8 && (size_t)((nqb_gemm + g.gq - 1) / g.gq) * ic::kGemmTile * L.row_bytes > kL2Share) g.gq *= 2;
+            if (!timer.start()) return IC_ERR_DEVICE;
+            if (et == 0) launch_gemm<0>(std::max(8, index->compute_units / 8 * 8), st, g);
+            else launch_gemm<1>(std::max(8, index->compute_units / 8 * 8), st, g);
+            timer.stop();
+
+            // blocks whose candidate lists overflowed are redone by the streaming scan
+            a.redo = index->redo;
+            kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
+
+            ic::MergeArgs m{};
+            m.src = index->glist;
+            m.q_stride = gcap;
+            m.seg_cap = std::min(gcap, kGemmListSeg);
+            m.seg_stride = m.seg_cap;
+            m.total_counts = index->gcount;
+            m.nseg = (gcap + m.seg_cap - 1) / m.seg_cap;
+            m.segs_per_wg = 1;
+            run_merge(index, m, qc, k, out_s, out_i, nullptr);
+        } else {
+            if (!timer.start()) return IC_ERR_DEVICE;
+            kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
+            timer.stop();
+        }
+
+        // a6: merge the S candidate regions of every query (after the tiled scan: only the
+        // blocks that were redone)
+        ic::MergeArgs m{};
         m.src = index->regions;
         m.q_stride = (int64_t)S * cap;
         m.seg_stride = cap;
         m.seg_cap = cap;
         m.seg_counts = index->counts;
         m.nseg = S;
-        m.segs_per_wg = ic::kMergeKeys / cap;
-        uint64_t *ping = index->list_a, *pong = index->list_b;
-        for (;;) {
-            const int G = std::max(1, (m.nseg + m.segs_per_wg - 1) / m.segs_per_wg);
-            m.dst = (G == 1) ? nullptr : ping;
-            hipLaunchKernelGGL(ic::merge_lists, dim3(qc, G), dim3(256), 0, st, m);
-            if (G == 1) break;
-            m.src = ping;
-            m.q_stride = (int64_t)G * k;
-            m.seg_stride = k;
-            m.seg_cap = k;
-            m.seg_counts = nullptr;
-            m.nseg = G;
-            m.segs_per_wg = ic::kMergeKeys / k;
-            std::swap(ping, pong);
-        }
+        m.segs_per_wg = std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
+        run_merge(index, m, qc, k, out_s, out_i, gemm ? index->redo : nullptr);
     }
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     return IC_OK;

@@ -92,12 +92,15 @@ def test_library_exports_every_declared_symbol():
 def test_workspace_bytes_arithmetic():
     import paper_2501_12689_amd as pkg
     w = pkg.ic_workspace_bytes
-    base = w(768, pkg.STORE_BF16, 1_000_000, 64, 64)
-    more = w(768, pkg.STORE_BF16, 2_000_000, 64, 64)
-    # one more million rows: 1536 B row + 4 B utility + 4 B score bias each (up to alignment)
-    assert abs((more - base) - 1_000_000 * (1536 + 4 + 4)) <= 1024
-    f8 = w(1024, pkg.STORE_FP8_E4M3, 2_000_000, 64, 64) - w(1024, pkg.STORE_FP8_E4M3, 1_000_000, 64, 64)
-    assert abs(f8 - 1_000_000 * (1024 + 4 + 4 + 4)) <= 1024      # + per-row scale
+    M = 1 << 20                       # capacities are padded to whole 256-row tiles
+    base = w(768, pkg.STORE_BF16, M, 64, 64)
+    more = w(768, pkg.STORE_BF16, 2 * M, 64, 64)
+    # M more rows: 1536 B row + 4 B utility + 4 B score bias each (up to alignment)
+    assert abs((more - base) - M * (1536 + 4 + 4)) <= 1024
+    f8 = w(1024, pkg.STORE_FP8_E4M3, 2 * M, 64, 64) - w(1024, pkg.STORE_FP8_E4M3, M, 64, 64)
+    assert abs(f8 - M * (1024 + 4 + 4 + 4)) <= 1024      # + per-row scale
+    # large batches add the per-query candidate lists of the tiled scan
+    assert w(768, pkg.STORE_BF16, M, 4096, 16) > w(768, pkg.STORE_BF16, M, 64, 16) + 4096 * 2048 * 8
     # rows pad to 128 B: d = 100 bf16 -> 256 B
     a = w(100, pkg.STORE_BF16, 1 << 20, 64, 64) - w(100, pkg.STORE_BF16, 1 << 19, 64, 64)
     assert abs(a - (1 << 19) * (256 + 4 + 4)) <= 1024
