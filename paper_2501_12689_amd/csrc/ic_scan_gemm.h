@@ -9,11 +9,13 @@
 //     walks the dimension in stages of 128 bytes per row.  Both operands of a stage (512 rows x
 //     128 B = 64 KB) are copied from global memory straight into LDS (global_load_lds_dwordx4: no
 //     staging registers, no LDS store instructions); LDS is double buffered, one barrier per stage.
-//   * LDS layout: row-major, 128 B per row, the eight 16-byte granules of a row XOR-swizzled with
-//     the row index so that the 32 lanes of an operand read hit distinct banks.  A direct load
-//     writes lane l of a wavefront to (wave's LDS base + 16*l), i.e. 8 rows x 8 granules per
-//     instruction, so the swizzle is applied on the global side: lane l fetches granule
-//     (l%8) ^ (l/8) of its row.
+//   * LDS layout: row-major, 128 B per row; granule g (16 bytes) of row r sits at position
+//     g ^ ((r / 2) % 8).  A 128-bit LDS read is served 16 lanes at a time, and 16 consecutive rows
+//     then cover all sixteen 16-byte slots of the 256-byte bank span exactly once (keying the
+//     swizzle on r % 8 made rows r and r + 8 collide: measured 47 % of LDS cycles in conflict).
+//     A direct load writes lane l of a wavefront to (wave's LDS base + 16*l), i.e. 8 rows x 8
+//     granules per instruction, so the swizzle is applied on the global side: the lane fetches
+//     the granule that belongs at its position.
 //   * Operand mapping: lane (r = lane%32, h = lane/32) reads granule 2*p + h of row r for step p;
 //     rows and queries use the same mapping, so each MFMA pairs equal coordinates (the order of
 //     the coordinates inside a dot product is free).  bf16: one v_mfma_f32_32x32x16_bf16 per
@@ -107,13 +109,14 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
     // ---- copy plan: one direct load moves 8 rows x 128 B per wavefront; wavefront w covers rows
     // 8w .. 8w+7 of every group of 32 rows; 16 loads per stage (8 for the rows, 8 for the queries)
     const int crow = tid >> 3;                       // row within a group of 32
-    const int cg_src = (lane & 7) ^ ((lane >> 3) & 7);  // granule fetched, so that it lands swizzled
+    const int cg_src = (lane & 7) ^ ((4 * w + (lane >> 4)) & 7);  // granule fetched: position ^ ((row / 2) % 8)
     const uint32_t q_off = (uint32_t)(crow * a.row_bytes + cg_src * 16);
 
     // ---- operand read plan: byte offset inside a stage of this lane's granule for step p
     uint32_t frag_off[4];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) frag_off[p] = (uint32_t)(r32 * kGemmStageBytes + (((2 * p + h) ^ (r32 & 7)) * 16));
+    for (int p = 0; p < 4; ++p)
+        frag_off[p] = (uint32_t)(r32 * kGemmStageBytes + (((2 * p + h) ^ ((r32 >> 1) & 7)) * 16));
     const uint32_t a_base = (uint32_t)(wm * 128 * kGemmStageBytes);
     const uint32_t b_base = (uint32_t)((kGemmTile + wn * 128) * kGemmStageBytes);
 
@@ -127,20 +130,19 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         uint8_t *dst = lds + buf * kStage + w * (8 * kGemmStageBytes);  // wave-uniform
         const uint8_t *ra = rows_base + ks * kGemmStageBytes;           // uniform
         const uint8_t *qa = q_base + ks * kGemmStageBytes;              // uniform
-        // address = uniform base (stage, row group) + one 32-bit per-thread offset shared by all groups
+        // address = uniform base (stage, row group) + a 32-bit per-thread offset.  The offsets are
+        // rebuilt at every use (a few VALU ops) so that none of them lives in a register across the
+        // stages; the empty asm keeps the compiler from hoisting them out of the loop.
+        int c0 = crow;
+        asm volatile("" : "+v"(c0));
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int i = 2 * part + u;
-            if (last == kGemmTile - 1) {
-                __builtin_amdgcn_global_load_lds((gptr_t)(ra + (size_t)i * 32 * a.row_bytes + q_off),
-                                                 (lptr_t)(dst + i * 32 * kGemmStageBytes), 16, 0, 0);
-            } else {  // ragged last tile: rows past the end re-read the last valid row; their bias is -inf
-                int r = crow + 32 * i;
-                r = r < last ? r : last;
-                __builtin_amdgcn_global_load_lds((gptr_t)(ra + (uint32_t)(r * a.row_bytes + cg_src * 16)),
-                                                 (lptr_t)(dst + i * 32 * kGemmStageBytes), 16, 0, 0);
-            }
-            __builtin_amdgcn_global_load_lds((gptr_t)(qa + (size_t)i * 32 * a.row_bytes + q_off),
+            int r = c0 + 32 * i;
+            r = r < last ? r : last;  // ragged last tile: rows past the end re-read the last valid row (bias -inf)
+            __builtin_amdgcn_global_load_lds((gptr_t)(ra + (uint32_t)(r * a.row_bytes + cg_src * 16)),
+                                             (lptr_t)(dst + i * 32 * kGemmStageBytes), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(qa + (size_t)i * 32 * a.row_bytes + (uint32_t)(c0 * a.row_bytes + cg_src * 16)),
                                              (lptr_t)(dst + (kGemmTile + i * 32) * kGemmStageBytes), 16, 0, 0);
         }
     };
