@@ -34,6 +34,8 @@
 //     If a candidate list overflows, its block of 64 queries is flagged and redone by the
 //     streaming scan, so the result stays exact whatever the data.
 #pragma once
+#include <type_traits>
+
 #include "ic_common.h"
 
 namespace ic {
@@ -41,7 +43,9 @@ namespace ic {
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kGemmTile = 256;        // rows and queries per output tile
-constexpr int kGemmStageBytes = 128;  // bytes of every row per stage
+constexpr int kGemmStageBytes = 128;  // rows are padded to a multiple of this
+constexpr int kGemmHalfBytes = 64;    // bytes of every row per pipeline step
+constexpr int kGemmSlots = 4;         // LDS ring: pipeline steps resident or in flight
 
 struct GemmArgs {
     const uint8_t *store;    // [n] rows, row_bytes apart
@@ -73,7 +77,7 @@ struct HitEntry {   // 16 scores of one lane's block that reached its query's th
 };
 
 constexpr size_t gemm_lds_bytes() {
-    return (size_t)2 * 2 * kGemmTile * kGemmStageBytes + 2 * kGemmTile * 4 + (size_t)kGemmPark * 12 + 16 +
+    return (size_t)kGemmSlots * 2 * kGemmTile * kGemmHalfBytes + 2 * kGemmTile * 4 + (size_t)kGemmPark * 12 + 16 +
            (size_t)kGemmHits * sizeof(HitEntry);
 }
 
@@ -81,8 +85,8 @@ template <int ET>
 __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
-    constexpr int kStage = 2 * kGemmTile * kGemmStageBytes;  // 64 KB: rows then queries
-    float *bias_t = reinterpret_cast<float *>(lds + 2 * kStage);
+    constexpr int kSlot = 2 * kGemmTile * kGemmHalfBytes;  // 32 KB: 256 rows then 256 queries, 64 B each
+    float *bias_t = reinterpret_cast<float *>(lds + kGemmSlots * kSlot);
     float *scale_t = bias_t + kGemmTile;
     uint64_t *park_key = reinterpret_cast<uint64_t *>(scale_t + kGemmTile);  // [kGemmPark]
     uint32_t *park_q = reinterpret_cast<uint32_t *>(park_key + kGemmPark);    // [kGemmPark]
@@ -95,7 +99,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w >> 1, wn = w & 1;
     const int r32 = lane & 31, h = lane >> 5;
-    const int nst = a.row_bytes / kGemmStageBytes;
+    const int nhs = a.row_bytes / kGemmHalfBytes;  // pipeline steps per tile (even, >= 2)
 
     // ---- which tiles this workgroup walks
     const int xcd = blockIdx.x & 7;
@@ -105,55 +109,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
     const int64_t nr_x = (a.ntiles - rclass + gr - 1) / gr;           // row tiles of this XCD
     const int64_t work = (int64_t)nq_x * nr_x;
     const int64_t step = gridDim.x >> 3;
-
-    // ---- copy plan: one direct load moves 8 rows x 128 B per wavefront; wavefront w covers rows
-    // 8w .. 8w+7 of every group of 32 rows; 16 loads per stage (8 for the rows, 8 for the queries)
-    const int crow = tid >> 3;                       // row within a group of 32
-    const int cg_src = (lane & 7) ^ ((4 * w + (lane >> 4)) & 7);  // granule fetched: position ^ ((row / 2) % 8)
-    const uint32_t q_off = (uint32_t)(crow * a.row_bytes + cg_src * 16);
-
-    // ---- operand read plan: byte offset inside a stage of this lane's granule for step p
-    uint32_t frag_off[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-        frag_off[p] = (uint32_t)(r32 * kGemmStageBytes + (((2 * p + h) ^ ((r32 >> 1) & 7)) * 16));
-    const uint32_t a_base = (uint32_t)(wm * 128 * kGemmStageBytes);
-    const uint32_t b_base = (uint32_t)((kGemmTile + wn * 128) * kGemmStageBytes);
-
-    typedef const void __attribute__((address_space(1))) *gptr_t;
-    typedef void __attribute__((address_space(3))) *lptr_t;
-    // Request quarter `part` (0..3) of stage ks of a tile into LDS buffer buf: 2 of the 8 row
-    // groups and 2 of the 8 query groups.  The quarters are issued between the MFMA steps of the
-    // previous stage so that the memory instructions hide behind the matrix work.  Completion is
-    // awaited with vmcnt.
-    auto load_quarter = [&](const uint8_t *rows_base, int last, const uint8_t *q_base, int ks, int buf, int part) {
-        uint8_t *dst = lds + buf * kStage + w * (8 * kGemmStageBytes);  // wave-uniform
-        const uint8_t *ra = rows_base + ks * kGemmStageBytes;           // uniform
-        const uint8_t *qa = q_base + ks * kGemmStageBytes;              // uniform
-        // address = uniform base (stage, row group) + a 32-bit per-thread offset.  The offsets are
-        // rebuilt at every use (a few VALU ops) so that none of them lives in a register across the
-        // stages; the empty asm keeps the compiler from hoisting them out of the loop.
-        int c0 = crow;
-        asm volatile("" : "+v"(c0));
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int i = 2 * part + u;
-            int r = c0 + 32 * i;
-            r = r < last ? r : last;  // ragged last tile: rows past the end re-read the last valid row (bias -inf)
-            __builtin_amdgcn_global_load_lds((gptr_t)(ra + (uint32_t)(r * a.row_bytes + cg_src * 16)),
-                                             (lptr_t)(dst + i * 32 * kGemmStageBytes), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(qa + (size_t)i * 32 * a.row_bytes + (uint32_t)(c0 * a.row_bytes + cg_src * 16)),
-                                             (lptr_t)(dst + (kGemmTile + i * 32) * kGemmStageBytes), 16, 0, 0);
-        }
-    };
-    auto load_stage = [&](const uint8_t *rows_base, int last, const uint8_t *q_base, int ks, int buf) {
-#pragma unroll
-        for (int part = 0; part < 4; ++part) load_quarter(rows_base, last, q_base, ks, buf, part);
-    };
-    auto await_stage = [&]() {  // every direct load issued so far has landed, and all wavefronts know it
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-    };
+    if ((int64_t)(blockIdx.x >> 3) >= work) return;  // nothing to do: no load is ever issued
 
     // Everything a tile needs to address its operands.
     struct Tile {
@@ -171,7 +127,91 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         const int64_t last = a.n - 1 - t.row0;
         t.last = (int)(last < kGemmTile - 1 ? last : kGemmTile - 1);
     };
+    // job = rl * nq_x + ql walks query blocks fastest; the pair is advanced without divisions
+    struct Walk {
+        int ql;
+        int64_t rl;
+        int64_t job;
+    };
+    const int step_q = (int)(step % nq_x);
+    const int64_t step_r = step / nq_x;
+    auto walk_next = [&](Walk &x) {
+        x.job += step;
+        x.ql += step_q;
+        x.rl += step_r;
+        if (x.ql >= nq_x) {
+            x.ql -= nq_x;
+            x.rl += 1;
+        }
+    };
+    Walk tw;  // the tile being computed
+    tw.job = blockIdx.x >> 3;
+    tw.ql = (int)(tw.job % nq_x);
+    tw.rl = tw.job / nq_x;
 
+    // ---- copy plan.  One direct load moves 16 rows x 64 B per wavefront: lane l lands at the
+    // wavefront's LDS base + 16*l, i.e. row l/4, position l%4, and therefore fetches granule
+    // (l%4) ^ ((row/4)%4).  Per pipeline step a wavefront issues 8 loads: row groups w, w+4, w+8,
+    // w+12 (of 16 rows each) of the cached rows and the same groups of the queries.
+    typedef const void __attribute__((address_space(1))) *gptr_t;
+    typedef void __attribute__((address_space(3))) *lptr_t;
+    const int crow = lane >> 2;
+    const int cg = (lane & 3) ^ ((lane >> 4) & 3);
+    uint32_t off_q[4], off_r[4];  // byte offsets from a tile's first query / first row (rows clamped per tile)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) off_q[u] = (uint32_t)(((w + 4 * u) * 16 + crow) * a.row_bytes + cg * 16);
+    Walk cw = tw;   // the load cursor runs kGemmSlots pipeline steps ahead of the computation
+    const uint8_t *c_rows, *c_q;
+    int c_hs;
+    auto cursor_tile = [&]() {
+        Tile t;
+        locate(cw.ql, cw.rl, t);
+        c_rows = t.rows_base;
+        c_q = t.q_base;
+        c_hs = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            int r = (w + 4 * u) * 16 + crow;
+            r = r < t.last ? r : t.last;  // ragged last tile: rows past the end re-read the last valid row (bias -inf)
+            off_r[u] = (uint32_t)(r * a.row_bytes + cg * 16);
+        }
+    };
+    auto issue = [&](int slot) {  // request the cursor's step into an LDS slot
+        uint8_t *dst = lds + slot * kSlot + w * (16 * kGemmHalfBytes);  // wave-uniform
+        const uint8_t *ra = c_rows + c_hs * kGemmHalfBytes;
+        const uint8_t *qa = c_q + c_hs * kGemmHalfBytes;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(ra + off_r[u]), (lptr_t)(dst + u * 64 * kGemmHalfBytes), 16, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(qa + off_q[u]),
+                                             (lptr_t)(dst + (kGemmTile + u * 64) * kGemmHalfBytes), 16, 0, 0);
+    };
+    auto advance = [&]() {  // move the cursor one step on (uniform control flow)
+        if (++c_hs == nhs) {
+            // past the last tile the same tile is requested again; those loads are never used
+            if (cw.job + step < work) walk_next(cw);
+            cursor_tile();
+        }
+    };
+
+    // ---- operand read plan: byte offset inside a slot of this lane's granule for step p (0, 1):
+    // granule 2*p + h of row r sits at position (2*p + h) ^ ((r / 4) % 4)
+    uint32_t frag_off[2];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+        frag_off[p] = (uint32_t)(r32 * kGemmHalfBytes + (((2 * p + h) ^ ((r32 >> 2) & 3)) * 16));
+    const uint32_t a_base = (uint32_t)(wm * 128 * kGemmHalfBytes);
+    const uint32_t b_base = (uint32_t)((kGemmTile + wn * 128) * kGemmHalfBytes);
+
+    // Barrier for data exchanged through LDS only: unlike __syncthreads() it does not wait for this
+    // wavefront's outstanding global loads and stores (the direct loads in flight, the list flushes).
+    auto lds_barrier = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
     // append one candidate to its query's list (slot from the query's atomic counter)
     auto append_global = [&](uint32_t q, uint64_t key, int pos) {
         if (pos < a.gcap) a.glist[(size_t)q * a.gcap + pos] = key;
@@ -182,19 +222,21 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         *hit_n = 0u;
     }
 
-    // job = rl * nq_x + ql walks query blocks fastest; the pair is advanced without divisions
-    int64_t job = blockIdx.x >> 3;
-    const int step_q = nq_x > 0 ? (int)(step % nq_x) : 0;
-    const int64_t step_r = nq_x > 0 ? step / nq_x : 0;
-    int ql = nq_x > 0 ? (int)(job % nq_x) : 0;
-    int64_t rl = nq_x > 0 ? job / nq_x : 0;
-    Tile cur;
-    if (job < work) {
-        locate(ql, rl, cur);
-        load_stage(cur.rows_base, cur.last, cur.q_base, 0, 0);
+    // fill the ring: the first kGemmSlots steps of this workgroup's work
+    cursor_tile();
+#pragma unroll
+    for (int sl = 0; sl < kGemmSlots; ++sl) {
+        issue(sl);
+        advance();
     }
-    for (; job < work; job += step) {
-        locate(ql, rl, cur);
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    int hslot = 0;  // ring slot of the step being computed
+    for (; tw.job < work; walk_next(tw)) {
+        Tile cur;
+        locate(tw.ql, tw.rl, cur);
         const int qb = cur.qb;
         const int64_t row0 = cur.row0;
 
@@ -206,76 +248,111 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-        await_stage();  // stage 0 was requested before the previous tile's epilogue
-
         // What the previous tile parked is flushed during this tile: slots are claimed (one atomic
-        // per candidate) at the start of the last stage, where no wait for direct loads follows,
-        // and the keys are written after it.
-        const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);
+        // per candidate) in the tile's last step and the keys are written after it.
         int fl_pos[2] = {-1, -1};
+        uint64_t thr_raw[4];
+        float qs[4];
+        f32x4 bias_r = {0.f, 0.f, 0.f, 0.f}, scale_r = {1.f, 1.f, 1.f, 1.f};
 
-        for (int ks = 0; ks < nst; ++ks) {
-            const int buf = ks & 1;
-            const bool more = ks + 1 < nst;
-            if (!more) {
+        i32x4 fa[2][4], fb[2][4];
+        auto read_frags = [&](int slot, int p, i32x4 *xa, i32x4 *xb) {
+            const uint8_t *sa = lds + slot * kSlot + a_base + frag_off[p];
+            const uint8_t *sb = lds + slot * kSlot + b_base + frag_off[p];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xa[i] = *reinterpret_cast<const i32x4 *>(sa + i * 32 * kGemmHalfBytes);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xb[j] = *reinterpret_cast<const i32x4 *>(sb + j * 32 * kGemmHalfBytes);
+        };
+        auto mfma16 = [&](const i32x4 *xa, const i32x4 *xb) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (ET == 0) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, xa[i]), __builtin_bit_cast(bf16x8, xb[j]), acc[i][j], 0, 0, 0);
+                    } else {
+                        const i64x2 x = __builtin_bit_cast(i64x2, xa[i]);
+                        const i64x2 y = __builtin_bit_cast(i64x2, xb[j]);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.x, y.x, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.y, y.y, acc[i][j], 0, 0, 0);
+                    }
+                }
+        };
+        constexpr int kPer = (ET == 0) ? 1 : 2;  // MFMA instructions per accumulator tile and step
+
+        // One pipeline step = 64 B of every row = two MFMA steps of 16 accumulator tiles.
+        //   first half:  MFMAs on the operands read earlier; the second half's operands are read
+        //   barrier:     this wavefront's loads for the next step have landed (at most the two
+        //                younger steps are still in flight) and it has read all it needs from the
+        //                current slot; after the barrier that holds for every wavefront
+        //   second half: the current slot is refilled with the step kGemmSlots ahead, the next
+        //                step's first operands are read, MFMAs on the second operands
+        // Nothing waits for a load younger than three steps, and LDS reads are always one MFMA
+        // step ahead of their use.
+        auto half = [&](auto last_c) {
+            constexpr bool kLast = decltype(last_c)::value;
+            read_frags(hslot, 1, fa[1], fb[1]);
+            mfma16(fa[0], fb[0]);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 8 * kPer, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            if (kLast) {
+                // what the epilogue needs from global memory, and the slots of the parked candidates
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
+                    if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
+                    thr_raw[j] = a.thr_init[q];
+                    qs[j] = (ET == 1) ? a.q_scale[q] : 1.0f;
+                }
+                if (tid < 64) {
+                    bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
+                    if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
+                }
+                const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const uint32_t e = tid + 256 * u;
                     if (e < parked) fl_pos[u] = atomicAdd(a.gcount + park_q[e], 1);
                 }
-            }
-            const uint8_t *sa = lds + buf * kStage + a_base;
-            const uint8_t *sb = lds + buf * kStage + b_base;
-            // operands of step p+1 are read while the 16 MFMAs of step p run
-            i32x4 fa[2][4], fb[2][4];
-            auto read_frags = [&](int p, i32x4 *xa, i32x4 *xb) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) xa[i] = *reinterpret_cast<const i32x4 *>(sa + i * 32 * kGemmStageBytes + frag_off[p]);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) xb[j] = *reinterpret_cast<const i32x4 *>(sb + j * 32 * kGemmStageBytes + frag_off[p]);
-            };
-            read_frags(0, fa[0], fb[0]);
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                if (more) load_quarter(cur.rows_base, cur.last, cur.q_base, ks + 1, buf ^ 1, p);
-                if (p + 1 < 4) read_frags(p + 1, fa[(p + 1) & 1], fb[(p + 1) & 1]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        if (ET == 0) {
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                __builtin_bit_cast(bf16x8, fa[p & 1][i]), __builtin_bit_cast(bf16x8, fb[p & 1][j]),
-                                acc[i][j], 0, 0, 0);
-                        } else {
-                            const i64x2 x = __builtin_bit_cast(i64x2, fa[p & 1][i]);
-                            const i64x2 y = __builtin_bit_cast(i64x2, fb[p & 1][j]);
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.x, y.x, acc[i][j], 0, 0, 0);
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.y, y.y, acc[i][j], 0, 0, 0);
-                        }
-                    }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (more) await_stage();
-            else __syncthreads();
-        }
-
-        // what the epilogue needs from global memory is requested only now, so that nothing but the
-        // accumulators and the operand pipeline lives in registers across the stages
-        uint64_t thr_raw[4];
-        float qs[4];
+            issue(hslot);
+            const int nslot = (hslot + 1) & (kGemmSlots - 1);
+            if (!kLast) read_frags(nslot, 0, fa[0], fb[0]);
+            mfma16(fa[1], fb[1]);
+            if (!kLast) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
-            if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
-            thr_raw[j] = a.thr_init[q];
-            qs[j] = (ET == 1) ? a.q_scale[q] : 1.0f;
-        }
-        f32x4 bias_r = {0.f, 0.f, 0.f, 0.f}, scale_r = {1.f, 1.f, 1.f, 1.f};
-        if (tid < 64) {
-            bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
-            if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
-        }
+                for (int g = 0; g < 8; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x008, 8 * kPer, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            advance();
+            hslot = nslot;
+        };
+        read_frags(hslot, 0, fa[0], fb[0]);  // the step landed before the barrier of the step before it
+        for (int hs = 0; hs + 1 < nhs; ++hs) half(std::false_type{});
+        half(std::true_type{});
+
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const uint32_t e = tid + 256 * u;
@@ -285,23 +362,12 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
             *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
             if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
         }
-        __syncthreads();   // the parked entries have been read by their flushers
+        lds_barrier();   // the parked entries have been read by their flushers
         if (tid == 0) {
             *park_n = 0u;
             *hit_n = 0u;
         }
-        __syncthreads();
-
-        // request the next tile's first stage; it lands while this tile's scores are examined
-        ql += step_q;
-        rl += step_r;
-        if (ql >= nq_x) {
-            ql -= nq_x;
-            rl += 1;
-        }
-        const bool have_next = job + step < work;
-        Tile nxt;
-        if (have_next) locate(ql, rl, nxt);
+        lds_barrier();
 
         // ---- epilogue: score = dot * scales + bias, compare with the query's threshold
         // accumulator v of tile (i, j) is row wm*128 + i*32 + 8*(v/4) + 4*h + v%4, query column j*32 + r32
@@ -316,8 +382,6 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         // threshold (about 17 lanes per tile) copies the block's scores to a small LDS list.
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            // a quarter of the next tile's first stage per block row: it lands while the scores are examined
-            if (have_next) load_quarter(nxt.rows_base, nxt.last, nxt.q_base, 0, 0, i);
             f32x4 bs[4], rs[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -352,7 +416,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
                 }
             }
         }
-        __syncthreads();
+        lds_barrier();
         // pass 2: the listed blocks, one score per thread; what passes the exact key test is parked
         {
             const uint32_t nh = min(*hit_n, (uint32_t)kGemmHits);
@@ -376,7 +440,9 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         }
     }
 
-    // the last tile's parked candidates
+    // the last tile's parked candidates; the direct loads of the unused extra stage must have landed
+    // before the workgroup gives up its LDS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);
     for (uint32_t e = tid; e < parked; e += 256) {
