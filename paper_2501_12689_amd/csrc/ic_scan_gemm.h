@@ -46,6 +46,7 @@ constexpr int kGemmTile = 256;        // rows and queries per output tile
 constexpr int kGemmStageBytes = 128;  // rows are padded to a multiple of this
 constexpr int kGemmHalfBytes = 64;    // bytes of every row per pipeline step
 constexpr int kGemmSlots = 4;         // LDS ring: pipeline steps resident or in flight
+constexpr int kGemmThreads = 512;     // 8 wavefronts, two per SIMD: one issues MFMAs while the other issues loads
 
 struct GemmArgs {
     const uint8_t *store;    // [n] rows, row_bytes apart
@@ -66,7 +67,7 @@ struct GemmArgs {
     int gq;                  // XCD mapping: query-block groups (1, 2, 4 or 8); 8/gq row classes
 };
 
-constexpr int kGemmPark = 512;        // candidates a workgroup can park per tile
+constexpr int kGemmPark = 512;        // candidates a workgroup can park per tile (one flusher thread each)
 constexpr int kGemmHits = 96;         // blocks of 16 scores a workgroup can list per tile
 
 struct HitEntry {   // 16 scores of one lane's block that reached its query's threshold
@@ -82,7 +83,7 @@ constexpr size_t gemm_lds_bytes() {
 }
 
 template <int ET>
-__global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
+__global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
     constexpr int kSlot = 2 * kGemmTile * kGemmHalfBytes;  // 32 KB: 256 rows then 256 queries, 64 B each
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w >> 1, wn = w & 1;
+    const int wm = w >> 1, wn = w & 1;  // 4 x 2 wavefronts of 64 rows x 128 queries
     const int r32 = lane & 31, h = lane >> 5;
     const int nhs = a.row_bytes / kGemmHalfBytes;  // pipeline steps per tile (even, >= 2)
 
@@ -151,15 +152,15 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
 
     // ---- copy plan.  One direct load moves 16 rows x 64 B per wavefront: lane l lands at the
     // wavefront's LDS base + 16*l, i.e. row l/4, position l%4, and therefore fetches granule
-    // (l%4) ^ ((row/4)%4).  Per pipeline step a wavefront issues 8 loads: row groups w, w+4, w+8,
-    // w+12 (of 16 rows each) of the cached rows and the same groups of the queries.
+    // (l%4) ^ ((row/4)%4).  Per pipeline step a wavefront issues 4 loads: row groups w and w+8 (of 16
+    // rows each) of the cached rows and the same groups of the queries.
     typedef const void __attribute__((address_space(1))) *gptr_t;
     typedef void __attribute__((address_space(3))) *lptr_t;
     const int crow = lane >> 2;
     const int cg = (lane & 3) ^ ((lane >> 4) & 3);
-    uint32_t off_q[4], off_r[4];  // byte offsets from a tile's first query / first row (rows clamped per tile)
+    uint32_t off_q[2], off_r[2];  // byte offsets from a tile's first query / first row (rows clamped per tile)
 #pragma unroll
-    for (int u = 0; u < 4; ++u) off_q[u] = (uint32_t)(((w + 4 * u) * 16 + crow) * a.row_bytes + cg * 16);
+    for (int u = 0; u < 2; ++u) off_q[u] = (uint32_t)(((w + 8 * u) * 16 + crow) * a.row_bytes + cg * 16);
     Walk cw = tw;   // the load cursor runs kGemmSlots pipeline steps ahead of the computation
     const uint8_t *c_rows, *c_q;
     int c_hs;
@@ -170,8 +171,8 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         c_q = t.q_base;
         c_hs = 0;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int r = (w + 4 * u) * 16 + crow;
+        for (int u = 0; u < 2; ++u) {
+            int r = (w + 8 * u) * 16 + crow;
             r = r < t.last ? r : t.last;  // ragged last tile: rows past the end re-read the last valid row (bias -inf)
             off_r[u] = (uint32_t)(r * a.row_bytes + cg * 16);
         }
@@ -181,12 +182,12 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         const uint8_t *ra = c_rows + c_hs * kGemmHalfBytes;
         const uint8_t *qa = c_q + c_hs * kGemmHalfBytes;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            __builtin_amdgcn_global_load_lds((gptr_t)(ra + off_r[u]), (lptr_t)(dst + u * 64 * kGemmHalfBytes), 16, 0, 0);
+        for (int u = 0; u < 2; ++u)
+            __builtin_amdgcn_global_load_lds((gptr_t)(ra + off_r[u]), (lptr_t)(dst + u * 128 * kGemmHalfBytes), 16, 0, 0);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 2; ++u)
             __builtin_amdgcn_global_load_lds((gptr_t)(qa + off_q[u]),
-                                             (lptr_t)(dst + (kGemmTile + u * 64) * kGemmHalfBytes), 16, 0, 0);
+                                             (lptr_t)(dst + (kGemmTile + u * 128) * kGemmHalfBytes), 16, 0, 0);
     };
     auto advance = [&]() {  // move the cursor one step on (uniform control flow)
         if (++c_hs == nhs) {
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
 #pragma unroll
     for (int p = 0; p < 2; ++p)
         frag_off[p] = (uint32_t)(r32 * kGemmHalfBytes + (((2 * p + h) ^ ((r32 >> 2) & 3)) * 16));
-    const uint32_t a_base = (uint32_t)(wm * 128 * kGemmHalfBytes);
+    const uint32_t a_base = (uint32_t)(wm * 64 * kGemmHalfBytes);
     const uint32_t b_base = (uint32_t)((kGemmTile + wn * 128) * kGemmHalfBytes);
 
     // Barrier for data exchanged through LDS only: unlike __syncthreads() it does not wait for this
@@ -240,9 +241,9 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         const int qb = cur.qb;
         const int64_t row0 = cur.row0;
 
-        f32x16 acc[4][4];
+        f32x16 acc[2][4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -250,23 +251,23 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
 
         // What the previous tile parked is flushed during this tile: slots are claimed (one atomic
         // per candidate) in the tile's last step and the keys are written after it.
-        int fl_pos[2] = {-1, -1};
+        int fl_pos = -1;
         uint64_t thr_raw[4];
         float qs[4];
         f32x4 bias_r = {0.f, 0.f, 0.f, 0.f}, scale_r = {1.f, 1.f, 1.f, 1.f};
 
-        i32x4 fa[2][4], fb[2][4];
+        i32x4 fa[2][2], fb[2][4];
         auto read_frags = [&](int slot, int p, i32x4 *xa, i32x4 *xb) {
             const uint8_t *sa = lds + slot * kSlot + a_base + frag_off[p];
             const uint8_t *sb = lds + slot * kSlot + b_base + frag_off[p];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) xa[i] = *reinterpret_cast<const i32x4 *>(sa + i * 32 * kGemmHalfBytes);
+            for (int i = 0; i < 2; ++i) xa[i] = *reinterpret_cast<const i32x4 *>(sa + i * 32 * kGemmHalfBytes);
 #pragma unroll
             for (int j = 0; j < 4; ++j) xb[j] = *reinterpret_cast<const i32x4 *>(sb + j * 32 * kGemmHalfBytes);
         };
-        auto mfma16 = [&](const i32x4 *xa, const i32x4 *xb) {
+        auto mfma8 = [&](const i32x4 *xa, const i32x4 *xb) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     if (ET == 0) {
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         };
         constexpr int kPer = (ET == 0) ? 1 : 2;  // MFMA instructions per accumulator tile and step
 
-        // One pipeline step = 64 B of every row = two MFMA steps of 16 accumulator tiles.
+        // One pipeline step = 64 B of every row = two MFMA steps of 8 accumulator tiles.
         //   first half:  MFMAs on the operands read earlier; the second half's operands are read
         //   barrier:     this wavefront's loads for the next step have landed (at most the two
         //                younger steps are still in flight) and it has read all it needs from the
@@ -294,15 +295,15 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         auto half = [&](auto last_c) {
             constexpr bool kLast = decltype(last_c)::value;
             read_frags(hslot, 1, fa[1], fb[1]);
-            mfma16(fa[0], fb[0]);
+            mfma8(fa[0], fb[0]);
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {
+            for (int g = 0; g < 6; ++g) {
                 __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);  // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // LDS read
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, 8 * kPer, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2 * kPer, 0);
             __builtin_amdgcn_sched_barrier(0);
-            asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
@@ -320,30 +321,25 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
                     if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
                 }
                 const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const uint32_t e = tid + 256 * u;
-                    if (e < parked) fl_pos[u] = atomicAdd(a.gcount + park_q[e], 1);
-                }
+                if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
             issue(hslot);
             const int nslot = (hslot + 1) & (kGemmSlots - 1);
             if (!kLast) read_frags(nslot, 0, fa[0], fb[0]);
-            mfma16(fa[1], fb[1]);
+            mfma8(fa[1], fb[1]);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                if (!kLast) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
             if (!kLast) {
 #pragma unroll
-                for (int g = 0; g < 8; ++g) {
+                for (int g = 0; g < 2; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
-            } else {
-                __builtin_amdgcn_sched_group_barrier(0x008, 8 * kPer, 0);
-            }
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
-                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
             }
             __builtin_amdgcn_sched_barrier(0);
             advance();
@@ -353,11 +349,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         for (int hs = 0; hs + 1 < nhs; ++hs) half(std::false_type{});
         half(std::true_type{});
 
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const uint32_t e = tid + 256 * u;
-            if (fl_pos[u] >= 0) append_global(park_q[e], park_key[e], fl_pos[u]);
-        }
+        if (fl_pos >= 0) append_global(park_q[tid], park_key[tid], fl_pos);
         if (tid < 64) {  // every wavefront is past the previous tile's epilogue (it has met this tile's barriers)
             *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
             if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
@@ -370,7 +362,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         lds_barrier();
 
         // ---- epilogue: score = dot * scales + bias, compare with the query's threshold
-        // accumulator v of tile (i, j) is row wm*128 + i*32 + 8*(v/4) + 4*h + v%4, query column j*32 + r32
+        // accumulator v of tile (i, j) is row wm*64 + i*32 + 8*(v/4) + 4*h + v%4, query column wn*128 + j*32 + r32
         float thr_s[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -378,14 +370,14 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
             thr_s[j] = thr_raw[j] > kKeyFloor ? key_score(thr_raw[j]) : -INFINITY;
             if (q >= a.Q) thr_s[j] = INFINITY;  // padding query: nothing passes
         }
-        // pass 1: 16 blocks of 16 scores per lane.  A lane whose block reaches the query's
+        // pass 1: 8 blocks of 16 scores per lane.  A lane whose block reaches the query's
         // threshold (about 17 lanes per tile) copies the block's scores to a small LDS list.
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             f32x4 bs[4], rs[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int rr = wm * 128 + i * 32 + 8 * u + 4 * h;
+                const int rr = wm * 64 + i * 32 + 8 * u + 4 * h;
                 bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
                 if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
             }
@@ -408,7 +400,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                         for (int u = 0; u < 4; ++u) e.sc[u] = sc[u];
                         e.q = (uint32_t)q;
-                        e.row = (uint32_t)(row0 + wm * 128 + i * 32 + 4 * h);  // row of score 0; score v: + 8*(v/4) + v%4
+                        e.row = (uint32_t)(row0 + wm * 64 + i * 32 + 4 * h);  // row of score 0; score v: + 8*(v/4) + v%4
                         e.thr = thr_raw[j];
                     } else {
                         a.redo[q >> 6] = 1;  // list full (never in practice): the block is redone exactly
@@ -421,7 +413,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
         {
             const uint32_t nh = min(*hit_n, (uint32_t)kGemmHits);
             const int v = tid & 15;
-            for (uint32_t e = tid >> 4; e < nh; e += 16) {
+            for (uint32_t e = tid >> 4; e < nh; e += kGemmThreads / 16) {
                 const HitEntry &he = hits[e];
                 const float x = he.sc[v >> 2][v & 3];
                 const uint64_t t0 = he.thr;
@@ -445,7 +437,7 @@ __global__ __launch_bounds__(256) void scan_gemm(const GemmArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);
-    for (uint32_t e = tid; e < parked; e += 256) {
+    for (uint32_t e = tid; e < parked; e += kGemmThreads) {
         const uint32_t q = park_q[e];
         append_global(q, park_key[e], atomicAdd(a.gcount + q, 1));
     }

@@ -137,7 +137,7 @@ void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
         hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::gemm_lds_bytes());
     (void)allowed;
-    hipLaunchKernelGGL((ic::scan_gemm<ET>), dim3(grid), dim3(256), ic::gemm_lds_bytes(), st, a);
+    hipLaunchKernelGGL((ic::scan_gemm<ET>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(), st, a);
 }
 
 }  // namespace
