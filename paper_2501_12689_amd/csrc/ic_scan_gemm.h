@@ -64,6 +64,9 @@ struct GemmArgs {
     int32_t *redo;           // [ceil(Q/64)] set to 1 when a list of the block overflowed
     int nqb;                 // query blocks of 256
     int64_t ntiles;          // row tiles of 256
+    uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over a sampled tile, id = tile)
+    int pilot_stride;
+    int64_t tile_stride;     // the t-th row tile of the walk is tile t * tile_stride of the store (1: every tile)
     int gq;                  // XCD mapping: query-block groups (1, 2, 4 or 8); 8/gq row classes
 };
 
@@ -82,7 +85,7 @@ constexpr size_t gemm_lds_bytes() {
            (size_t)kGemmHits * sizeof(HitEntry);
 }
 
-template <int ET>
+template <int ET, bool PILOT>
 __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
@@ -122,7 +125,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     };
     auto locate = [&](int ql, int64_t rl, Tile &t) {  // ql-th query block, rl-th row tile of this XCD
         t.qb = qgroup + a.gq * ql;
-        t.row0 = (rclass + gr * rl) * kGemmTile;
+        t.row0 = (rclass + gr * rl) * a.tile_stride * kGemmTile;
         t.rows_base = a.store + t.row0 * a.row_bytes;
         t.q_base = a.qbuf + (size_t)t.qb * kGemmTile * a.row_bytes;
         const int64_t last = a.n - 1 - t.row0;
@@ -223,18 +226,28 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         *hit_n = 0u;
     }
 
-    // fill the ring: the first kGemmSlots steps of this workgroup's work
+    // The two wavefronts of a SIMD (w and w + 4) issue their direct loads half a step apart, so
+    // that one of them always has nothing but MFMAs and LDS reads to issue: the first four refill
+    // a slot right after the barrier that frees it, the other four during the first half of the
+    // following step.
+    const bool late = w >= 4;
+    // fill the ring: the first kGemmSlots steps of this workgroup's work (the late wavefronts
+    // request their share of the last one during the first step)
     cursor_tile();
 #pragma unroll
     for (int sl = 0; sl < kGemmSlots; ++sl) {
-        issue(sl);
-        advance();
+        if (sl + 1 < kGemmSlots || !late) {
+            issue(sl);
+            advance();
+        }
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
     int hslot = 0;  // ring slot of the step being computed
+    auto run_tiles = [&](auto late_c) {
+    constexpr bool kLate = decltype(late_c)::value;
     for (; tw.job < work; walk_next(tw)) {
         Tile cur;
         locate(tw.ql, tw.rl, cur);
@@ -294,15 +307,18 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         // step ahead of their use.
         auto half = [&](auto last_c) {
             constexpr bool kLast = decltype(last_c)::value;
+            if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1));  // the slot freed by the previous barrier
             read_frags(hslot, 1, fa[1], fb[1]);
             mfma8(fa[0], fb[0]);
 #pragma unroll
             for (int g = 0; g < 6; ++g) {
                 __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);  // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // LDS read
+                if (kLate && g < 4) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 2 * kPer, 0);
             __builtin_amdgcn_sched_barrier(0);
+            if (kLate) advance();
             asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
@@ -313,25 +329,27 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 for (int j = 0; j < 4; ++j) {
                     int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
                     if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
-                    thr_raw[j] = a.thr_init[q];
+                    thr_raw[j] = PILOT ? 0ull : a.thr_init[q];
                     qs[j] = (ET == 1) ? a.q_scale[q] : 1.0f;
                 }
                 if (tid < 64) {
                     bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
                     if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
                 }
-                const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
-                if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
+                if (!PILOT) {
+                    const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
+                    if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            issue(hslot);
+            if (!kLate) issue(hslot);
             const int nslot = (hslot + 1) & (kGemmSlots - 1);
             if (!kLast) read_frags(nslot, 0, fa[0], fb[0]);
             mfma8(fa[1], fb[1]);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
-                __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                if (!kLate) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
                 if (!kLast) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
             if (!kLast) {
@@ -342,13 +360,54 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            advance();
+            if (!kLate) advance();
             hslot = nslot;
         };
         read_frags(hslot, 0, fa[0], fb[0]);  // the step landed before the barrier of the step before it
         for (int hs = 0; hs + 1 < nhs; ++hs) half(std::false_type{});
         half(std::true_type{});
 
+        if (PILOT) {
+            // Pilot launch: the best score of every query over this tile's rows, combined into the
+            // query's slice (sampled tile modulo pilot_stride) with a 64-bit atomic maximum.
+            uint32_t *pmax = reinterpret_cast<uint32_t *>(hits);  // [kGemmTile] order-preserving score bits
+            if (tid < 64) {
+                *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
+                if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
+            }
+            if (tid < kGemmTile) pmax[tid] = 0u;
+            lds_barrier();
+            float best[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                f32x4 bs[4], rs[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int rr = wm * 64 + i * 32 + 8 * u + 4 * h;
+                    bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
+                    if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
+                                                  : acc[i][j][v] + bs[v >> 2][v & 3];
+                        best[j] = fmaxf(best[j], x);
+                    }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) atomicMax(pmax + wn * 128 + j * 32 + r32, ord_of_score(best[j]));
+            lds_barrier();
+            if (tid < kGemmTile) {
+                const int q = qb * kGemmTile + tid;
+                const uint32_t slice = (uint32_t)((row0 / (a.tile_stride * kGemmTile)) % a.pilot_stride);
+                if (q < a.Q)
+                    atomicMax(reinterpret_cast<unsigned long long *>(a.pilot_out) + (size_t)q * a.pilot_stride + slice,
+                              ((unsigned long long)pmax[tid] << 32) | (unsigned long long)(0xFFFFFFFFu - slice));
+            }
+            continue;  // the K-loop barriers of the next tile separate these reads from the next reset
+        }
         if (fl_pos >= 0) append_global(park_q[tid], park_key[tid], fl_pos);
         if (tid < 64) {  // every wavefront is past the previous tile's epilogue (it has met this tile's barriers)
             *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
@@ -431,6 +490,9 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             }
         }
     }
+    };
+    if (late) run_tiles(std::true_type{});
+    else run_tiles(std::false_type{});
 
     // the last tile's parked candidates; the direct loads of the unused extra stage must have landed
     // before the workgroup gives up its LDS
@@ -441,6 +503,12 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         const uint32_t q = park_q[e];
         append_global(q, park_key[e], atomicAdd(a.gcount + q, 1));
     }
+}
+
+// Zero the slice maxima before a pilot launch of scan_gemm.
+__global__ void gemm_pilot_reset(uint64_t *keys, int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) keys[i] = 0ull;
 }
 
 // Zero the per-query counters and the redo flags before a scan_gemm launch.

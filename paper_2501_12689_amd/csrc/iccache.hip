@@ -131,13 +131,13 @@ const ScanFn kScanTable[2][2][3][8] = {
 };
 #undef IC_SCAN_ROW
 
-template <int ET>
+template <int ET, bool PILOT>
 void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
     static const hipError_t allowed =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET, PILOT>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::gemm_lds_bytes());
     (void)allowed;
-    hipLaunchKernelGGL((ic::scan_gemm<ET>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(), st, a);
+    hipLaunchKernelGGL((ic::scan_gemm<ET, PILOT>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(), st, a);
 }
 
 }  // namespace
@@ -477,7 +477,50 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
         // Threshold pilot: a pass over a strided sample of the tiles that keeps the best score
         // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
         // k rows, so the full scan may start from it.
-        if (pilot_ok && qc >= kPilotMinQueries) {
+        const int gemm_grid = std::max(8, index->compute_units / 8 * 8);
+        ic::GemmArgs g{};
+        if (gemm) {
+            g.store = index->rows;
+            g.n = n;
+            g.row_bytes = L.row_bytes;
+            g.row_scale = index->scale;
+            g.bias = index->bias;
+            g.qbuf = index->qbuf;
+            g.q_scale = index->qscale;
+            g.Q = qc;
+            g.nqb = nqb_gemm;
+            g.ntiles = (n + ic::kGemmTile - 1) / ic::kGemmTile;
+            g.tile_stride = 1;
+            g.gq = 1;  // query-block groups: enough that a group's blocks stay in an XCD's L2
+            while (g.gq < 8 && (size_t)((nqb_gemm + g.gq - 1) / g.gq) * ic::kGemmTile * L.row_bytes > kL2Share) g.gq *= 2;
+        }
+        if (gemm) {
+            // The pilot of the tiled scan is the tiled scan itself over every 32nd (small k: 64th)
+            // tile of 256 rows; a slice is the set of sampled tiles with the same index modulo
+            // kPilotSlices.  Starting from its threshold about stride * k rows per query pass.
+            ic::GemmArgs p = g;
+            const int64_t want = (k <= 16) ? 64 : 32;
+            p.tile_stride = std::max<int64_t>(1, std::min<int64_t>(want, g.ntiles / kPilotSlices));
+            p.ntiles = (g.ntiles + p.tile_stride - 1) / p.tile_stride;
+            p.pilot_out = index->pilot_keys;
+            p.pilot_stride = kPilotSlices;
+            const int64_t nkeys = (int64_t)qc * kPilotSlices;
+            hipLaunchKernelGGL(ic::gemm_pilot_reset, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, st,
+                               index->pilot_keys, nkeys);
+            if (et == 0) launch_gemm<0, true>(gemm_grid, st, p);
+            else launch_gemm<1, true>(gemm_grid, st, p);
+            ic::MergeArgs m{};
+            m.src = index->pilot_keys;
+            m.q_stride = kPilotSlices;
+            m.seg_stride = kPilotSlices;
+            m.seg_cap = (int)std::min<int64_t>(kPilotSlices, p.ntiles);
+            m.nseg = 1;
+            m.segs_per_wg = 1;
+            m.k = k;
+            m.kth_out = index->thr_init;
+            hipLaunchKernelGGL(ic::merge_lists, dim3(qc, 1), dim3(256), 0, st, m);
+            a.thr_init = index->thr_init;
+        } else if (pilot_ok && qc >= kPilotMinQueries) {
             ic::ScanArgs p = a;
             p.S = kPilotSlices;
             p.tile_mul = (int)std::min<int64_t>(64, ntiles / (kPilotSlices * 8));
@@ -513,27 +556,14 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
             const int nblk64 = (qc + 63) / 64;
             hipLaunchKernelGGL(ic::gemm_reset, dim3((qc + 255) / 256), dim3(256), 0, st, index->gcount, qc,
                                index->redo, nblk64);
-            ic::GemmArgs g;
-            g.store = index->rows;
-            g.n = n;
-            g.row_bytes = L.row_bytes;
-            g.row_scale = index->scale;
-            g.bias = index->bias;
-            g.qbuf = index->qbuf;
-            g.q_scale = index->qscale;
-            g.Q = qc;
             g.thr_init = index->thr_init;
             g.glist = index->glist;
             g.gcap = gcap;
             g.gcount = index->gcount;
             g.redo = index->redo;
-            g.nqb = nqb_gemm;
-            g.ntiles = (n + ic::kGemmTile - 1) / ic::kGemmTile;
-            g.gq = 1;  // query-block groups: enough that a group's blocks stay in an XCD's L2
-            while (g.gq < 8 && (size_t)((nqb_gemm + g.gq - 1) / g.gq) * ic::kGemmTile * L.row_bytes > kL2Share) g.gq *= 2;
             if (!timer.start()) return IC_ERR_DEVICE;
-            if (et == 0) launch_gemm<0>(std::max(8, index->compute_units / 8 * 8), st, g);
-            else launch_gemm<1>(std::max(8, index->compute_units / 8 * 8), st, g);
+            if (et == 0) launch_gemm<0, false>(gemm_grid, st, g);
+            else launch_gemm<1, false>(gemm_grid, st, g);
             timer.stop();
 
             // blocks whose candidate lists overflowed are redone by the streaming scan
