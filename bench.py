@@ -9,6 +9,10 @@ merge.  The headline value is queries/s at Q = 64; Q = 1 and Q = 8 are reported
 in ``config.per_Q``.  Appending (normalise + quantise + store) happens once per
 example, not per batch; its rate is reported separately under ``append``.
 
+The matrix-core regime is timed as well (fewer steps, they are long): Q = 4096 on
+the same store (``config.per_Q["4096"]``) and the N = 4,000,000, d = 1024, k = 16
+configuration with utility and mask (``large_batch``, ``roofline_mfma``).
+
 Prints one JSON line.  ``roofline`` refers to the scan kernel, timed with HIP
 events on the library's stream inside the timed steps; ``cpu_baseline`` is the
 CPU reference timed on a bounded sample of the same workload.
@@ -24,6 +28,29 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+LARGE_Q = 4096
+
+
+def time_search(ix, torch, qd, k, lam, mask, out_s, out_i, warmup, steps):
+    """Time `steps` searches on resident inputs; returns (ms per step, scan kernel ms per launch, wall ms)."""
+    ix.set_timing(False)
+    for _ in range(warmup):
+        ix.search(qd, k, lam, mask, out_s, out_i)
+    torch.cuda.synchronize()
+    ix.set_timing(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    # the library brackets every scan launch with events on this stream; nothing waits
+    for _ in range(steps):
+        ix.search(qd, k, lam, mask, out_s, out_i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    scan_ms, launches = ix.scan_time_ms()
+    ix.set_timing(False)
+    return e0.elapsed_time(e1) / steps, scan_ms / max(launches, 1), wall_ms / steps
 
 
 def main() -> int:
@@ -33,6 +60,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--rows", type=int, default=None, help="override N (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-large-batch", action="store_true", help="skip the Q = 4096 legs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies, so that a counter run over this "
+                         "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -50,8 +81,17 @@ def main() -> int:
     cfg = workloads.C3 if args.rows is None else workloads.C3.scaled(N=args.rows)
     wl = workloads.Workload(cfg, dev)
 
+    if args.copy_calibration:
+        x = torch.full((1 << 28,), 1.0, dtype=torch.float32, device=dev)   # 1 GiB
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        del x, y
+        torch.cuda.empty_cache()
+
     # ---- build the index (timed separately: a1 runs once per example)
-    ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, 64, cfg.k, dev)
+    ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, 64 if args.no_large_batch else LARGE_Q, cfg.k, dev)
     chunk = 16 * workloads.BLOCK
     append_ms, sample_rows = 0.0, None
     sample_n = min(cfg.N, 2 * chunk)
@@ -78,34 +118,69 @@ def main() -> int:
         qd = wl.queries(Q, batch=Q)
         out_s = torch.empty(Q, cfg.k, dtype=torch.float32, device=dev)
         out_i = torch.empty(Q, cfg.k, dtype=torch.int64, device=dev)
-        ix.set_timing(False)
-        for _ in range(args.warmup):
-            ix.search(qd, cfg.k, cfg.lam, None, out_s, out_i)
-        torch.cuda.synchronize()
-        ix.set_timing(True)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        # the library brackets every scan launch with events on this stream; nothing waits
-        for _ in range(args.steps):
-            ix.search(qd, cfg.k, cfg.lam, None, out_s, out_i)
-        e1.record()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3
-        scan_ms, launches = ix.scan_time_ms()
-        ix.set_timing(False)
-        ms = e0.elapsed_time(e1) / args.steps
-        scan = scan_ms / max(launches, 1)
+        ms, scan, wall = time_search(ix, torch, qd, cfg.k, cfg.lam, None, out_s, out_i, args.warmup, args.steps)
         per_q[str(Q)] = {
             "queries_per_s": Q / (ms * 1e-3),
             "ms_per_step": ms,
             "scan_kernel_ms": scan,
             "scan_GBps": store_bytes / (scan * 1e-3) / 1e9,
             "hbm_frac": store_bytes / (scan * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "wall_ms_per_step": wall_ms / args.steps,
+            "wall_ms_per_step": wall,
         }
         if Q == 64:
             headline = per_q[str(Q)]
+
+    # ---- matrix-core regime: Q = 4096 on the same store, then the N = 4M, d = 1024 configuration
+    large, roof_mfma = None, None
+    if not args.no_large_batch:
+        lsteps, lwarm = max(3, min(10, args.steps)), 2
+        Q = LARGE_Q
+        qd = wl.queries(Q, batch=Q)
+        out_s = torch.empty(Q, cfg.k, dtype=torch.float32, device=dev)
+        out_i = torch.empty(Q, cfg.k, dtype=torch.int64, device=dev)
+        ms, scan, wall = time_search(ix, torch, qd, cfg.k, cfg.lam, None, out_s, out_i, lwarm, lsteps)
+        flop = 2.0 * Q * cfg.N * cfg.d
+        per_q[str(Q)] = {
+            "queries_per_s": Q / (ms * 1e-3), "ms_per_step": ms, "steps": lsteps, "scan_kernel_ms": scan,
+            "scan_TFLOPs": flop / (scan * 1e-3) / 1e12,
+            "mfma_frac": flop / (scan * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall,
+        }
+        del qd, out_s, out_i
+    ix.close()
+    ix.arena = None
+    del ix
+    torch.cuda.empty_cache()
+    if not args.no_large_batch:
+        c4 = workloads.C4 if args.rows is None else workloads.C4.scaled(N=min(workloads.C4.N, args.rows))
+        wl4 = workloads.Workload(c4, dev)
+        ix4 = pkg.Index(c4.d, c4.N, pkg.STORE_BF16, c4.Q, c4.k, dev)
+        masks = []
+        for lo in range(0, c4.N, chunk):
+            n = min(chunk, c4.N - lo)
+            E, U, M = wl4.rows(lo, n)
+            ix4.append(E, U)
+            masks.append(M)
+            del E
+        mask4 = torch.cat(masks) if masks[0] is not None else None
+        qd = wl4.queries(c4.Q)
+        out_s = torch.empty(c4.Q, c4.k, dtype=torch.float32, device=dev)
+        out_i = torch.empty(c4.Q, c4.k, dtype=torch.int64, device=dev)
+        ms, scan, wall = time_search(ix4, torch, qd, c4.k, c4.lam, mask4, out_s, out_i, lwarm, lsteps)
+        flop = 2.0 * c4.Q * c4.N * c4.d
+        large = {
+            "workload": f"C4: N={c4.N} d={c4.d} bf16 store, {c4.clusters}-cluster mixture, Q={c4.Q}, k={c4.k}, "
+                        f"lambda={c4.lam}, {1.0 - c4.p_valid:.0%} masked rows",
+            "queries_per_s": c4.Q / (ms * 1e-3), "ms_per_step": ms, "steps": lsteps, "warmup": lwarm,
+            "scan_kernel_ms": scan, "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall,
+        }
+        ach = flop / (scan * 1e-3) / 1e12
+        roof_mfma = {
+            "bound": "mfma", "kernel": f"scan_gemm (bf16 MFMA contraction + fused threshold selection), Q={c4.Q}",
+            "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+            "traffic": None, "algorithmic_flops_per_launch": flop,
+        }
+        ix4.close()
 
     # ---- CPU reference on a bounded sample (rank 0, N = 1 only)
     cpu = None
@@ -151,6 +226,8 @@ def main() -> int:
             "algorithmic_bytes_per_launch": store_bytes,
         },
         "cpu_baseline": cpu,
+        "large_batch": large,
+        "roofline_mfma": roof_mfma,
     }
     print(json.dumps(line))
     return 0
