@@ -29,6 +29,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per Q = 64 scan launch on the N = 10M, d = 768 store, from two rocprofv3 counter runs
+# (FETCH_SIZE 7,501,007 KiB x 2.0000, WRITE_SIZE 3,726 KiB x 1.0000; the factors are what the same counters read
+# for a plain 1 GiB copy).  Valid for the scan_stream kernel as committed with profiles/scan_stream_c3_bf16.md;
+# set to None when that kernel changes until the counters are taken again.
+SCAN_TRAFFIC_BYTES_Q64 = (7_501_007 * (1_048_576 / 524_304) + 3_726) * 1024
 LARGE_Q = 4096
 
 
@@ -222,7 +227,7 @@ def main() -> int:
         "roofline": {
             "bound": "hbm", "kernel": "scan_stream (similarity + fused partial top-k), Q=64",
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": SCAN_TRAFFIC_BYTES_Q64 if args.rows is None else None,
             "algorithmic_bytes_per_launch": store_bytes,
         },
         "cpu_baseline": cpu,
