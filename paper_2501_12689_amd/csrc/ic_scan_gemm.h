@@ -4,35 +4,40 @@
 // streaming scan, for batches large enough that the matrix cores, not HBM, bound the work.
 //
 // Shape of the computation
-//   * One output tile = 256 rows x 256 queries over the whole embedding dimension.  A workgroup
-//     (4 wavefronts, 2 x 2, each 128 x 128 = 4 x 4 MFMA tiles of 32x32, 256 accumulator registers)
-//     walks the dimension in stages of 128 bytes per row.  Both operands of a stage (512 rows x
-//     128 B = 64 KB) are copied from global memory straight into LDS (global_load_lds_dwordx4: no
-//     staging registers, no LDS store instructions); LDS is double buffered, one barrier per stage.
-//   * LDS layout: row-major, 128 B per row; granule g (16 bytes) of row r sits at position
-//     g ^ ((r / 2) % 8).  A 128-bit LDS read is served 16 lanes at a time, and 16 consecutive rows
-//     then cover all sixteen 16-byte slots of the 256-byte bank span exactly once (keying the
-//     swizzle on r % 8 made rows r and r + 8 collide: measured 47 % of LDS cycles in conflict).
-//     A direct load writes lane l of a wavefront to (wave's LDS base + 16*l), i.e. 8 rows x 8
-//     granules per instruction, so the swizzle is applied on the global side: the lane fetches
-//     the granule that belongs at its position.
-//   * Operand mapping: lane (r = lane%32, h = lane/32) reads granule 2*p + h of row r for step p;
-//     rows and queries use the same mapping, so each MFMA pairs equal coordinates (the order of
-//     the coordinates inside a dot product is free).  bf16: one v_mfma_f32_32x32x16_bf16 per
-//     granule pair; fp8: two v_mfma_f32_32x32x16_fp8_fp8 (8 bytes each).
+//   * One output tile = 256 rows x 256 queries over the whole embedding dimension.  A workgroup has
+//     8 wavefronts (4 x 2, each 64 rows x 128 queries = 2 x 4 MFMA tiles of 32x32, 128 accumulator
+//     registers), two per SIMD: while one issues loads or LDS reads the other keeps the matrix pipe
+//     fed (with one wavefront per SIMD every direct load cost about 27 cycles of idle pipe).
+//   * A pipeline step is 64 bytes of every row of the tile (512 rows x 64 B = 32 KB).  An LDS ring
+//     of 4 slots holds the step being multiplied and up to three in flight.  Operands are copied
+//     from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS
+//     store instructions).  The wait before a step's barrier is counted (vmcnt): only the next
+//     step's loads must have landed, so a load has three steps to arrive.
+//   * LDS layout: row-major, 64 B per row; granule g (16 bytes) of row r sits at position
+//     g ^ ((r / 4) % 4).  A 128-bit LDS read is served 16 lanes at a time, and 16 consecutive rows
+//     then cover all sixteen 16-byte slots of the 256-byte bank span exactly once.  A direct load
+//     writes lane l of a wavefront to (wave's LDS base + 16*l), i.e. 16 rows x 4 granules per
+//     instruction, so the swizzle is applied on the global side: the lane fetches the granule that
+//     belongs at its position.
+//   * Operand mapping: lane (r = lane%32, h = lane/32) reads granule 2*p + h of row r for MFMA
+//     step p (0, 1); rows and queries use the same mapping, so each MFMA pairs equal coordinates
+//     (the order of the coordinates inside a dot product is free).  bf16: one
+//     v_mfma_f32_32x32x16_bf16 per granule pair; fp8: two v_mfma_f32_32x32x16_fp8_fp8 (8 bytes each).
 //   * Workgroups are persistent and XCD-aware: workgroup id modulo 8 is the XCD it runs on; an XCD
 //     owns a group of query blocks small enough to stay in its L2 and a class of row tiles, and
-//     walks query blocks fastest so that a row tile is used by consecutive tiles.
-//   * Selection: thresholds come from the pilot (a score that at least k rows reach, per query)
-//     and stay in registers.  A tile's 65,536 scores are compared 16 at a time (max, then one
-//     compare); a lane whose 16 scores reach the threshold copies them to an LDS list, the
-//     workgroup then tests those few blocks exactly, one score per thread, and parks what passes
-//     (about 17 candidates per tile) in a second LDS list.  That list
-//     is flushed to the queries' candidate lists in global memory (slot = atomic counter per
-//     query) while the next tile is being computed: the atomics are issued at the start of that
-//     tile and their results used after its last stage, so nobody waits for an L2 round trip.
-//     If a candidate list overflows, its block of 64 queries is flagged and redone by the
-//     streaming scan, so the result stays exact whatever the data.
+//     walks query blocks fastest so that a row tile is used by consecutive tiles.  The load
+//     pipeline runs across tile boundaries: a cursor walks the same tile sequence 4 steps ahead.
+//   * Selection: thresholds come from the pilot (a score that at least k rows reach, per query).
+//     A tile's 65,536 scores are compared 16 at a time (max, then one compare); a lane whose 16
+//     scores reach the threshold copies them to an LDS list, the workgroup then tests those few
+//     blocks exactly, one score per thread, and parks what passes (about 17 candidates per tile)
+//     in a second LDS list.  That list is flushed to the queries' candidate lists in global
+//     memory (slot = atomic counter per query) while the next tile is being computed: the atomics
+//     are issued in that tile's last step and their results used after it, so nobody waits for an
+//     L2 round trip.  If a candidate list overflows, its block of 64 queries is flagged and redone
+//     by the streaming scan, so the result stays exact whatever the data.
+//   * Pilot launches (PILOT = true) run the same pipeline over a strided sample of the row tiles
+//     and keep, per query and slice, only the best score.
 #pragma once
 #include <type_traits>
 
