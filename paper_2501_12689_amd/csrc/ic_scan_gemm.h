@@ -46,6 +46,7 @@
 namespace ic {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 constexpr int kGemmTile = 256;        // rows and queries per output tile
 constexpr int kGemmStageBytes = 128;  // rows are padded to a multiple of this
@@ -368,9 +369,98 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             if (!kLate) advance();
             hslot = nslot;
         };
-        read_frags(hslot, 0, fa[0], fb[0]);  // the step landed before the barrier of the step before it
-        for (int hs = 0; hs + 1 < nhs; ++hs) half(std::false_type{});
-        half(std::true_type{});
+        // fp8: one v_mfma_f32_32x32x64_f8f6f4 per accumulator tile and step (twice the flops per
+        // cycle of the 32x32x16 forms).  Its operand is 32 bytes per lane: both granules (p = 0, 1)
+        // of the lane's row, so all 12 operand reads of a step are done one step ahead, into the
+        // other half of a double buffer, and the step's 8 MFMAs sit 4 before and 4 after the barrier.
+        i32x8 ga[2][2], gb[2][4];
+        auto read_frags8 = [&](int slot, i32x8 *xa, i32x8 *xb) {
+            const uint8_t *sa = lds + slot * kSlot + a_base;
+            const uint8_t *sb = lds + slot * kSlot + b_base;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                xa[i].lo = *reinterpret_cast<const i32x4 *>(sa + frag_off[0] + i * 32 * kGemmHalfBytes);
+                xa[i].hi = *reinterpret_cast<const i32x4 *>(sa + frag_off[1] + i * 32 * kGemmHalfBytes);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                xb[j].lo = *reinterpret_cast<const i32x4 *>(sb + frag_off[0] + j * 32 * kGemmHalfBytes);
+                xb[j].hi = *reinterpret_cast<const i32x4 *>(sb + frag_off[1] + j * 32 * kGemmHalfBytes);
+            }
+        };
+        auto half8 = [&](auto last_c, auto par_c) {
+            constexpr bool kLast = decltype(last_c)::value;
+            constexpr int kPar = decltype(par_c)::value;
+            if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1));  // the slot freed by the previous barrier
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ga[kPar][i], gb[kPar][j], acc[i][j], 0, 0, 0,
+                                                                                 0, 0, 0);
+            if (kLate) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (kLate) advance();
+            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            if (kLast) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
+                    if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
+                    thr_raw[j] = PILOT ? 0ull : a.thr_init[q];
+                    qs[j] = a.q_scale[q];
+                }
+                if (tid < 64) {
+                    bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
+                    scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
+                }
+                if (!PILOT) {
+                    const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
+                    if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (!kLate) issue(hslot);
+            const int nslot = (hslot + 1) & (kGemmSlots - 1);
+            if (!kLast) read_frags8(nslot, ga[kPar ^ 1], gb[kPar ^ 1]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 2; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ga[kPar][i], gb[kPar][j], acc[i][j], 0, 0, 0,
+                                                                                 0, 0, 0);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (!kLast) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      // LDS reads
+                if (!kLate) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);      // direct load
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (!kLate) advance();
+            hslot = nslot;
+        };
+        if constexpr (ET == 0) {
+            read_frags(hslot, 0, fa[0], fb[0]);  // the step landed before the barrier of the step before it
+            for (int hs = 0; hs + 1 < nhs; ++hs) half(std::false_type{});
+            half(std::true_type{});
+        } else {
+            read_frags8(hslot, ga[0], gb[0]);
+            for (int hs = 0; hs + 2 < nhs; hs += 2) {  // the number of steps is even
+                half8(std::false_type{}, std::integral_constant<int, 0>{});
+                half8(std::false_type{}, std::integral_constant<int, 1>{});
+            }
+            half8(std::false_type{}, std::integral_constant<int, 0>{});
+            half8(std::true_type{}, std::integral_constant<int, 1>{});
+        }
 
         if (PILOT) {
             // Pilot launch: the best score of every query over this tile's rows, combined into the
