@@ -196,15 +196,18 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     const int64_t last_row = a.n - 1;
     const int64_t S = a.S;
 
-    // Everything a tile needs from global memory, requested two tiles ahead.  The loads
-    // are unconditional (indices are clamped), so the only waits in the loop are counted
-    // waits for the oldest stage.
+    // Everything a tile needs from global memory, requested kStages - 1 tiles ahead: two tiles for
+    // long rows, four when a wavefront's share of a row is at most 4 chunks (the stages are small
+    // then, and short rows need more tiles in flight to cover the memory latency).  The loads are
+    // unconditional (indices are clamped), so the only waits in the loop are counted waits for the
+    // oldest stage.
+    constexpr int kStages = (CPW <= 4) ? 5 : 3;
     struct Stage {
         i32x4 rows[CPW];
         f32x4 bias;
         f32x4 rsc;
     };
-    Stage st[3];
+    Stage st[kStages];
     auto load_stage = [&](int64_t t, Stage &x) {
         const int64_t tt = (t < ntiles ? t : ntiles - 1) * tile_mul;
         int64_t r = tt * 16 + r16;
@@ -217,20 +220,20 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
         if (ET == 1) x.rsc = *reinterpret_cast<const f32x4 *>(a.row_scale + i0);
     };
 
-    // The loop body is unrolled by three so that the stage buffers are addressed statically.
-    // Tiles past the end of the slice (when its tile count is not a multiple of three) are
+    // The loop body is unrolled by kStages so that the stage buffers are addressed statically.
+    // Tiles past the end of the slice (when its tile count is not a multiple of kStages) are
     // processed like any other: their loads are clamped and all their rows fall past
     // last_row, so they contribute no candidate.
     int64_t t = s;
-    load_stage(t, st[0]);
-    load_stage(t + S, st[1]);
+#pragma unroll
+    for (int b = 0; b + 1 < kStages; ++b) load_stage(t + b * S, st[b]);
     const int64_t my_tiles = (s < ntiles) ? (ntiles - s + S - 1) / S : 0;
 
-    for (int64_t it = 0; it < my_tiles; it += 3) {
+    for (int64_t it = 0; it < my_tiles; it += kStages) {
 #pragma unroll
-        for (int b = 0; b < 3; ++b) {
+        for (int b = 0; b < kStages; ++b) {
             {
-                load_stage(t + 2 * S, st[(b + 2) % 3]);
+                load_stage(t + (kStages - 1) * S, st[(b + kStages - 1) % kStages]);
                 const Stage &cur = st[b];
 
                 f32x4 acc[QG];

@@ -39,6 +39,11 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 // Sized so that, with 64 queries per workgroup, two workgroups fit the LDS of a compute unit
 // for k <= 64 (64 * 112 * 8 B = 56 KB of regions each).
 inline int region_cap(int k) { return k <= 32 ? 64 : (k <= 64 ? 112 : ic::kMaxCap); }
+// With 64 queries per workgroup and 64 < k <= 100 the regions are kept at 112 keys as well, so that
+// two workgroups still fit a compute unit; the slack above k is small, which is fine because such
+// batches start from the pilot's threshold and a slice rarely sees more than a few dozen candidates
+// (a region that does fill up is compacted more often, nothing else changes).
+inline int region_cap_for(int k, int qg_idx) { return (qg_idx == 2 && k > 64 && k <= 100) ? 112 : region_cap(k); }
 
 // Keys of the per-query candidate list of the MFMA-tiled scan.  Starting from the pilot's
 // threshold about 64*k rows pass (the pilot sees every 64th tile); over 4096 queries with
@@ -390,7 +395,6 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
     const int et = (index->store == IC_STORE_BF16) ? 0 : 1;
     const int nchunks = L.row_bytes / 64;
     const int cpw = (nchunks + ic::kScanWaves - 1) / ic::kScanWaves;
-    const int cap = region_cap(k);
     const int64_t n = index->n;
     const int64_t ntiles = (n + 15) / 16;
     hipStream_t st = index->stream;
@@ -421,6 +425,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
         const bool gemm = gemm_ok && qc >= kGemmMinQueries;
         const int qg_idx = gemm ? 2 : (qc <= 16 ? 0 : (qc <= 32 ? 1 : 2));
         const int qb_rows = 16 << qg_idx;
+        const int cap = region_cap_for(k, qg_idx);
         const int nqb = (qc + qb_rows - 1) / qb_rows;                      // blocks of the streaming scan
         const int nqb_gemm = (qc + ic::kGemmTile - 1) / ic::kGemmTile;     // blocks of the tiled scan
         const int q_pad = gemm ? nqb_gemm * ic::kGemmTile : nqb * qb_rows;
