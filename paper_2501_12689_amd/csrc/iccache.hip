@@ -31,7 +31,7 @@ constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on que
 constexpr int kGemmMinQueries = 128;        // batches from here on use the MFMA-tiled scan
 constexpr int kGemmListSeg = ic::kMergeKeys;  // candidate lists are merged in segments of this many keys
 constexpr int kGemmListMax = 8 * kGemmListSeg;
-constexpr size_t kL2Share = 2u << 20;       // query-block bytes an XCD keeps resident in its L2
+constexpr size_t kL2Share = 4u << 20;       // query-block bytes of a group of XCDs (measured: 4 MB beats 2 MB and 8 MB by about 3 %)
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
