@@ -11,7 +11,9 @@ example, not per batch; its rate is reported separately under ``append``.
 
 The matrix-core regime is timed as well (fewer steps, they are long): Q = 4096 on
 the same store (``config.per_Q["4096"]``) and the N = 4,000,000, d = 1024, k = 16
-configuration with utility and mask (``large_batch``, ``roofline_mfma``).
+configuration with utility and mask (``large_batch``, ``roofline_mfma``); and the fp8 store
+(N = 20,000,000, d = 1024, k = 100, built by appends of 100,000 rows) at Q = 1, 64 and 4096
+(``fp8_store``).
 
 Prints one JSON line.  ``roofline`` refers to the scan kernel, timed with HIP
 events on the library's stream inside the timed steps; ``cpu_baseline`` is the
@@ -29,6 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_FP8_PEAK_TFLOPS = 5000.0
 # HBM bytes per Q = 64 scan launch on the N = 10M, d = 768 store, from two rocprofv3 counter runs
 # (FETCH_SIZE 7,501,007 KiB x 2.0000, WRITE_SIZE 3,726 KiB x 1.0000; the factors are what the same counters read
 # for a plain 1 GiB copy).  Valid for the scan_stream kernel as committed with profiles/scan_stream_c3_bf16.md;
@@ -38,24 +41,30 @@ LARGE_Q = 4096
 
 
 def time_search(ix, torch, qd, k, lam, mask, out_s, out_i, warmup, steps):
-    """Time `steps` searches on resident inputs; returns (ms per step, scan kernel ms per launch, wall ms)."""
+    """Time `steps` searches on resident inputs.
+
+    Returns (ms per step = whole timed region / steps, scan kernel ms per launch, wall ms per step,
+    {median, p10, p90} of the single steps from an event recorded after every step)."""
     ix.set_timing(False)
     for _ in range(warmup):
         ix.search(qd, k, lam, mask, out_s, out_i)
     torch.cuda.synchronize()
     ix.set_timing(True)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
-    e0.record()
+    ev[0].record()
     # the library brackets every scan launch with events on this stream; nothing waits
-    for _ in range(steps):
+    for i in range(steps):
         ix.search(qd, k, lam, mask, out_s, out_i)
-    e1.record()
+        ev[i + 1].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     scan_ms, launches = ix.scan_time_ms()
     ix.set_timing(False)
-    return e0.elapsed_time(e1) / steps, scan_ms / max(launches, 1), wall_ms / steps
+    each = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    pick = lambda f: each[min(steps - 1, int(f * steps))]
+    spread = {"median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9)}
+    return ev[0].elapsed_time(ev[steps]) / steps, scan_ms / max(launches, 1), wall_ms / steps, spread
 
 
 def main() -> int:
@@ -66,6 +75,7 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=None, help="override N (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large-batch", action="store_true", help="skip the Q = 4096 legs")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the fp8 (N = 20M) legs")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, so that a counter run over this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -123,14 +133,14 @@ def main() -> int:
         qd = wl.queries(Q, batch=Q)
         out_s = torch.empty(Q, cfg.k, dtype=torch.float32, device=dev)
         out_i = torch.empty(Q, cfg.k, dtype=torch.int64, device=dev)
-        ms, scan, wall = time_search(ix, torch, qd, cfg.k, cfg.lam, None, out_s, out_i, args.warmup, args.steps)
+        ms, scan, wall, spread = time_search(ix, torch, qd, cfg.k, cfg.lam, None, out_s, out_i, args.warmup, args.steps)
         per_q[str(Q)] = {
             "queries_per_s": Q / (ms * 1e-3),
             "ms_per_step": ms,
             "scan_kernel_ms": scan,
             "scan_GBps": store_bytes / (scan * 1e-3) / 1e9,
             "hbm_frac": store_bytes / (scan * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "wall_ms_per_step": wall,
+            "wall_ms_per_step": wall, "step_ms": spread,
         }
         if Q == 64:
             headline = per_q[str(Q)]
@@ -143,13 +153,13 @@ def main() -> int:
         qd = wl.queries(Q, batch=Q)
         out_s = torch.empty(Q, cfg.k, dtype=torch.float32, device=dev)
         out_i = torch.empty(Q, cfg.k, dtype=torch.int64, device=dev)
-        ms, scan, wall = time_search(ix, torch, qd, cfg.k, cfg.lam, None, out_s, out_i, lwarm, lsteps)
+        ms, scan, wall, spread = time_search(ix, torch, qd, cfg.k, cfg.lam, None, out_s, out_i, lwarm, lsteps)
         flop = 2.0 * Q * cfg.N * cfg.d
         per_q[str(Q)] = {
             "queries_per_s": Q / (ms * 1e-3), "ms_per_step": ms, "steps": lsteps, "scan_kernel_ms": scan,
             "scan_TFLOPs": flop / (scan * 1e-3) / 1e12,
             "mfma_frac": flop / (scan * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-            "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall,
+            "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall, "step_ms": spread,
         }
         del qd, out_s, out_i
     ix.close()
@@ -171,13 +181,14 @@ def main() -> int:
         qd = wl4.queries(c4.Q)
         out_s = torch.empty(c4.Q, c4.k, dtype=torch.float32, device=dev)
         out_i = torch.empty(c4.Q, c4.k, dtype=torch.int64, device=dev)
-        ms, scan, wall = time_search(ix4, torch, qd, c4.k, c4.lam, mask4, out_s, out_i, lwarm, lsteps)
+        ms, scan, wall, spread = time_search(ix4, torch, qd, c4.k, c4.lam, mask4, out_s, out_i, lwarm, lsteps)
         flop = 2.0 * c4.Q * c4.N * c4.d
         large = {
             "workload": f"C4: N={c4.N} d={c4.d} bf16 store, {c4.clusters}-cluster mixture, Q={c4.Q}, k={c4.k}, "
                         f"lambda={c4.lam}, {1.0 - c4.p_valid:.0%} masked rows",
             "queries_per_s": c4.Q / (ms * 1e-3), "ms_per_step": ms, "steps": lsteps, "warmup": lwarm,
             "scan_kernel_ms": scan, "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall,
+            "step_ms": spread,
         }
         ach = flop / (scan * 1e-3) / 1e12
         roof_mfma = {
@@ -186,6 +197,53 @@ def main() -> int:
             "traffic": None, "algorithmic_flops_per_launch": flop,
         }
         ix4.close()
+        ix4.arena = None
+        del ix4, mask4, masks, qd, out_s, out_i
+        torch.cuda.empty_cache()
+
+    # ---- fp8 store: N = 20M, d = 1024, k = 100 (built by appends of 100,000 rows), Q = 1, 64, 4096
+    fp8 = None
+    if not args.no_large_batch and not args.no_fp8:
+        c5 = workloads.C5 if args.rows is None else workloads.C5.scaled(N=min(workloads.C5.N, args.rows))
+        wl5 = workloads.Workload(c5, dev)
+        ix5 = pkg.Index(c5.d, c5.N, pkg.STORE_FP8_E4M3, LARGE_Q, c5.k, dev)
+        app_ms, app_rows = 0.0, 0
+        for lo in range(0, c5.N, chunk):
+            n = min(chunk, c5.N - lo)
+            E, U, M = wl5.rows(lo, n)
+            for a0 in range(0, n, 100_000):
+                a1 = min(n, a0 + 100_000)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ix5.append(E[a0:a1], None)
+                e1.record()
+                e1.synchronize()
+                app_ms += e0.elapsed_time(e1)
+                app_rows += a1 - a0
+            del E
+        row5 = ix5.store_view()[0].shape[1]
+        bytes5 = c5.N * (row5 + 4)   # rows + per-row scale
+        fp8 = {"workload": f"C5: N={c5.N} d={c5.d} fp8 e4m3 store with per-row scale, {c5.clusters}-cluster "
+                           f"Zipf(1.1) mixture, k={c5.k}, lambda=0, no mask",
+               "append_rows_per_s": app_rows / (app_ms * 1e-3), "per_Q": {}}
+        for Q in (1, 64, LARGE_Q):
+            qd = wl5.queries(Q, batch=Q)
+            out_s = torch.empty(Q, c5.k, dtype=torch.float32, device=dev)
+            out_i = torch.empty(Q, c5.k, dtype=torch.int64, device=dev)
+            st, wu = (lsteps, lwarm) if Q == LARGE_Q else (max(10, args.steps // 4), max(2, args.warmup // 4))
+            ms, scan, wall, spread = time_search(ix5, torch, qd, c5.k, c5.lam, None, out_s, out_i, wu, st)
+            rec = {"queries_per_s": Q / (ms * 1e-3), "ms_per_step": ms, "steps": st, "scan_kernel_ms": scan,
+                   "step_ms": spread}
+            if Q == LARGE_Q:
+                flop = 2.0 * Q * c5.N * c5.d
+                rec["scan_TFLOPs"] = flop / (scan * 1e-3) / 1e12
+                rec["mfma_frac"] = rec["scan_TFLOPs"] / MFMA_FP8_PEAK_TFLOPS
+            else:
+                rec["scan_GBps"] = bytes5 / (scan * 1e-3) / 1e9
+                rec["hbm_frac"] = rec["scan_GBps"] / HBM_PEAK_GBS
+            fp8["per_Q"][str(Q)] = rec
+            del qd, out_s, out_i
+        ix5.close()
 
     # ---- CPU reference on a bounded sample (rank 0, N = 1 only)
     cpu = None
@@ -233,6 +291,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "large_batch": large,
         "roofline_mfma": roof_mfma,
+        "fp8_store": fp8,
     }
     print(json.dumps(line))
     return 0

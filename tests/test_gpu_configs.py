@@ -113,6 +113,26 @@ def _search(run, Q=None, mask=True):
     return s, i
 
 
+def _tiled_batch_check(pkg, run, ref, where, Q=4096):
+    """The same store searched with a batch large enough for the MFMA-tiled scan: a second index
+    (max_queries = Q) is filled from the masters on the GPU, the referenced queries sit at the
+    front of a batch of Q, and their rows of the result go through the same checks."""
+    cfg = run.cfg
+    store = pkg.STORE_BF16 if cfg.store == "bf16" else pkg.STORE_FP8_E4M3
+    ix2 = pkg.Index(cfg.d, cfg.N, store, Q, cfg.k, DEV)
+    for lo in range(0, cfg.N, CHUNK):
+        hi = min(cfg.N, lo + CHUNK)
+        ix2.append(run.E[lo:hi], None if run.U is None else run.U[lo:hi])
+    big = run.wl.queries(Q, batch=3)
+    big[: run.Qd.shape[0]] = run.Qd
+    t0 = time.time()
+    s, i = ix2.search(big, cfg.k, cfg.lam, run.M)
+    torch.cuda.synchronize()
+    print(f"   search Q={Q} (tiled) took {1e3 * (time.time() - t0):.2f} ms (incl. launch)", flush=True)
+    run.check(s, i, ref, where)
+    ix2.close()
+
+
 def test_c1_full(pkg, oracle):
     cfg = workloads.C1
     _say(f"{cfg}")
@@ -143,6 +163,7 @@ def test_c3_full(pkg, oracle):
         s, i = _search(run, Q)
         assert torch.equal(i, i64[:Q]) and torch.equal(s, s64[:Q])
         run.check(s, i, ref, f"C3 Q={Q}")
+    _tiled_batch_check(pkg, run, ref, "C3 Q=4096 (tiled)")
 
 
 def test_c4_full(pkg, oracle):
@@ -176,3 +197,4 @@ def test_c5_full_with_appends(pkg, oracle):
     s3, i3 = run.ix.search(big[100:101].contiguous(), cfg.k, cfg.lam)
     torch.cuda.synchronize()
     assert torch.equal(i2[100], i3[0]) and torch.equal(s2[100], s3[0])
+    _tiled_batch_check(pkg, run, ref, "C5 Q=4096 (tiled, fp8)")
