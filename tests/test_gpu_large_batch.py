@@ -51,6 +51,8 @@ LARGE = [
     ("bf16", 300000, 64, 16, 513, 128, 0.1, "uniform", 0.7),
     ("fp8", 300000, 256, 64, 257, 100, 0.0, "none", 1.0),
     ("fp8", 270000, 100, 16, 128, 10, 0.3, "uniform", 0.95),
+    ("bf16", 262400, 1024, 16, 140, 8, 0.0, "none", 1.0),     # longest bf16 rows: 32 pipeline steps per tile
+    ("fp8", 262145, 1024, 16, 129, 128, 0.05, "uniform", 0.99),  # ragged last tile of one row, largest k
 ]
 
 
@@ -97,3 +99,22 @@ def test_large_batch_equals_small_batches(pkg):
     # rows may swap only where two scores are within rounding of each other
     assert float(same.float().mean()) > 0.995
     ix.close()
+
+
+def test_large_batch_in_chunks(pkg, oracle):
+    """A batch larger than max_queries is searched in chunks: 128 + 128 through the tiled scan, the
+    last 44 through the streaming scan; every row of the result is checked the same way."""
+    _say("tiled scan, batch split into chunks of max_queries")
+    cfg = workloads.Config("G", N=265000, d=192, clusters=32, Q=300, k=20, store="bf16", zipf=1.1, lam=0.1,
+                           util="uniform", p_valid=0.9, seed=8300)
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, M = wl.rows(0, cfg.N)
+    Qm = wl.queries()
+    ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, 128, cfg.k, DEV)
+    ix.append(E.to(DEV), U.to(DEV))
+    s, i = ix.search(Qm.to(DEV), cfg.k, cfg.lam, M.to(DEV))
+    torch.cuda.synchronize()
+    ix.close()
+    sample = [0, 63, 64, 127, 128, 129, 200, 255, 256, 257, 280, 299]
+    parity.check_batch("bf16", s.cpu().numpy(), i.cpu().numpy(), E.numpy(), U.numpy(), M.numpy(), Qm.numpy(),
+                       cfg.k, cfg.lam, "chunks", queries=sample)
