@@ -22,7 +22,8 @@
  *   - All work is enqueued on the index's stream and is asynchronous; calls on
  *     one index are ordered.  No call synchronises the host except
  *     ic_index_scan_time_ms.
- *   - Example ids are append order: 0-based, dense, stable.
+ *   - Example ids are append order: 0-based, dense, stable (until ic_index_compact
+ *     renumbers the surviving rows).
  *   - Errors are returned as ic_status; nothing throws or aborts.  On error the
  *     outputs are untouched.  Inputs must be finite.
  */
@@ -59,7 +60,7 @@ typedef enum {
 
 /*
  * Bytes of device memory an index needs: the embedding store (rows padded to a
- * multiple of 128 B), per-row scale and utility arrays, the prepared query
+ * multiple of 128 B), per-row scale, utility and validity arrays, the prepared query
  * block, and the top-k workspace for searches of up to max_queries queries per
  * call with k <= max_k.  Returns 0 if an argument is out of range.
  */
@@ -110,6 +111,34 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
 ic_status ic_search(const ic_index *index, const float *q_dev, int64_t Q, int32_t k,
                     float lambda, const uint8_t *mask_dev, float *out_scores_dev,
                     int64_t *out_ids_dev);
+
+/*
+ * Maintenance driven by the Example Manager (Sec. 4.3, "Capping Example Cache Size over
+ * Time"): the manager keeps a moving average of every example's gain, decays it (factor 0.9
+ * per hour in the paper) and evicts low-utility examples.  The four calls below are what the
+ * embedding store needs for that.  They are ordered with searches and appends on the stream.
+ *
+ * ic_index_set_utility   utility[ids_dev[j]] = util_dev[j] for j < n.  ids outside
+ *                        [0, size) are ignored; if an id occurs twice either value may win.
+ * ic_index_scale_utility utility[i] *= factor for every row (one fp32 multiplication).
+ * ic_index_invalidate    marks the rows ids_dev[0..n) as evicted: they are never returned by
+ *                        later searches, exactly as if every later mask had a 0 for them.  Ids
+ *                        outside [0, size) are ignored.  The rows still occupy the store (and
+ *                        cost bandwidth) until ic_index_compact.
+ * ic_index_compact       squeezes the invalidated rows out, keeping the order of the others.
+ *                        id_map_dev [size before the call] int64 receives the new id of every
+ *                        old row, or -1 for a dropped row; *new_size (host, may be NULL) the
+ *                        number of rows left.  Ids change: this is the one call after which
+ *                        "ids are append order" refers to the surviving rows only, and masks
+ *                        given to later searches are indexed by the new ids.  Unlike the other
+ *                        calls it waits for the stream (the new size is needed on the host).
+ *                        Cost: the store is read and written twice, O(size).
+ * Errors: INVALID_ARG, DEVICE.
+ */
+ic_status ic_index_set_utility(ic_index *index, const int64_t *ids_dev, const float *util_dev, int64_t n);
+ic_status ic_index_scale_utility(ic_index *index, float factor);
+ic_status ic_index_invalidate(ic_index *index, const int64_t *ids_dev, int64_t n);
+ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_size);
 
 /* Release the handle.  Device memory belongs to the caller and is not touched. */
 ic_status ic_index_destroy(ic_index *index);

@@ -251,3 +251,44 @@ def search_numpy(E, queries, k: int, lam: float = 0.0, U=None, mask=None):
         out_s[q, :len(order)] = s[q, cand[order]]
         out_i[q, :len(order)] = cand[order]
     return out_s.astype(np.float32), out_i, out_s
+
+
+# --------------------------------------------------------------------------
+# Store maintenance (Example Manager, Sec. 4.3 "Capping Example Cache Size over Time"): what
+# the store holds after utilities are refreshed or decayed and after evicted examples are
+# squeezed out.  Plain definitions on host arrays.
+# --------------------------------------------------------------------------
+
+def set_utility(U, ids, values):
+    """U with U[ids[j]] = values[j]; ids outside the store are ignored (ids must be distinct)."""
+    out = np.array(U, dtype=np.float32, copy=True)
+    for j, i in enumerate(np.asarray(ids, dtype=np.int64)):
+        if 0 <= i < out.shape[0]:
+            out[i] = np.float32(values[j])
+    return out
+
+
+def scale_utility(U, factor):
+    """Every utility times ``factor``, one fp32 multiplication each (the hourly decay uses 0.9)."""
+    return (np.asarray(U, dtype=np.float32) * np.float32(factor)).astype(np.float32)
+
+
+def invalidate(valid, ids):
+    """Validity flags after the rows ``ids`` were evicted."""
+    out = np.array(valid, dtype=np.uint8, copy=True)
+    for i in np.asarray(ids, dtype=np.int64):
+        if 0 <= i < out.shape[0]:
+            out[i] = 0
+    return out
+
+
+def compaction_map(valid):
+    """New id of every row once the invalid rows are dropped and the others keep their order:
+    the number of valid rows before it, or -1 for a dropped row.  Returns (id_map, new_size)."""
+    out = np.full(len(valid), -1, dtype=np.int64)
+    nxt = 0
+    for i, v in enumerate(valid):
+        if v:
+            out[i] = nxt
+            nxt += 1
+    return out, nxt

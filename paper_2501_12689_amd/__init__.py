@@ -12,8 +12,12 @@ from .binding import (  # noqa: F401
     ICError,
     Index,
     ic_index_append,
+    ic_index_compact,
     ic_index_create,
     ic_index_destroy,
+    ic_index_invalidate,
+    ic_index_scale_utility,
+    ic_index_set_utility,
     ic_search,
     ic_workspace_bytes,
     lib_path,

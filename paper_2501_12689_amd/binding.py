@@ -24,6 +24,7 @@ EXPORTS = (
     "ic_workspace_bytes", "ic_index_create", "ic_index_append", "ic_search", "ic_index_destroy",
     "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing",
     "ic_index_scan_time_ms", "ic_status_string",
+    "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
 )
 
 _lib = None
@@ -73,6 +74,14 @@ def load_library() -> ctypes.CDLL:
     L.ic_index_set_timing.argtypes = [vp, ctypes.c_int]
     L.ic_index_scan_time_ms.restype = ctypes.c_int
     L.ic_index_scan_time_ms.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(i64)]
+    L.ic_index_set_utility.restype = ctypes.c_int
+    L.ic_index_set_utility.argtypes = [vp, vp, vp, i64]
+    L.ic_index_scale_utility.restype = ctypes.c_int
+    L.ic_index_scale_utility.argtypes = [vp, f32]
+    L.ic_index_invalidate.restype = ctypes.c_int
+    L.ic_index_invalidate.argtypes = [vp, vp, i64]
+    L.ic_index_compact.restype = ctypes.c_int
+    L.ic_index_compact.argtypes = [vp, vp, ctypes.POINTER(i64)]
     L.ic_status_string.restype = ctypes.c_char_p
     L.ic_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -143,6 +152,31 @@ def ic_index_destroy(handle: int) -> None:
     _check(load_library().ic_index_destroy(handle), "ic_index_destroy")
 
 
+def ic_index_set_utility(handle: int, ids: torch.Tensor, util: torch.Tensor) -> None:
+    """utility[ids[j]] = util[j] (ids int64 [n], util fp32 [n], both on the GPU)."""
+    _check(load_library().ic_index_set_utility(handle, _dev_ptr(ids, torch.int64, "ids"),
+                                               _dev_ptr(util, torch.float32, "util"), ids.numel()),
+           "ic_index_set_utility")
+
+
+def ic_index_scale_utility(handle: int, factor: float) -> None:
+    _check(load_library().ic_index_scale_utility(handle, float(factor)), "ic_index_scale_utility")
+
+
+def ic_index_invalidate(handle: int, ids: torch.Tensor) -> None:
+    """Mark rows as evicted; later searches never return them."""
+    _check(load_library().ic_index_invalidate(handle, _dev_ptr(ids, torch.int64, "ids"), ids.numel()),
+           "ic_index_invalidate")
+
+
+def ic_index_compact(handle: int, id_map: torch.Tensor) -> int:
+    """Drop invalidated rows; ``id_map`` int64 [old size] receives new ids (-1 = dropped).  Returns the new size."""
+    n = ctypes.c_int64(-1)
+    _check(load_library().ic_index_compact(handle, _dev_ptr(id_map, torch.int64, "id_map"), ctypes.byref(n)),
+           "ic_index_compact")
+    return n.value
+
+
 # ---- convenience owner of (arena, handle) -----------------------------------
 
 class Index:
@@ -193,6 +227,21 @@ class Index:
         if scale.value:
             s = self.arena[scale.value - base: scale.value - base + 4 * n].view(torch.float32)
         return r, s, u
+
+    def set_utility(self, ids: torch.Tensor, util: torch.Tensor) -> None:
+        ic_index_set_utility(self.handle, ids, util)
+
+    def scale_utility(self, factor: float) -> None:
+        ic_index_scale_utility(self.handle, factor)
+
+    def invalidate(self, ids: torch.Tensor) -> None:
+        ic_index_invalidate(self.handle, ids)
+
+    def compact(self) -> torch.Tensor:
+        """Drop invalidated rows; returns the id map (int64 [old size], -1 = dropped)."""
+        id_map = torch.empty(max(len(self), 1), dtype=torch.int64, device=self.device)[: len(self)]
+        ic_index_compact(self.handle, id_map)
+        return id_map
 
     def close(self) -> None:
         if getattr(self, "handle", None):

@@ -74,15 +74,17 @@ __host__ __device__ constexpr size_t scan_lds_bytes(int qg, int cap) {
 }
 
 // Score bias of every row for one search: lambda * utility where the row is valid, -inf
-// where the mask excludes it and for the padding rows [n, n_pad).  util or mask may be NULL.
+// where the mask excludes it, where the row has been invalidated (live[i] == 0) and for the
+// padding rows [n, n_pad).  util, mask and live may be NULL.
 __global__ __launch_bounds__(256) void make_bias(const float *__restrict__ util,
-                                                 const uint8_t *__restrict__ mask, int64_t n,
+                                                 const uint8_t *__restrict__ mask,
+                                                 const uint8_t *__restrict__ live, int64_t n,
                                                  int64_t n_pad, float lambda, float *__restrict__ bias) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t step = (int64_t)gridDim.x * 256;
     for (; i < n_pad; i += step) {
         float b = -INFINITY;
-        if (i < n && (!mask || mask[i] != 0)) b = util ? lambda * util[i] : 0.0f;
+        if (i < n && (!mask || mask[i] != 0) && (!live || live[i] != 0)) b = util ? lambda * util[i] : 0.0f;
         bias[i] = b;
     }
 }

@@ -12,6 +12,7 @@
 #include "ic_common.h"
 #include "ic_merge.h"
 #include "ic_quantize.h"
+#include "ic_maintain.h"
 #include "ic_scan_gemm.h"
 #include "ic_scan_stream.h"
 
@@ -59,7 +60,7 @@ struct Layout {
     int64_t cap_pad = 0;
     size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
            off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, off_pilot = 0, off_thr = 0, off_glist = 0, off_gcount = 0,
-           off_redo = 0, total = 0;
+           off_redo = 0, off_valid = 0, off_blocks = 0, total = 0;
     int64_t list_slots = 0;
     int q_rows = 0;  // rows of the prepared query block
 };
@@ -99,6 +100,8 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_glist = take(gemm ? (size_t)L.q_chunk * (size_t)gemm_list_cap(max_k) * 8 : 0);
     L.off_gcount = take(gemm ? (size_t)L.q_chunk * 4 : 0);
     L.off_redo = take(gemm ? (size_t)(L.q_chunk / 64 + 1) * 4 : 0);
+    L.off_valid = take((size_t)L.cap_pad);                                          // persistent validity, 1 B/row
+    L.off_blocks = take((size_t)(L.cap_pad / ic::kScanBlock + 2) * 8);              // compaction: block offsets
     L.total = off;
     return true;
 }
@@ -161,6 +164,9 @@ struct ic_index {
     uint8_t *rows;
     float *scale;
     float *util;
+    uint8_t *valid;        // [cap_pad] 1 = row is live, 0 = invalidated (evicted) and waiting for compaction
+    int64_t *block_offsets;  // compaction scratch
+    bool any_invalid;      // some row has been invalidated since the last compaction
     uint8_t *qbuf;
     float *qscale;
     uint64_t *regions;
@@ -235,6 +241,9 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->rows = base + L.off_rows;
     ix->scale = (store == IC_STORE_FP8_E4M3) ? (float *)(base + L.off_scale) : nullptr;
     ix->util = (float *)(base + L.off_util);
+    ix->valid = base + L.off_valid;
+    ix->block_offsets = (int64_t *)(base + L.off_blocks);
+    ix->any_invalid = false;
     ix->qbuf = base + L.off_qbuf;
     ix->qscale = (float *)(base + L.off_qscale);
     ix->regions = (uint64_t *)(base + L.off_regions);
@@ -325,9 +334,82 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
         hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, index->stream, emb_dev, n, n,
                            index->d, index->L.row_bytes, dst, index->scale + at, util_dev, util_dst);
     }
+    hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream,
+                       index->valid + at, n, (uint8_t)1);
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     index->n += n;
     return IC_OK;
+}
+
+// ---- Example Manager maintenance (Sec. 4.3) --------------------------------------------------
+
+ic_status ic_index_set_utility(ic_index *index, const int64_t *ids_dev, const float *util_dev, int64_t n) {
+    if (!index || n < 0 || (n > 0 && (!ids_dev || !util_dev))) return IC_ERR_INVALID_ARG;
+    if (n == 0) return IC_OK;
+    hipLaunchKernelGGL(ic::set_utility, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream, ids_dev,
+                       util_dev, n, index->util, index->n);
+    return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
+}
+
+ic_status ic_index_scale_utility(ic_index *index, float factor) {
+    if (!index) return IC_ERR_INVALID_ARG;
+    if (index->n == 0) return IC_OK;
+    hipLaunchKernelGGL(ic::scale_utility, dim3((unsigned)((index->n + 255) / 256)), dim3(256), 0, index->stream,
+                       index->util, index->n, factor);
+    return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
+}
+
+ic_status ic_index_invalidate(ic_index *index, const int64_t *ids_dev, int64_t n) {
+    if (!index || n < 0 || (n > 0 && !ids_dev)) return IC_ERR_INVALID_ARG;
+    if (n == 0) return IC_OK;
+    hipLaunchKernelGGL(ic::invalidate_rows, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream, ids_dev,
+                       n, index->valid, index->n);
+    index->any_invalid = true;
+    return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
+}
+
+ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_size) {
+    if (!index || !id_map_dev) return IC_ERR_INVALID_ARG;
+    const int64_t n = index->n;
+    if (new_size) *new_size = n;
+    if (n == 0) return IC_OK;
+    hipStream_t st = index->stream;
+    const Layout &L = index->L;
+    const int64_t nblocks = (n + ic::kScanBlock - 1) / ic::kScanBlock;
+    int64_t *offs = index->block_offsets;
+    hipLaunchKernelGGL(ic::count_valid, dim3((unsigned)nblocks), dim3(256), 0, st, index->valid, n, offs);
+    hipLaunchKernelGGL(ic::scan_block_sums, dim3(1), dim3(256), 0, st, offs, nblocks);
+    hipLaunchKernelGGL(ic::write_id_map, dim3((unsigned)nblocks), dim3(256), 0, st, index->valid, n, offs, id_map_dev);
+    // rows, chunk by chunk through the candidate-region scratch (free between searches)
+    uint8_t *bounce = (uint8_t *)index->regions;
+    const size_t bounce_bytes = (size_t)kRegionSlots * (size_t)region_cap(index->max_k) * 8;
+    const int64_t chunk = std::max<int64_t>(ic::kScanBlock,
+                                            (int64_t)(bounce_bytes / (size_t)L.row_bytes) / ic::kScanBlock * ic::kScanBlock);
+    const int grid = std::max(8, index->compute_units) * 4;
+    for (int64_t lo = 0; lo < n; lo += chunk) {
+        const int64_t hi = std::min(n, lo + chunk);
+        hipLaunchKernelGGL(ic::gather_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, id_map_dev, offs,
+                           lo, hi, bounce);
+        hipLaunchKernelGGL(ic::store_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, offs, lo,
+                           (hi + ic::kScanBlock - 1) / ic::kScanBlock, bounce);
+    }
+    // side arrays through the per-search bias scratch
+    const unsigned g1 = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, index->util, id_map_dev, n, index->bias);
+    hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->bias, offs + nblocks, index->util);
+    if (index->scale) {
+        hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, index->scale, id_map_dev, n, index->bias);
+        hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->bias, offs + nblocks, index->scale);
+    }
+    hipLaunchKernelGGL(ic::fill_bytes, dim3(g1), dim3(256), 0, st, index->valid, n, (uint8_t)1);
+    int64_t total = 0;
+    if (hipMemcpyAsync(&total, offs + nblocks, sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return IC_ERR_DEVICE;
+    index->n = total;
+    index->any_invalid = false;
+    if (new_size) *new_size = total;
+    return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
 }
 
 namespace {
@@ -411,13 +493,14 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
     // a4 (first half): per-row additive term, once per search.  The tiled scan always reads it
     // (it marks the padding rows of the last tile); the streaming scan only if it is not all zero.
     const bool any_gemm = gemm_ok && std::min<int64_t>(Q, L.q_chunk) >= kGemmMinQueries;
-    const bool use_bias = (lambda != 0.0f) || mask_dev != nullptr || any_gemm;
+    const bool use_bias = (lambda != 0.0f) || mask_dev != nullptr || any_gemm || index->any_invalid;
     if (use_bias && n > 0) {
         const int64_t n_pad = round_up(n, ic::kGemmTile);
         const int grid = (int)std::min<int64_t>((n_pad + 255) / 256, 4096);
         hipLaunchKernelGGL(ic::make_bias, dim3(grid), dim3(256), 0, st,
                            (lambda != 0.0f) ? (const float *)index->util : (const float *)nullptr, mask_dev,
-                           n, n_pad, lambda, index->bias);
+                           index->any_invalid ? (const uint8_t *)index->valid : (const uint8_t *)nullptr, n, n_pad,
+                           lambda, index->bias);
     }
 
     for (int64_t q0 = 0; q0 < Q; q0 += L.q_chunk) {

@@ -354,3 +354,53 @@ def test_quantisation_score_error_bounds(oracle):
     s8 = oracle.scores(oracle.decode_e4m3(c), oracle.decode_e4m3(cq), normalize=False,
                        row_scale=s, q_scale=sq)
     assert np.abs(s8 - exact).max() < 6e-2 / 4      # fp8 rows and fp8 queries, margin 4x
+
+
+# ---- store maintenance (Sec. 4.3): plain definitions, pinned on hand-made cases ----
+
+def test_compaction_map_hand_cases(oracle):
+    m, n = oracle.compaction_map([1, 0, 1, 1, 0])
+    assert m.tolist() == [0, -1, 1, 2, -1] and n == 3
+    m, n = oracle.compaction_map([0, 0, 0])
+    assert m.tolist() == [-1, -1, -1] and n == 0
+    m, n = oracle.compaction_map([1] * 7)
+    assert m.tolist() == list(range(7)) and n == 7
+    m, n = oracle.compaction_map([])
+    assert m.tolist() == [] and n == 0
+
+
+def test_compaction_map_properties(oracle):
+    rng = np.random.default_rng(5)
+    valid = (rng.random(5000) < 0.8).astype(np.uint8)
+    m, n = oracle.compaction_map(valid)
+    kept = np.flatnonzero(valid)
+    assert n == kept.size
+    # surviving rows keep their order and land on 0 .. n-1; dropped rows map to -1
+    assert np.array_equal(m[kept], np.arange(n)) and np.all(m[valid == 0] == -1)
+    # same thing through a cumulative sum
+    assert np.array_equal(m, np.where(valid != 0, np.cumsum(valid.astype(np.int64)) - 1, -1))
+
+
+def test_utility_updates_hand_cases(oracle):
+    U = np.array([0.5, 1.0, 0.25, 2.0], dtype=np.float32)
+    assert oracle.set_utility(U, [2, 0, 9, -1], [7.0, 8.0, 1.0, 1.0]).tolist() == [8.0, 1.0, 7.0, 2.0]
+    assert U.tolist() == [0.5, 1.0, 0.25, 2.0]          # the input is not modified
+    d = oracle.scale_utility(U, 0.9)
+    assert d.dtype == np.float32 and np.array_equal(d, (U * np.float32(0.9)).astype(np.float32))
+    assert oracle.scale_utility(U, 0.5).tolist() == [0.25, 0.5, 0.125, 1.0]  # exact in binary
+    assert oracle.invalidate(np.ones(4, np.uint8), [1, 3, 3, 17]).tolist() == [1, 0, 1, 0]
+
+
+def test_search_after_eviction_equals_search_on_the_survivors(oracle):
+    """Evicting rows and compacting is the same as never having had them: the result on the
+    compacted arrays, mapped back through the id map, equals the masked result on the original."""
+    rng = np.random.default_rng(11)
+    E = rng.standard_normal((400, 24)).astype(np.float32)
+    U = rng.random(400).astype(np.float32)
+    Qm = rng.standard_normal((5, 24)).astype(np.float32)
+    valid = oracle.invalidate(np.ones(400, np.uint8), rng.choice(400, 90, replace=False))
+    m, n = oracle.compaction_map(valid)
+    keep = np.flatnonzero(valid)
+    s1, i1, _ = oracle.search(E, Qm, 12, 0.3, U, valid)
+    s2, i2, _ = oracle.search(E[keep], Qm, 12, 0.3, U[keep], None)
+    assert np.array_equal(m[i1], i2) and np.array_equal(s1, s2)
