@@ -13,7 +13,8 @@ The matrix-core regime is timed as well (fewer steps, they are long): Q = 4096 o
 the same store (``config.per_Q["4096"]``) and the N = 4,000,000, d = 1024, k = 16
 configuration with utility and mask (``large_batch``, ``roofline_mfma``); and the fp8 store
 (N = 20,000,000, d = 1024, k = 100, built by appends of 100,000 rows) at Q = 1, 64 and 4096
-(``fp8_store``).
+(``fp8_store``).  ``maintenance`` times the eviction of the masked rows of the d = 1024
+configuration and the compaction that squeezes them out.
 
 Prints one JSON line.  ``roofline`` refers to the scan kernel, timed with HIP
 events on the library's stream inside the timed steps; ``cpu_baseline`` is the
@@ -146,7 +147,7 @@ def main() -> int:
             headline = per_q[str(Q)]
 
     # ---- matrix-core regime: Q = 4096 on the same store, then the N = 4M, d = 1024 configuration
-    large, roof_mfma = None, None
+    large, roof_mfma, maintenance = None, None, None
     if not args.no_large_batch:
         lsteps, lwarm = max(3, min(10, args.steps)), 2
         Q = LARGE_Q
@@ -196,6 +197,28 @@ def main() -> int:
             "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
             "traffic": None, "algorithmic_flops_per_launch": flop,
         }
+        # store maintenance on the same index: evict the masked rows for good, squeeze them out,
+        # search the smaller store without a mask
+        if mask4 is not None:
+            gone = torch.nonzero(mask4 == 0).flatten()
+            ix4.invalidate(gone)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ix4.compact()
+            e1.record()
+            e1.synchronize()
+            cms = e0.elapsed_time(e1)
+            row4 = ix4.store_view()[0].shape[1]
+            moved = (c4.N + len(ix4)) * (row4 + 4)      # every row read once, every survivor written once
+            ms2, scan2, _, _ = time_search(ix4, torch, qd, c4.k, c4.lam, None, out_s, out_i, lwarm, lsteps)
+            maintenance = {
+                "evicted_rows": int(gone.numel()), "rows_left": len(ix4), "compact_ms": cms,
+                "compact_rows_per_s": c4.N / (cms * 1e-3),
+                "compact_GBps_algorithmic": moved / (cms * 1e-3) / 1e9,
+                "compact_hbm_frac": moved / (cms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "search_after_compact": {"queries_per_s": c4.Q / (ms2 * 1e-3), "ms_per_step": ms2,
+                                         "scan_kernel_ms": scan2},
+            }
         ix4.close()
         ix4.arena = None
         del ix4, mask4, masks, qd, out_s, out_i
@@ -292,6 +315,7 @@ def main() -> int:
         "large_batch": large,
         "roofline_mfma": roof_mfma,
         "fp8_store": fp8,
+        "maintenance": maintenance,
     }
     print(json.dumps(line))
     return 0

@@ -107,15 +107,23 @@ __global__ __launch_bounds__(256) void write_id_map(const uint8_t *__restrict__ 
     }
 }
 
-// ---- compaction, step 2: move the surviving rows of one chunk [lo, hi) of the store (lo, hi
-// multiples of kScanBlock, or hi = size) through a bounce buffer.  gather_rows packs them into
-// the buffer; store_rows copies the packed rows to their final place, which ends at or before
-// the chunk's own end and so only overwrites rows that have already been read.
-__global__ __launch_bounds__(256) void gather_rows(const uint8_t *__restrict__ rows, int row_bytes,
+// ---- compaction, step 2: move the surviving rows of one chunk [lo, hi) of the store (lo a
+// multiple of kScanBlock; hi too, or hi = size).  Chunks are processed in order, one pair of
+// launches each.  Once at least a chunk's worth of rows has been dropped before the chunk, its
+// destination lies entirely before lo, where every row has already been moved: gather_rows
+// writes the rows straight to their final place and store_rows does nothing.  Until then the
+// destination overlaps the chunk's own unread rows, so gather_rows packs them into a bounce
+// buffer and store_rows copies the packed rows to their place afterwards.
+__device__ __forceinline__ bool chunk_moves_directly(int64_t lo, int64_t hi, int64_t first_new) {
+    return lo - first_new >= hi - lo;
+}
+__global__ __launch_bounds__(256) void gather_rows(const uint8_t *rows, int row_bytes,
                                                    const int64_t *__restrict__ id_map,
                                                    const int64_t *__restrict__ block_offsets, int64_t lo,
-                                                   int64_t hi, uint8_t *__restrict__ bounce) {
+                                                   int64_t hi, uint8_t *bounce) {
     const int64_t first_new = block_offsets[lo / kScanBlock];
+    uint8_t *out = chunk_moves_directly(lo, hi, first_new) ? const_cast<uint8_t *>(rows) + first_new * (int64_t)row_bytes
+                                                           : bounce;
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
@@ -123,15 +131,17 @@ __global__ __launch_bounds__(256) void gather_rows(const uint8_t *__restrict__ r
         const int64_t to = id_map[r];
         if (to < 0) continue;
         const i32x4 *src = reinterpret_cast<const i32x4 *>(rows + r * (int64_t)row_bytes);
-        i32x4 *dst = reinterpret_cast<i32x4 *>(bounce + (to - first_new) * (int64_t)row_bytes);
+        i32x4 *dst = reinterpret_cast<i32x4 *>(out + (to - first_new) * (int64_t)row_bytes);
         for (int c = lane; c < row_bytes / 16; c += 64) dst[c] = src[c];
     }
 }
 
 __global__ __launch_bounds__(256) void store_rows(uint8_t *__restrict__ rows, int row_bytes,
                                                   const int64_t *__restrict__ block_offsets, int64_t lo,
-                                                  int64_t hi_block, const uint8_t *__restrict__ bounce) {
+                                                  int64_t hi, int64_t hi_block,
+                                                  const uint8_t *__restrict__ bounce) {
     const int64_t first_new = block_offsets[lo / kScanBlock];
+    if (chunk_moves_directly(lo, hi, first_new)) return;
     const int64_t count = block_offsets[hi_block] - first_new;
     const int64_t vecs = count * (int64_t)(row_bytes / 16);
     const i32x4 *src = reinterpret_cast<const i32x4 *>(bounce);

@@ -390,7 +390,7 @@ ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_si
         const int64_t hi = std::min(n, lo + chunk);
         hipLaunchKernelGGL(ic::gather_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, id_map_dev, offs,
                            lo, hi, bounce);
-        hipLaunchKernelGGL(ic::store_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, offs, lo,
+        hipLaunchKernelGGL(ic::store_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, offs, lo, hi,
                            (hi + ic::kScanBlock - 1) / ic::kScanBlock, bounce);
     }
     // side arrays through the per-search bias scratch
