@@ -113,6 +113,19 @@ ic_status ic_search(const ic_index *index, const float *q_dev, int64_t Q, int32_
                     int64_t *out_ids_dev);
 
 /*
+ * Top-k selection with a score threshold (Sec. 4.1, "Selecting Example Combinations": the
+ * selector drops examples whose estimated helpfulness falls below a dynamic threshold, so the
+ * number of examples varies per query).  Same as ic_search, except that an entry is kept only if
+ * its score (the fp32 value that would be returned) is >= min_score; dropped entries are
+ * (score = -inf, id = -1) and each row stays sorted, so the kept entries come first.
+ *   out_counts_dev  [Q] int32: entries kept for each query (0 .. k); may be NULL
+ * min_score = -inf keeps everything.  Errors: as ic_search; INVALID_ARG for a NaN threshold.
+ */
+ic_status ic_search_threshold(const ic_index *index, const float *q_dev, int64_t Q, int32_t k,
+                              float lambda, const uint8_t *mask_dev, float min_score,
+                              float *out_scores_dev, int64_t *out_ids_dev, int32_t *out_counts_dev);
+
+/*
  * Maintenance driven by the Example Manager (Sec. 4.3, "Capping Example Cache Size over
  * Time"): the manager keeps a moving average of every example's gain, decays it (factor 0.9
  * per hour in the paper) and evicts low-utility examples.  The four calls below are what the

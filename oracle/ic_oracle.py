@@ -292,3 +292,20 @@ def compaction_map(valid):
             out[i] = nxt
             nxt += 1
     return out, nxt
+
+
+# --------------------------------------------------------------------------
+# Threshold mode (Sec. 4.1, "Selecting Example Combinations"): examples below a score threshold
+# are dropped, so the number selected varies per query.
+# --------------------------------------------------------------------------
+
+def search_threshold(E, queries, k: int, min_score: float, lam: float = 0.0, U=None, mask=None):
+    """search(), then entries with fp64 score < min_score become (-inf, -1).
+    Returns (scores fp32, ids, scores fp64, counts)."""
+    s32, ids, s64 = search(E, queries, k, lam, U, mask)
+    s32, ids, s64 = s32.copy(), ids.copy(), s64.copy()
+    drop = (ids < 0) | (s64 < float(min_score))
+    s32[drop] = -np.inf
+    s64[drop] = -np.inf
+    ids[drop] = -1
+    return s32, ids, s64, (~drop).sum(axis=1).astype(np.int32)

@@ -25,6 +25,7 @@ EXPORTS = (
     "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing",
     "ic_index_scan_time_ms", "ic_status_string",
     "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
+    "ic_search_threshold",
 )
 
 _lib = None
@@ -61,6 +62,8 @@ def load_library() -> ctypes.CDLL:
     L.ic_index_append.argtypes = [vp, vp, vp, i64, ctypes.POINTER(i64)]
     L.ic_search.restype = ctypes.c_int
     L.ic_search.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp]
+    L.ic_search_threshold.restype = ctypes.c_int
+    L.ic_search_threshold.argtypes = [vp, vp, i64, i32, f32, vp, f32, vp, vp, vp]
     L.ic_index_destroy.restype = ctypes.c_int
     L.ic_index_destroy.argtypes = [vp]
     L.ic_index_size.restype = i64
@@ -148,6 +151,22 @@ def ic_search(handle: int, queries: torch.Tensor, k: int, lam: float = 0.0,
     return out_scores, out_ids
 
 
+def ic_search_threshold(handle: int, queries: torch.Tensor, k: int, min_score: float, lam: float = 0.0,
+                        mask: Optional[torch.Tensor] = None):
+    """ic_search that keeps only entries with score >= min_score: (scores, ids, counts int32 [Q])."""
+    L = load_library()
+    Q = queries.shape[0]
+    out_scores = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
+    out_ids = torch.empty((Q, k), dtype=torch.int64, device=queries.device)
+    counts = torch.empty((Q,), dtype=torch.int32, device=queries.device)
+    _check(L.ic_search_threshold(handle, _dev_ptr(queries, torch.float32, "queries"), Q, k, float(lam),
+                                 _dev_ptr(mask, torch.uint8, "mask"), float(min_score),
+                                 _dev_ptr(out_scores, torch.float32, "out_scores"),
+                                 _dev_ptr(out_ids, torch.int64, "out_ids"),
+                                 _dev_ptr(counts, torch.int32, "counts")), "ic_search_threshold")
+    return out_scores, out_ids, counts
+
+
 def ic_index_destroy(handle: int) -> None:
     _check(load_library().ic_index_destroy(handle), "ic_index_destroy")
 
@@ -227,6 +246,10 @@ class Index:
         if scale.value:
             s = self.arena[scale.value - base: scale.value - base + 4 * n].view(torch.float32)
         return r, s, u
+
+    def search_threshold(self, queries: torch.Tensor, k: int, min_score: float, lam: float = 0.0,
+                         mask: Optional[torch.Tensor] = None):
+        return ic_search_threshold(self.handle, queries, k, min_score, lam, mask)
 
     def set_utility(self, ids: torch.Tensor, util: torch.Tensor) -> None:
         ic_index_set_utility(self.handle, ids, util)

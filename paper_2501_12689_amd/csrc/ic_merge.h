@@ -34,12 +34,15 @@ struct MergeArgs {
     int64_t *out_ids;           // final: [Q][k], or NULL
     uint64_t *kth_out;          // final: [Q] key of the k-th best (0 if there are fewer), or NULL
     const int32_t *only_flagged;  // if not NULL, queries whose block of 64 has flag 0 are left alone
+    float min_score;            // final: entries whose score is below it are dropped (-inf: none)
+    int32_t *out_counts;        // final: [Q] entries kept, or NULL
 };
 
 __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     __shared__ uint64_t buf[kMergeKeys];
     __shared__ int seg_cnt[kMergeMaxSegs];
     __shared__ int seg_off[kMergeMaxSegs + 1];
+    __shared__ int kept;
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
     const int g = blockIdx.y;
@@ -97,17 +100,24 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     }
     __syncthreads();
 
+    if (tid == 0) kept = 0;
+    __syncthreads();
     for (int r = tid; r < a.k; r += 256) {
         const uint64_t key = buf[r];
         if (a.dst) {
             a.dst[((int64_t)q * gridDim.y + g) * a.k + r] = key;
         } else if (a.out_scores) {
-            const bool none = key <= kKeyFloor;
+            const bool none = key <= kKeyFloor || key_score(key) < a.min_score;
             a.out_scores[(int64_t)q * a.k + r] = none ? -INFINITY : key_score(key);
             a.out_ids[(int64_t)q * a.k + r] = none ? (int64_t)-1 : (int64_t)key_id(key);
+            if (!none) atomicAdd(&kept, 1);
         }
     }
     if (!a.dst && a.kth_out && tid == 0) a.kth_out[q] = buf[a.k - 1];
+    if (!a.dst && a.out_scores && a.out_counts) {
+        __syncthreads();
+        if (tid == 0) a.out_counts[q] = kept;
+    }
 }
 
 }  // namespace ic

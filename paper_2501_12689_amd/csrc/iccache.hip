@@ -416,8 +416,13 @@ namespace {
 
 // Chain merge_lists launches from the given first level down to one group per query, then
 // write the final rows.  `m` describes the first level; out pointers are for this query block.
+struct FinalOpts {          // how the last merge level writes a query's row of the result
+    float min_score;        // entries below it are dropped (threshold mode); -inf: keep all
+    int32_t *counts;        // [qc] entries kept per query, or NULL
+};
+
 void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_scores, int64_t *out_ids,
-               const int32_t *only_flagged) {
+               const int32_t *only_flagged, const FinalOpts &fo) {
     hipStream_t st = index->stream;
     uint64_t *ping = index->list_a, *pong = index->list_b;
     m.k = k;
@@ -425,6 +430,8 @@ void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_score
     m.out_scores = out_scores;
     m.out_ids = out_ids;
     m.only_flagged = only_flagged;
+    m.min_score = fo.min_score;
+    m.out_counts = fo.counts;
     for (;;) {
         const int G = std::max(1, (m.nseg + m.segs_per_wg - 1) / m.segs_per_wg);
         m.dst = (G == 1) ? nullptr : ping;
@@ -466,9 +473,30 @@ struct Timer {  // brackets the dominant kernel of a search with events when tim
 
 }  // namespace
 
+namespace {
+ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k, float lambda,
+                      const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, float min_score,
+                      int32_t *out_counts_dev);
+}
+
 ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
                     const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
-    ic_index *index = const_cast<ic_index *>(cindex);
+    return search_impl(const_cast<ic_index *>(cindex), q_dev, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev,
+                       -INFINITY, nullptr);
+}
+
+ic_status ic_search_threshold(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
+                              const uint8_t *mask_dev, float min_score, float *out_scores_dev,
+                              int64_t *out_ids_dev, int32_t *out_counts_dev) {
+    if (min_score != min_score) return IC_ERR_INVALID_ARG;  // NaN
+    return search_impl(const_cast<ic_index *>(cindex), q_dev, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev,
+                       min_score, out_counts_dev);
+}
+
+namespace {
+ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k, float lambda,
+                      const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, float min_score,
+                      int32_t *out_counts_dev) {
     if (!index || Q < 0 || k < 1 || k > index->max_k) return IC_ERR_INVALID_ARG;
     if (Q == 0) return IC_OK;
     if (!q_dev || !out_scores_dev || !out_ids_dev) return IC_ERR_INVALID_ARG;
@@ -514,6 +542,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
         const int q_pad = gemm ? nqb_gemm * ic::kGemmTile : nqb * qb_rows;
         float *out_s = out_scores_dev + q0 * (int64_t)k;
         int64_t *out_i = out_ids_dev + q0 * (int64_t)k;
+        const FinalOpts fo{min_score, out_counts_dev ? out_counts_dev + q0 : nullptr};
 
         // a2: unit-normalise the queries and write them in the store's format
         {
@@ -538,7 +567,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
             m.seg_counts = index->counts;
             m.nseg = 0;
             m.segs_per_wg = 1;
-            run_merge(index, m, qc, k, out_s, out_i, nullptr);
+            run_merge(index, m, qc, k, out_s, out_i, nullptr, fo);
             continue;
         }
 
@@ -666,7 +695,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
             m.total_counts = index->gcount;
             m.nseg = (gcap + m.seg_cap - 1) / m.seg_cap;
             m.segs_per_wg = 1;
-            run_merge(index, m, qc, k, out_s, out_i, nullptr);
+            run_merge(index, m, qc, k, out_s, out_i, nullptr, fo);
         } else {
             if (!timer.start()) return IC_ERR_DEVICE;
             kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
@@ -683,10 +712,11 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
         m.seg_counts = index->counts;
         m.nseg = S;
         m.segs_per_wg = std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
-        run_merge(index, m, qc, k, out_s, out_i, gemm ? index->redo : nullptr);
+        run_merge(index, m, qc, k, out_s, out_i, gemm ? index->redo : nullptr, fo);
     }
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     return IC_OK;
 }
+}  // namespace
 
 }  // extern "C"

@@ -1,0 +1,78 @@
+"""GPU parity of threshold-mode search (entries below a score threshold are dropped), through the
+C ABI: exactly the unthresholded result cut at the threshold, and within the comparison band of
+the CPU reference."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import parity
+import workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2501_12689_amd as p
+    p.load_library()
+    return p
+
+
+CASES = [
+    # store, N, d, Q, k, lam, util, p_valid
+    ("bf16", 60000, 96, 20, 24, 0.0, "none", 1.0),
+    ("fp8", 50000, 128, 70, 40, 0.3, "uniform", 0.9),
+    ("bf16", 280000, 128, 200, 16, 0.2, "beta25", 0.95),     # tiled scan
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_threshold_mode(pkg, oracle, case):
+    store, N, d, Q, k, lam, util, pv = case
+    print(f"[case] threshold mode {case}", flush=True)
+    sys.stdout.flush()
+    cfg = workloads.Config("T", N=N, d=d, clusters=32, Q=Q, k=k, store=store, zipf=1.1, lam=lam, util=util,
+                           p_valid=pv, seed=9400 + CASES.index(case))
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, M = wl.rows(0, N)
+    Qm = wl.queries()
+    sid = pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3
+    ix = pkg.Index(d, N, sid, Q, k, DEV)
+    ix.append(E.to(DEV), None if U is None else U.to(DEV))
+    qd = Qm.to(DEV)
+    md = None if M is None else M.to(DEV)
+    full_s, full_i = ix.search(qd, k, lam, md)
+    En, Un, Mn = E.numpy(), (None if U is None else U.numpy()), (None if M is None else M.numpy())
+    ref_s32, ref_i, ref_s = oracle.search(En, Qm.numpy(), k + 1, lam, Un, Mn)
+    tau = parity.TAU[store]
+    # thresholds: inside the score range of the results (some queries keep all, some a few),
+    # below everything, above everything
+    mid = float(np.median(ref_s[:, k // 2]))
+    for thr in (mid, float(ref_s[:, :k].min()) - 1.0, float(ref_s.max()) + 1.0, float("-inf")):
+        s, i, c = ix.search_threshold(qd, k, thr, lam, md)
+        torch.cuda.synchronize()
+        # (1) exactly the unthresholded result of the same kernels, cut at the threshold
+        keep = full_s >= thr
+        assert torch.equal(i, torch.where(keep, full_i, torch.full_like(full_i, -1)))
+        assert torch.equal(s, torch.where(keep, full_s, torch.full_like(full_s, float("-inf"))))
+        assert torch.equal(c.long(), keep.sum(1))
+        # (2) against the reference, with the band rule applied to the threshold as well: what the
+        # reference keeps with margin tau must be there, nothing may be more than tau below
+        gs, gi, gc = s.cpu().numpy(), i.cpu().numpy(), c.cpu().numpy()
+        for q in range(0, Q, max(1, Q // 16)):
+            top, sc = ref_i[q, :k], ref_s[q, :k]
+            kth1 = ref_s[q, k] if ref_i[q, k] >= 0 else -np.inf
+            must = set(top[(sc >= thr + tau) & (sc >= kth1 + tau) & (top >= 0)].tolist())
+            got = set(gi[q, :gc[q]].tolist())
+            assert must <= got, f"thr={thr} q={q}: missing {must - got}"
+            if gc[q]:
+                ids = gi[q, :gc[q]]
+                true = oracle.scores(En[ids], Qm.numpy()[q:q + 1], lam=lam, U=None if Un is None else Un[ids])[0]
+                assert np.all(true >= thr - tau), f"thr={thr} q={q}: kept a row {thr - true.min():.3g} below"
+                assert np.all(np.abs(true - gs[q, :gc[q]]) < tau)
+            assert np.all(gi[q, gc[q]:] == -1) and np.all(np.isneginf(gs[q, gc[q]:]))
+        print(f"   thr={thr:.4f}: kept per query min {gc.min()} max {gc.max()}", flush=True)
+    ix.close()

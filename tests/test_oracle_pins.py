@@ -404,3 +404,19 @@ def test_search_after_eviction_equals_search_on_the_survivors(oracle):
     s1, i1, _ = oracle.search(E, Qm, 12, 0.3, U, valid)
     s2, i2, _ = oracle.search(E[keep], Qm, 12, 0.3, U[keep], None)
     assert np.array_equal(m[i1], i2) and np.array_equal(s1, s2)
+
+
+def test_threshold_mode_hand_case(oracle):
+    """2-D rows at known angles: the threshold cuts the sorted list where cos drops below it."""
+    ang = np.deg2rad([0.0, 20.0, 40.0, 60.0, 80.0, 120.0])
+    E = np.stack([np.cos(ang), np.sin(ang)], axis=1).astype(np.float32)
+    q = np.array([[1.0, 0.0]], dtype=np.float32)
+    s32, ids, s64, cnt = oracle.search_threshold(E, q, 5, 0.6)        # cos 40 = 0.766, cos 60 = 0.5
+    assert cnt.tolist() == [3] and ids[0].tolist() == [0, 1, 2, -1, -1]
+    assert np.all(np.isneginf(s32[0, 3:])) and np.allclose(s64[0, :3], np.cos(ang[:3]), atol=1e-7)
+    # -inf keeps everything, a threshold above every score keeps nothing
+    assert oracle.search_threshold(E, q, 5, -np.inf)[3].tolist() == [5]
+    assert oracle.search_threshold(E, q, 5, 1.5)[3].tolist() == [0]
+    # prefix property: the kept entries are the head of the unthresholded result
+    full = oracle.search(E, q, 5)[1]
+    assert np.array_equal(ids[0, :3], full[0, :3])
