@@ -14,7 +14,8 @@ the same store (``config.per_Q["4096"]``) and the N = 4,000,000, d = 1024, k = 1
 configuration with utility and mask (``large_batch``, ``roofline_mfma``); and the fp8 store
 (N = 20,000,000, d = 1024, k = 100, built by appends of 100,000 rows) at Q = 1, 64 and 4096
 (``fp8_store``).  ``maintenance`` times the eviction of the masked rows of the d = 1024
-configuration and the compaction that squeezes them out.
+configuration and the compaction that squeezes them out; ``census`` runs a self-search of every
+row of a 1,000,000-row store against all the others.
 
 Prints one JSON line.  ``roofline`` refers to the scan kernel, timed with HIP
 events on the library's stream inside the timed steps; ``cpu_baseline`` is the
@@ -224,6 +225,38 @@ def main() -> int:
         del ix4, mask4, masks, qd, out_s, out_i
         torch.cuda.empty_cache()
 
+    # ---- self-similarity census: every row of a 1M-row store against all the others, k = 1
+    census = None
+    if not args.no_large_batch:
+        c2 = workloads.C2 if args.rows is None else workloads.C2.scaled(N=min(workloads.C2.N, args.rows))
+        wl2 = workloads.Workload(c2, dev)
+        ix2 = pkg.Index(c2.d, c2.N, pkg.STORE_BF16, LARGE_Q, 2, dev)
+        for lo in range(0, c2.N, chunk):
+            n = min(chunk, c2.N - lo)
+            E, U, M = wl2.rows(lo, n)
+            ix2.append(E, None)
+            del E
+        ix2.self_search(0, min(c2.N, 2 * LARGE_Q), 1)          # warm-up
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        top_s, top_i = ix2.self_search(0, c2.N, 1)
+        e1.record()
+        e1.synchronize()
+        cms = e0.elapsed_time(e1)
+        flop = 2.0 * c2.N * c2.N * c2.d
+        census = {
+            "workload": f"self-search of all N={c2.N} rows (d={c2.d} bf16, {c2.clusters}-cluster mixture), k=1, "
+                        "each row left out of its own result",
+            "ms": cms, "rows_per_s": c2.N / (cms * 1e-3), "TFLOPs": flop / (cms * 1e-3) / 1e12,
+            "mfma_frac": flop / (cms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "share_with_a_neighbour_above_0.8": float((top_s[:, 0] > 0.8).float().mean()),
+        }
+        ix2.close()
+        ix2.arena = None
+        del ix2, top_s, top_i
+        torch.cuda.empty_cache()
+
     # ---- fp8 store: N = 20M, d = 1024, k = 100 (built by appends of 100,000 rows), Q = 1, 64, 4096
     fp8 = None
     if not args.no_large_batch and not args.no_fp8:
@@ -316,6 +349,7 @@ def main() -> int:
         "roofline_mfma": roof_mfma,
         "fp8_store": fp8,
         "maintenance": maintenance,
+        "census": census,
     }
     print(json.dumps(line))
     return 0

@@ -126,6 +126,20 @@ ic_status ic_search_threshold(const ic_index *index, const float *q_dev, int64_t
                               float *out_scores_dev, int64_t *out_ids_dev, int32_t *out_counts_dev);
 
 /*
+ * Self-search: the stored rows first_row .. first_row + count - 1 are the queries, and each is
+ * left out of its own result.  This is the measurement behind Sec. 2.3 ("Voluminous requests lead
+ * to pervasive similarity": the top-1 similarity of every request to the others) and the lookup a
+ * semantic cache performs.  The rows are used as stored (already unit length and quantised), so
+ * no query is passed; everything else is as in ic_search.
+ *   k               1 .. max_k - 1 (the candidate lists also hold the row itself)
+ *   out_scores_dev  [count, k] fp32; out_ids_dev [count, k] int64
+ * Errors: INVALID_ARG (range outside the store, k out of range), DEVICE.
+ */
+ic_status ic_self_search(const ic_index *index, int64_t first_row, int64_t count, int32_t k,
+                         float lambda, const uint8_t *mask_dev, float *out_scores_dev,
+                         int64_t *out_ids_dev);
+
+/*
  * Maintenance driven by the Example Manager (Sec. 4.3, "Capping Example Cache Size over
  * Time"): the manager keeps a moving average of every example's gain, decays it (factor 0.9
  * per hour in the paper) and evicts low-utility examples.  The four calls below are what the

@@ -309,3 +309,27 @@ def search_threshold(E, queries, k: int, min_score: float, lam: float = 0.0, U=N
     s64[drop] = -np.inf
     ids[drop] = -1
     return s32, ids, s64, (~drop).sum(axis=1).astype(np.int32)
+
+
+# --------------------------------------------------------------------------
+# Self-search (Sec. 2.3, "Voluminous requests lead to pervasive similarity": the top-1 similarity of
+# every request to the others): the queries are rows of the cache itself, each left out of its
+# own result.
+# --------------------------------------------------------------------------
+
+def self_search(E, first_row: int, count: int, k: int, lam: float = 0.0, U=None, mask=None):
+    """For each row r in [first_row, first_row + count): the best k of the valid rows other than r.
+    Stated through search(): the best k + 1 over all valid rows with r removed (or, when r is not
+    among them, with the last one removed)."""
+    E = np.asarray(E, dtype=np.float32)
+    rows = np.arange(first_row, first_row + count)
+    s32, ids, s64 = search(E, E[rows], k + 1, lam, U, mask)
+    out32 = np.full((count, k), -np.inf, dtype=np.float32)
+    out64 = np.full((count, k), -np.inf, dtype=np.float64)
+    outi = np.full((count, k), -1, dtype=np.int64)
+    for j, r in enumerate(rows):
+        keep = [p for p in range(k + 1) if ids[j, p] != r][:k]
+        outi[j, :len(keep)] = ids[j, keep]
+        out32[j, :len(keep)] = s32[j, keep]
+        out64[j, :len(keep)] = s64[j, keep]
+    return out32, outi, out64

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     ic_index_set_utility,
     ic_search,
     ic_search_threshold,
+    ic_self_search,
     ic_workspace_bytes,
     lib_path,
     load_library,

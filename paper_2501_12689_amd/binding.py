@@ -25,7 +25,7 @@ EXPORTS = (
     "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing",
     "ic_index_scan_time_ms", "ic_status_string",
     "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
-    "ic_search_threshold",
+    "ic_search_threshold", "ic_self_search",
 )
 
 _lib = None
@@ -64,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     L.ic_search.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp]
     L.ic_search_threshold.restype = ctypes.c_int
     L.ic_search_threshold.argtypes = [vp, vp, i64, i32, f32, vp, f32, vp, vp, vp]
+    L.ic_self_search.restype = ctypes.c_int
+    L.ic_self_search.argtypes = [vp, i64, i64, i32, f32, vp, vp, vp]
     L.ic_index_destroy.restype = ctypes.c_int
     L.ic_index_destroy.argtypes = [vp]
     L.ic_index_size.restype = i64
@@ -167,6 +169,18 @@ def ic_search_threshold(handle: int, queries: torch.Tensor, k: int, min_score: f
     return out_scores, out_ids, counts
 
 
+def ic_self_search(handle: int, first_row: int, count: int, k: int, lam: float, mask: Optional[torch.Tensor],
+                   device) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Top-k of the stored rows [first_row, first_row + count) among all other rows."""
+    out_scores = torch.empty((count, k), dtype=torch.float32, device=device)
+    out_ids = torch.empty((count, k), dtype=torch.int64, device=device)
+    _check(load_library().ic_self_search(handle, first_row, count, k, float(lam),
+                                         _dev_ptr(mask, torch.uint8, "mask"),
+                                         _dev_ptr(out_scores, torch.float32, "out_scores"),
+                                         _dev_ptr(out_ids, torch.int64, "out_ids")), "ic_self_search")
+    return out_scores, out_ids
+
+
 def ic_index_destroy(handle: int) -> None:
     _check(load_library().ic_index_destroy(handle), "ic_index_destroy")
 
@@ -250,6 +264,10 @@ class Index:
     def search_threshold(self, queries: torch.Tensor, k: int, min_score: float, lam: float = 0.0,
                          mask: Optional[torch.Tensor] = None):
         return ic_search_threshold(self.handle, queries, k, min_score, lam, mask)
+
+    def self_search(self, first_row: int, count: int, k: int, lam: float = 0.0,
+                    mask: Optional[torch.Tensor] = None):
+        return ic_self_search(self.handle, first_row, count, k, lam, mask, self.device)
 
     def set_utility(self, ids: torch.Tensor, util: torch.Tensor) -> None:
         ic_index_set_utility(self.handle, ids, util)

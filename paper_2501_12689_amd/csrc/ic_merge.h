@@ -36,6 +36,9 @@ struct MergeArgs {
     const int32_t *only_flagged;  // if not NULL, queries whose block of 64 has flag 0 are left alone
     float min_score;            // final: entries whose score is below it are dropped (-inf: none)
     int32_t *out_counts;        // final: [Q] entries kept, or NULL
+    int64_t self_first;         // final: >= 0: query q is stored row self_first + q and is left out of its
+                                // own result (k_out = k - 1 entries are written); -1: off
+    int k_out;                  // final: entries per row of the result
 };
 
 __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
@@ -43,6 +46,7 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     __shared__ int seg_cnt[kMergeMaxSegs];
     __shared__ int seg_off[kMergeMaxSegs + 1];
     __shared__ int kept;
+    __shared__ int self_pos;
     const int tid = threadIdx.x;
     const int q = blockIdx.x;
     const int g = blockIdx.y;
@@ -100,16 +104,24 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     }
     __syncthreads();
 
-    if (tid == 0) kept = 0;
+    if (tid == 0) {
+        kept = 0;
+        self_pos = a.k;  // position of the query's own row among the best k keys (a.k: not there)
+    }
     __syncthreads();
+    if (!a.dst && a.out_scores && a.self_first >= 0) {
+        for (int r = tid; r < a.k; r += 256)
+            if (buf[r] > kKeyFloor && (int64_t)key_id(buf[r]) == a.self_first + q) self_pos = r;
+        __syncthreads();
+    }
     for (int r = tid; r < a.k; r += 256) {
-        const uint64_t key = buf[r];
         if (a.dst) {
-            a.dst[((int64_t)q * gridDim.y + g) * a.k + r] = key;
-        } else if (a.out_scores) {
+            a.dst[((int64_t)q * gridDim.y + g) * a.k + r] = buf[r];
+        } else if (a.out_scores && r < a.k_out) {
+            const uint64_t key = buf[r + (r >= self_pos ? 1 : 0)];  // skip the query's own row
             const bool none = key <= kKeyFloor || key_score(key) < a.min_score;
-            a.out_scores[(int64_t)q * a.k + r] = none ? -INFINITY : key_score(key);
-            a.out_ids[(int64_t)q * a.k + r] = none ? (int64_t)-1 : (int64_t)key_id(key);
+            a.out_scores[(int64_t)q * a.k_out + r] = none ? -INFINITY : key_score(key);
+            a.out_ids[(int64_t)q * a.k_out + r] = none ? (int64_t)-1 : (int64_t)key_id(key);
             if (!none) atomicAdd(&kept, 1);
         }
     }

@@ -73,6 +73,8 @@ struct GemmArgs {
     uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over a sampled tile, id = tile)
     int pilot_stride;
     int64_t tile_stride;     // the t-th row tile of the walk is tile t * tile_stride of the store (1: every tile)
+    int64_t self_first;      // self-search: query q is stored row self_first + q and must not select
+                             // itself (a tile on the diagonal would otherwise list 256 hits); -1: off
     int gq;                  // XCD mapping: query-block groups (1, 2, 4 or 8); 8/gq row classes
 };
 
@@ -523,6 +525,20 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
             thr_s[j] = thr_raw[j] > kKeyFloor ? key_score(thr_raw[j]) : -INFINITY;
             if (q >= a.Q) thr_s[j] = INFINITY;  // padding query: nothing passes
+        }
+        // self-search: in the (at most two) row tiles that hold this query block's own rows, the
+        // dot product of a query with itself is replaced by -inf before the scores are examined
+        // (scales are positive, so the score stays -inf)
+        const int64_t self0 = a.self_first + (int64_t)qb * kGemmTile;  // stored row of the block's first query
+        if (a.self_first >= 0 && row0 < self0 + kGemmTile && row0 + kGemmTile > self0) {
+            const int d0 = (int)(row0 - self0) + wm * 64 + 4 * h - wn * 128 - r32;  // row - query at i = j = v = 0
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (d0 + i * 32 + 8 * (v >> 2) + (v & 3) - j * 32 == 0) acc[i][j][v] = -INFINITY;
         }
         // pass 1: 8 blocks of 16 scores per lane.  A lane whose block reaches the query's
         // threshold (about 17 lanes per tile) copies the block's scores to a small LDS list.

@@ -61,6 +61,12 @@ struct ScanArgs {
     uint64_t *pilot_out;     // PILOT kernels: [Q][S] keys (best score of the slice, id = slice)
     const uint64_t *thr_init;  // full scan: per query, key of a score that >= k rows reach, or NULL
     const int32_t *redo;     // if not NULL (QG == 4 only): query blocks whose flag is 0 are skipped
+    // Set when thr_init was computed by a different kernel (the tiled scan's pilot): that kernel adds
+    // the products in another order, so the score it saw for the k-th row may be a few ulps above
+    // what this kernel computes for the same row, which would then miss its own threshold.  The
+    // starting score is lowered by this much (absolute) plus 2^-20 of its magnitude; a lower start
+    // only admits more candidates, the selection stays exact.
+    float thr_slack;
 };
 
 constexpr int kScanWaves = 4;
@@ -154,7 +160,13 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     auto start_threshold = [&](int q) -> uint64_t {
         if (!a.thr_init || q >= a.Q) return kKeyFloor;
         const uint64_t t0 = a.thr_init[q];
-        return t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
+        if (t0 <= kKeyFloor) return kKeyFloor;
+        if (a.thr_slack > 0.0f) {
+            const float s0 = key_score(t0);
+            const float s1 = s0 - (a.thr_slack + fabsf(s0) * 0x1p-20f);
+            return ((uint64_t)ord_of_score(s1) << 32) - 1ull;
+        }
+        return ((t0 >> 32) << 32) - 1ull;
     };
     if (tid < QB && !PILOT) {
         thr_key[tid] = start_threshold(qb * QB + tid);

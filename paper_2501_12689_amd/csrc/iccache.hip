@@ -419,6 +419,8 @@ namespace {
 struct FinalOpts {          // how the last merge level writes a query's row of the result
     float min_score;        // entries below it are dropped (threshold mode); -inf: keep all
     int32_t *counts;        // [qc] entries kept per query, or NULL
+    int64_t self_first;     // self-search: query j of the block is stored row self_first + j, which is
+                            // left out of its own result (the lists then hold k + 1 keys); -1: off
 };
 
 void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_scores, int64_t *out_ids,
@@ -432,6 +434,8 @@ void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_score
     m.only_flagged = only_flagged;
     m.min_score = fo.min_score;
     m.out_counts = fo.counts;
+    m.self_first = fo.self_first;
+    m.k_out = fo.self_first >= 0 ? k - 1 : k;
     for (;;) {
         const int G = std::max(1, (m.nseg + m.segs_per_wg - 1) / m.segs_per_wg);
         m.dst = (G == 1) ? nullptr : ping;
@@ -476,13 +480,21 @@ struct Timer {  // brackets the dominant kernel of a search with events when tim
 namespace {
 ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k, float lambda,
                       const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, float min_score,
-                      int32_t *out_counts_dev);
+                      int32_t *out_counts_dev, int64_t self_first);
 }
 
 ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
                     const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
     return search_impl(const_cast<ic_index *>(cindex), q_dev, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev,
-                       -INFINITY, nullptr);
+                       -INFINITY, nullptr, -1);
+}
+
+ic_status ic_self_search(const ic_index *cindex, int64_t first_row, int64_t count, int32_t k, float lambda,
+                         const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
+    if (!cindex || first_row < 0 || count < 0 || first_row + count > cindex->n) return IC_ERR_INVALID_ARG;
+    if (k < 1 || k + 1 > cindex->max_k) return IC_ERR_INVALID_ARG;  // the lists hold the row itself as well
+    return search_impl(const_cast<ic_index *>(cindex), nullptr, count, k, lambda, mask_dev, out_scores_dev,
+                       out_ids_dev, -INFINITY, nullptr, first_row);
 }
 
 ic_status ic_search_threshold(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
@@ -490,16 +502,18 @@ ic_status ic_search_threshold(const ic_index *cindex, const float *q_dev, int64_
                               int64_t *out_ids_dev, int32_t *out_counts_dev) {
     if (min_score != min_score) return IC_ERR_INVALID_ARG;  // NaN
     return search_impl(const_cast<ic_index *>(cindex), q_dev, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev,
-                       min_score, out_counts_dev);
+                       min_score, out_counts_dev, -1);
 }
 
 namespace {
-ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k, float lambda,
+ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k_out, float lambda,
                       const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, float min_score,
-                      int32_t *out_counts_dev) {
-    if (!index || Q < 0 || k < 1 || k > index->max_k) return IC_ERR_INVALID_ARG;
+                      int32_t *out_counts_dev, int64_t self_first) {
+    const bool self = self_first >= 0;
+    const int32_t k = self ? k_out + 1 : k_out;  // what the scans and merges select
+    if (!index || Q < 0 || k_out < 1 || k > index->max_k) return IC_ERR_INVALID_ARG;
     if (Q == 0) return IC_OK;
-    if (!q_dev || !out_scores_dev || !out_ids_dev) return IC_ERR_INVALID_ARG;
+    if ((!self && !q_dev) || !out_scores_dev || !out_ids_dev) return IC_ERR_INVALID_ARG;
 
     const Layout &L = index->L;
     const int et = (index->store == IC_STORE_BF16) ? 0 : 1;
@@ -540,12 +554,20 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k,
         const int nqb = (qc + qb_rows - 1) / qb_rows;                      // blocks of the streaming scan
         const int nqb_gemm = (qc + ic::kGemmTile - 1) / ic::kGemmTile;     // blocks of the tiled scan
         const int q_pad = gemm ? nqb_gemm * ic::kGemmTile : nqb * qb_rows;
-        float *out_s = out_scores_dev + q0 * (int64_t)k;
-        int64_t *out_i = out_ids_dev + q0 * (int64_t)k;
-        const FinalOpts fo{min_score, out_counts_dev ? out_counts_dev + q0 : nullptr};
+        float *out_s = out_scores_dev + q0 * (int64_t)k_out;
+        int64_t *out_i = out_ids_dev + q0 * (int64_t)k_out;
+        const FinalOpts fo{min_score, out_counts_dev ? out_counts_dev + q0 : nullptr, self ? self_first + q0 : -1};
 
-        // a2: unit-normalise the queries and write them in the store's format
-        {
+        // a2: unit-normalise the queries and write them in the store's format; a self-search
+        // takes the rows as they are stored (same format, already normalised)
+        if (self) {
+            if (hipMemcpyAsync(index->qbuf, index->rows + (self_first + q0) * (int64_t)L.row_bytes,
+                               (size_t)qc * L.row_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+                return IC_ERR_DEVICE;
+            if (et == 1 && hipMemcpyAsync(index->qscale, index->scale + self_first + q0, (size_t)qc * 4,
+                                          hipMemcpyDeviceToDevice, st) != hipSuccess)
+                return IC_ERR_DEVICE;
+        } else {
             const int grid = (q_pad + 3) / 4;
             const float *src = q_dev + q0 * (int64_t)index->d;
             if (et == 0)
@@ -589,6 +611,7 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k,
         a.pilot_out = index->pilot_keys;
         a.thr_init = nullptr;
         a.redo = nullptr;
+        a.thr_slack = 0.0f;
         a.tile_mul = 1;
 
         // Threshold pilot: a pass over a strided sample of the tiles that keeps the best score
@@ -608,6 +631,7 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k,
             g.nqb = nqb_gemm;
             g.ntiles = (n + ic::kGemmTile - 1) / ic::kGemmTile;
             g.tile_stride = 1;
+            g.self_first = fo.self_first;
             g.gq = 1;  // query-block groups: enough that a group's blocks stay in an XCD's L2
             while (g.gq < 8 && (size_t)((nqb_gemm + g.gq - 1) / g.gq) * ic::kGemmTile * L.row_bytes > kL2Share) g.gq *= 2;
         }
@@ -617,7 +641,8 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k,
             // kPilotSlices.  Starting from its threshold about stride * k rows per query pass.
             ic::GemmArgs p = g;
             const int64_t want = (k <= 16) ? 64 : 32;
-            p.tile_stride = std::max<int64_t>(1, std::min<int64_t>(want, g.ntiles / kPilotSlices));
+            // at least max(k, 64) sampled tiles, so that the k-th largest slice maximum exists
+            p.tile_stride = std::max<int64_t>(1, std::min<int64_t>(want, g.ntiles / std::max(k, 64)));
             p.ntiles = (g.ntiles + p.tile_stride - 1) / p.tile_stride;
             p.pilot_out = index->pilot_keys;
             p.pilot_stride = kPilotSlices;
@@ -683,8 +708,11 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k,
             else launch_gemm<1, false>(gemm_grid, st, g);
             timer.stop();
 
-            // blocks whose candidate lists overflowed are redone by the streaming scan
+            // blocks whose candidate lists overflowed are redone by the streaming scan; the
+            // thresholds come from the other kernel, hence the slack (1e-4 bounds the difference
+            // between two fp32 summation orders of a dot product of unit vectors)
             a.redo = index->redo;
+            a.thr_slack = 1e-4f;
             kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
 
             ic::MergeArgs m{};

@@ -118,3 +118,35 @@ def test_large_batch_in_chunks(pkg, oracle):
     sample = [0, 63, 64, 127, 128, 129, 200, 255, 256, 257, 280, 299]
     parity.check_batch("bf16", s.cpu().numpy(), i.cpu().numpy(), E.numpy(), U.numpy(), M.numpy(), Qm.numpy(),
                        cfg.k, cfg.lam, "chunks", queries=sample)
+
+
+@pytest.mark.parametrize("list_cap", [None, 8])
+def test_large_batch_queries_that_are_stored_rows(pkg, oracle, list_cap):
+    """Queries that sit in the store themselves: the tile on the diagonal has one match per query,
+    which overflows the workgroup's hit list, so those blocks are redone by the streaming scan from
+    thresholds that the tiled pilot computed.  The two kernels round differently; the threshold of a
+    query must still admit the row it came from (regression: such queries lost their k-th result)."""
+    _say(f"tiled scan, queries taken from the store, list_cap={list_cap}")
+    cfg = workloads.Config("G", N=280000, d=128, clusters=32, Q=256, k=4, store="bf16", zipf=1.1, lam=0.0,
+                           util="beta25", p_valid=0.95, seed=8400)
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, M = wl.rows(0, cfg.N)
+    first = 1000
+    Qm = E[first:first + cfg.Q].contiguous()
+    if list_cap is not None:
+        os.environ["IC_GEMM_LIST_CAP"] = str(list_cap)
+    try:
+        ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, cfg.Q, cfg.k, DEV)
+    finally:
+        os.environ.pop("IC_GEMM_LIST_CAP", None)
+    ix.append(E.to(DEV), U.to(DEV))
+    for k in (1, 2, 4):
+        s, i = ix.search(Qm.to(DEV), k, cfg.lam, M.to(DEV))
+        torch.cuda.synchronize()
+        s, i = s.cpu().numpy(), i.cpu().numpy()
+        assert np.all(i >= 0), f"k={k}: queries {np.flatnonzero((i < 0).any(1))[:8]} lost results"
+        valid_self = M.numpy()[first:first + cfg.Q] != 0
+        assert np.all(i[valid_self, 0] == np.arange(first, first + cfg.Q)[valid_self])   # itself comes first
+        parity.check_batch("bf16", s, i, E.numpy(), U.numpy(), M.numpy(), Qm.numpy(), k, cfg.lam, f"stored rows k={k}",
+                           queries=range(0, cfg.Q, 17))
+    ix.close()

@@ -420,3 +420,27 @@ def test_threshold_mode_hand_case(oracle):
     # prefix property: the kept entries are the head of the unthresholded result
     full = oracle.search(E, q, 5)[1]
     assert np.array_equal(ids[0, :3], full[0, :3])
+
+
+def test_self_search_hand_cases(oracle):
+    """Duplicates find each other with cosine exactly 1; a row never returns itself; the result is
+    the plain search with that one row masked out."""
+    e = np.eye(6, dtype=np.float32)
+    E = np.stack([e[0], e[1], e[0] + e[1], e[0], -e[1], 2 * e[1]]).astype(np.float32)
+    s32, ids, s64 = oracle.self_search(E, 0, 6, 2)
+    assert ids[0].tolist() == [3, 2] and s64[0, 0] == 1.0 and abs(s64[0, 1] - 2 ** -0.5) < 1e-12
+    assert ids[3].tolist() == [0, 2]                       # the duplicate of row 0
+    assert ids[1].tolist() == [5, 2] and s64[1, 0] == 1.0  # 2*e1 is the same direction as e1
+    assert ids[4, 0] in (0, 3) and s64[4, 0] == 0.0        # -e1: best others are orthogonal; lowest id first
+    assert ids[4].tolist() == [0, 3]
+    for r in range(6):
+        assert r not in ids[r].tolist()
+    rng = np.random.default_rng(3)
+    E = rng.standard_normal((300, 16)).astype(np.float32)
+    U = rng.random(300).astype(np.float32)
+    M = (rng.random(300) < 0.8).astype(np.uint8)
+    s32, ids, s64 = oracle.self_search(E, 40, 25, 7, 0.4, U, M)
+    for j, r in enumerate(range(40, 65)):
+        Mr = M.copy(); Mr[r] = 0
+        a32, ai, a64 = oracle.search(E, E[r:r + 1], 7, 0.4, U, Mr)
+        assert np.array_equal(ai[0], ids[j]) and np.array_equal(a64[0], s64[j])
