@@ -167,6 +167,55 @@ ic_status ic_index_scale_utility(ic_index *index, float factor);
 ic_status ic_index_invalidate(ic_index *index, const int64_t *ids_dev, int64_t n);
 ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_size);
 
+/*
+ * Cluster pruning in front of the scan (Sec. 4.1, "Two-Stage Scalable Example Selection": the
+ * cached examples are clustered offline into K groups with K-Means; online a request is compared
+ * with the K centroids and then only with the examples of the nearest clusters, K + N/K
+ * comparisons per request instead of N, smallest at K = sqrt(N)).  The result is approximate: an
+ * example outside the probed clusters cannot be returned.
+ *
+ * An ic_ivf sits on top of an index ("base") and lives in its own caller-owned arena.  It holds K
+ * centroids in the store's format, the cluster of every row, and a copy of the base's live rows
+ * sorted by cluster, which the online scan reads as contiguous ranges.  It is a snapshot: after
+ * appends, evictions or a compaction of the base, call ic_ivf_assign (or train) again.
+ *
+ * ic_ivf_workspace_bytes  arena bytes for a base index, K clusters (1 .. 2^20) and searches that
+ *                         probe up to max_probe (1 .. IC_MAX_K) clusters; 0 if out of range.
+ * ic_ivf_create           arena_dev IC_ARENA_ALIGN-aligned.  Uses the base's stream.
+ * ic_ivf_set_centroids    centroids_dev [K, d] fp32 from the caller's own clustering; they are
+ *                         normalised and stored like examples.  Lists must be rebuilt afterwards.
+ * ic_ivf_assign           cluster of a row = its most similar centroid (cosine, ties to the lowest
+ *                         centroid id); then builds the lists and the sorted copy.
+ * ic_ivf_set_assignment   the same from the caller's assignment, assign_dev [size] int32; rows
+ *                         with a cluster outside [0, K) or invalidated rows are in no list.
+ * ic_ivf_update_centroids K-Means update: every centroid becomes the mean direction of its list
+ *                         (sum of the stored unit rows, normalised); an empty list keeps its centroid.
+ * ic_ivf_train            K-Means from the stored rows: the start is the rows at positions
+ *                         floor(c * size / K); then iters times (assign, update), then assign.
+ * ic_ivf_search           as ic_search without a mask, over the rows of the nprobe (1 .. max_probe)
+ *                         nearest clusters of each query only.  Same output conventions.
+ * ic_ivf_view             inspection: cluster of every base row [size], list offsets [K + 1] (into the
+ *                         sorted copy), base id of every sorted row, and the two internal indices
+ *                         (for ic_index_store_view / ic_index_size).  Any out pointer may be NULL.
+ * assign, set_assignment and train wait for the stream (the number of listed rows is needed on the
+ * host); the other calls are asynchronous.  Errors: INVALID_ARG (also: search or update before the
+ * lists exist, assign before centroids exist), CAPACITY, OOM, DEVICE.
+ */
+typedef struct ic_ivf ic_ivf; /* opaque */
+size_t ic_ivf_workspace_bytes(const ic_index *base, int32_t K, int32_t max_probe);
+ic_status ic_ivf_create(ic_ivf **out, ic_index *base, int32_t K, int32_t max_probe, void *arena_dev,
+                        size_t arena_bytes);
+ic_status ic_ivf_destroy(ic_ivf *ivf);
+ic_status ic_ivf_set_centroids(ic_ivf *ivf, const float *centroids_dev);
+ic_status ic_ivf_assign(ic_ivf *ivf);
+ic_status ic_ivf_set_assignment(ic_ivf *ivf, const int32_t *assign_dev);
+ic_status ic_ivf_update_centroids(ic_ivf *ivf);
+ic_status ic_ivf_train(ic_ivf *ivf, int32_t iters);
+ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, int32_t nprobe,
+                        float lambda, float *out_scores_dev, int64_t *out_ids_dev);
+ic_status ic_ivf_view(const ic_ivf *ivf, const int32_t **assign_dev, const int64_t **offsets_dev,
+                      const int32_t **perm_dev, const ic_index **centroids, const ic_index **sorted);
+
 /* Release the handle.  Device memory belongs to the caller and is not touched. */
 ic_status ic_index_destroy(ic_index *index);
 

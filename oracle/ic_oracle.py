@@ -333,3 +333,84 @@ def self_search(E, first_row: int, count: int, k: int, lam: float = 0.0, U=None,
         out32[j, :len(keep)] = s32[j, keep]
         out64[j, :len(keep)] = s64[j, keep]
     return out32, outi, out64
+
+
+# --------------------------------------------------------------------------
+# Cluster pruning (Sec. 4.1, "Two-Stage Scalable Example Selection"): K-Means clusters offline;
+# online the nearest centroids first, then only the examples of those clusters.  Each step is
+# written out plainly in fp64; search() above serves as the "nearest" primitive.
+# --------------------------------------------------------------------------
+
+def _unit(X):
+    X = np.asarray(X, dtype=np.float64)
+    nrm = np.sqrt((X * X).sum(axis=1, keepdims=True))
+    return np.where(nrm > 0, X / np.where(nrm > 0, nrm, 1.0), 0.0)
+
+
+def ivf_assign(E, C):
+    """Cluster of every row: the centroid with the highest cosine, lowest centroid id on ties."""
+    _, ids, _ = search(np.asarray(C, dtype=np.float32), np.asarray(E, dtype=np.float32), 1)
+    return ids[:, 0].astype(np.int32)
+
+
+def ivf_lists(assign, K: int, valid=None):
+    """offsets [K + 1] and, per cluster, the ascending ids of its rows (rows with a cluster outside
+    [0, K) or valid == 0 are in no list)."""
+    assign = np.asarray(assign)
+    ok = (assign >= 0) & (assign < K)
+    if valid is not None:
+        ok &= np.asarray(valid) != 0
+    lists = [np.flatnonzero(ok & (assign == c)).astype(np.int64) for c in range(K)]
+    offsets = np.zeros(K + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum([len(x) for x in lists])
+    return offsets, lists
+
+
+def ivf_update(E, assign, K: int, C_old, valid=None, normalize: bool = True):
+    """K-Means update on the unit sphere: every centroid becomes the normalised sum of the unit
+    rows of its list; an empty list keeps its (normalised) centroid.  fp64.  ``normalize=False``
+    takes the rows as they are (this is how the values a quantised store holds are fed through
+    the same step, as in search())."""
+    Eu = _unit(E) if normalize else np.asarray(E, dtype=np.float64)
+    out = _unit(C_old).copy()
+    _, lists = ivf_lists(assign, K, valid)
+    for c, ids in enumerate(lists):
+        if len(ids):
+            out[c] = _unit(Eu[ids].sum(axis=0, keepdims=True))[0]
+    return out
+
+
+def ivf_kmeans(E, K: int, iters: int):
+    """K-Means as the library runs it: start from the rows at positions floor(c * N / K), then
+    ``iters`` times (assign, update), then a final assign.  Returns (centroids fp64, assign)."""
+    E = np.asarray(E, dtype=np.float32)
+    N = E.shape[0]
+    C = _unit(E[[(c * N) // K for c in range(K)]])
+    for _ in range(iters):
+        C = ivf_update(E, ivf_assign(E, C), K, C)
+    return C, ivf_assign(E, C)
+
+
+def ivf_search(E, C, assign, queries, k: int, nprobe: int, lam: float = 0.0, U=None, valid=None):
+    """Top-k over the rows of the nprobe nearest clusters of each query.
+    Returns (scores fp32, ids, scores fp64, probes [Q, nprobe])."""
+    E = np.asarray(E, dtype=np.float32)
+    Qm = np.asarray(queries, dtype=np.float32)
+    K = np.asarray(C).shape[0]
+    _, probes, _ = search(np.asarray(C, dtype=np.float32), Qm, nprobe)
+    _, lists = ivf_lists(assign, K, valid)
+    Q = Qm.shape[0]
+    s32 = np.full((Q, k), -np.inf, dtype=np.float32)
+    s64 = np.full((Q, k), -np.inf, dtype=np.float64)
+    ids = np.full((Q, k), -1, dtype=np.int64)
+    for q in range(Q):
+        cand = np.concatenate([lists[c] for c in probes[q] if c >= 0] + [np.zeros(0, np.int64)])
+        if not len(cand):
+            continue
+        cand.sort()
+        a32, ai, a64 = search(E[cand], Qm[q:q + 1], k, lam, None if U is None else np.asarray(U)[cand])
+        m = int((ai[0] >= 0).sum())
+        ids[q, :m] = cand[ai[0, :m]]
+        s32[q, :m] = a32[0, :m]
+        s64[q, :m] = a64[0, :m]
+    return s32, ids, s64, probes

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     STORE_FP8_E4M3,
     ICError,
     Index,
+    Ivf,
     ic_index_append,
     ic_index_compact,
     ic_index_create,

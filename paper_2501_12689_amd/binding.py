@@ -26,6 +26,8 @@ EXPORTS = (
     "ic_index_scan_time_ms", "ic_status_string",
     "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
     "ic_search_threshold", "ic_self_search",
+    "ic_ivf_workspace_bytes", "ic_ivf_create", "ic_ivf_destroy", "ic_ivf_set_centroids", "ic_ivf_assign",
+    "ic_ivf_set_assignment", "ic_ivf_update_centroids", "ic_ivf_train", "ic_ivf_search", "ic_ivf_view",
 )
 
 _lib = None
@@ -87,6 +89,17 @@ def load_library() -> ctypes.CDLL:
     L.ic_index_invalidate.argtypes = [vp, vp, i64]
     L.ic_index_compact.restype = ctypes.c_int
     L.ic_index_compact.argtypes = [vp, vp, ctypes.POINTER(i64)]
+    L.ic_ivf_workspace_bytes.restype = ctypes.c_size_t
+    L.ic_ivf_workspace_bytes.argtypes = [vp, i32, i32]
+    L.ic_ivf_create.restype = ctypes.c_int
+    L.ic_ivf_create.argtypes = [ctypes.POINTER(vp), vp, i32, i32, vp, ctypes.c_size_t]
+    for name, args in (("ic_ivf_destroy", [vp]), ("ic_ivf_set_centroids", [vp, vp]), ("ic_ivf_assign", [vp]),
+                       ("ic_ivf_set_assignment", [vp, vp]), ("ic_ivf_update_centroids", [vp]),
+                       ("ic_ivf_train", [vp, i32]),
+                       ("ic_ivf_search", [vp, vp, i64, i32, i32, f32, vp, vp]),
+                       ("ic_ivf_view", [vp] + [ctypes.POINTER(vp)] * 5)):
+        getattr(L, name).restype = ctypes.c_int
+        getattr(L, name).argtypes = args
     L.ic_status_string.restype = ctypes.c_char_p
     L.ic_status_string.argtypes = [ctypes.c_int]
     _lib = L
@@ -287,6 +300,84 @@ class Index:
     def close(self) -> None:
         if getattr(self, "handle", None):
             ic_index_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Ivf:
+    """Cluster pruning on top of an ``Index``: owns its arena and the handle."""
+
+    def __init__(self, base: Index, K: int, max_probe: int):
+        L = load_library()
+        self.base, self.K, self.max_probe = base, int(K), int(max_probe)
+        nbytes = int(L.ic_ivf_workspace_bytes(base.handle, K, max_probe))
+        if nbytes == 0:
+            raise ValueError("ic_ivf_workspace_bytes rejected the arguments")
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=base.device)
+        h = ctypes.c_void_p()
+        _check(L.ic_ivf_create(ctypes.byref(h), base.handle, K, max_probe, self.arena.data_ptr(), nbytes),
+               "ic_ivf_create")
+        self.handle = h.value
+
+    def set_centroids(self, centroids: torch.Tensor) -> None:
+        assert centroids.shape == (self.K, self.base.d)
+        _check(load_library().ic_ivf_set_centroids(self.handle, _dev_ptr(centroids, torch.float32, "centroids")),
+               "ic_ivf_set_centroids")
+
+    def assign(self) -> None:
+        _check(load_library().ic_ivf_assign(self.handle), "ic_ivf_assign")
+
+    def set_assignment(self, assign: torch.Tensor) -> None:
+        assert assign.numel() == len(self.base)
+        _check(load_library().ic_ivf_set_assignment(self.handle, _dev_ptr(assign, torch.int32, "assign")),
+               "ic_ivf_set_assignment")
+
+    def update_centroids(self) -> None:
+        _check(load_library().ic_ivf_update_centroids(self.handle), "ic_ivf_update_centroids")
+
+    def train(self, iters: int) -> None:
+        _check(load_library().ic_ivf_train(self.handle, iters), "ic_ivf_train")
+
+    def search(self, queries: torch.Tensor, k: int, nprobe: int, lam: float = 0.0):
+        Q = queries.shape[0]
+        out_scores = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
+        out_ids = torch.empty((Q, k), dtype=torch.int64, device=queries.device)
+        _check(load_library().ic_ivf_search(self.handle, _dev_ptr(queries, torch.float32, "queries"), Q, k, nprobe,
+                                            float(lam), out_scores.data_ptr(), out_ids.data_ptr()), "ic_ivf_search")
+        return out_scores, out_ids
+
+    def view(self):
+        """(assign int32 [size], offsets int64 [K+1], perm int32 [listed rows], centroid rows uint8 [K, row_bytes],
+        centroid scales | None) as views of the arena."""
+        L = load_library()
+        a, o, p, c, s = (ctypes.c_void_p() for _ in range(5))
+        _check(L.ic_ivf_view(self.handle, ctypes.byref(a), ctypes.byref(o), ctypes.byref(p), ctypes.byref(c),
+                             ctypes.byref(s)), "ic_ivf_view")
+        base = self.arena.data_ptr()
+        n = len(self.base)
+        assign = self.arena[a.value - base: a.value - base + 4 * n].view(torch.int32)
+        offsets = self.arena[o.value - base: o.value - base + 8 * (self.K + 1)].view(torch.int64)
+        listed = int(L.ic_index_size(s.value))
+        perm = self.arena[p.value - base: p.value - base + 4 * listed].view(torch.int32)
+        rows, stride = ctypes.c_void_p(), ctypes.c_int64()
+        scale = ctypes.c_void_p()
+        _check(L.ic_index_store_view(c.value, ctypes.byref(rows), ctypes.byref(stride), ctypes.byref(scale), None),
+               "ic_index_store_view")
+        rb = stride.value
+        crow = self.arena[rows.value - base: rows.value - base + self.K * rb].view(self.K, rb)
+        cscale = None
+        if scale.value:
+            cscale = self.arena[scale.value - base: scale.value - base + 4 * self.K].view(torch.float32)
+        return assign, offsets, perm, crow, cscale
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            _check(load_library().ic_ivf_destroy(self.handle), "ic_ivf_destroy")
             self.handle = None
 
     def __del__(self):

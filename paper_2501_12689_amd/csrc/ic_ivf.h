@@ -1,0 +1,171 @@
+// Cluster pruning in front of the scan (Sec. 4.1, "Two-Stage Scalable Example Selection"): the
+// cached examples are clustered offline into K groups with K-Means; online a request is compared
+// with the K centroids first and then only with the examples of the nearest clusters, K + N/K
+// comparisons instead of N, smallest at K = sqrt(N).
+//
+// Kernels of the offline part: lists from an assignment (histogram, offsets, scatter), the copy of
+// the store sorted by cluster that the online scan reads as contiguous ranges, and the K-Means
+// update step (mean direction of every cluster).
+#pragma once
+#include "ic_common.h"
+
+namespace ic {
+
+// assign[i] = cluster of row i from a k = 1 search result (ids [n] int64, -1 = none)
+__global__ void ivf_take_assignment(const int64_t *__restrict__ ids, int64_t n, int32_t *__restrict__ assign) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) assign[i] = (int32_t)ids[i];
+}
+
+__global__ void ivf_zero_i64(int64_t *__restrict__ p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// counts[c] = live rows assigned to cluster c (rows with assign outside [0, K) or live == 0 are in no list)
+__global__ void ivf_histogram(const int32_t *__restrict__ assign, const uint8_t *__restrict__ live, int64_t n,
+                              int32_t K, int64_t *__restrict__ counts) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t c = assign[i];
+    if (c >= 0 && c < K && live[i] != 0) atomicAdd(reinterpret_cast<unsigned long long *>(counts + c), 1ull);
+}
+
+// offsets[c] = rows in clusters before c, offsets[K] = rows in lists; cursor[c] = offsets[c].
+// counts and offsets may not alias.  One workgroup.
+__global__ __launch_bounds__(256) void ivf_offsets(const int64_t *__restrict__ counts, int32_t K,
+                                                   int64_t *__restrict__ offsets, int64_t *__restrict__ cursor) {
+    __shared__ int64_t tile[256];
+    __shared__ int64_t carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int32_t lo = 0; lo < K; lo += 256) {
+        const int32_t c = lo + threadIdx.x;
+        const int64_t v = c < K ? counts[c] : 0;
+        tile[threadIdx.x] = v;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            const int64_t add = threadIdx.x >= off ? tile[threadIdx.x - off] : 0;
+            __syncthreads();
+            tile[threadIdx.x] += add;
+            __syncthreads();
+        }
+        if (c < K) {
+            offsets[c] = carry + tile[threadIdx.x] - v;
+            cursor[c] = carry + tile[threadIdx.x] - v;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) carry += tile[255];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) offsets[K] = carry;
+}
+
+// perm[position] = row, positions of a cluster handed out by an atomic cursor (the order inside a
+// list is not fixed; nothing depends on it: ids are mapped back before ties are broken)
+__global__ void ivf_scatter(const int32_t *__restrict__ assign, const uint8_t *__restrict__ live, int64_t n,
+                            int32_t K, int64_t *__restrict__ cursor, int32_t *__restrict__ perm) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t c = assign[i];
+    if (c < 0 || c >= K || live[i] == 0) return;
+    const int64_t pos = (int64_t)atomicAdd(reinterpret_cast<unsigned long long *>(cursor + c), 1ull);
+    perm[pos] = (int32_t)i;
+}
+
+// sorted copy: row j of dst = row perm[j] of src, with its utility and scale
+__global__ __launch_bounds__(256) void ivf_gather(const uint8_t *__restrict__ src_rows, const float *__restrict__ src_util,
+                                                  const float *__restrict__ src_scale, int row_bytes,
+                                                  const int32_t *__restrict__ perm, const int64_t *__restrict__ total,
+                                                  uint8_t *__restrict__ dst_rows, float *__restrict__ dst_util,
+                                                  float *__restrict__ dst_scale, uint8_t *__restrict__ dst_live) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int64_t n = *total;
+    for (int64_t j = wave; j < n; j += nwaves) {
+        const int64_t r = perm[j];
+        const i32x4 *s = reinterpret_cast<const i32x4 *>(src_rows + r * (int64_t)row_bytes);
+        i32x4 *d = reinterpret_cast<i32x4 *>(dst_rows + j * (int64_t)row_bytes);
+        for (int c = lane; c < row_bytes / 16; c += 64) d[c] = s[c];
+        if (lane == 0) {
+            dst_util[j] = src_util[r];
+            if (src_scale) dst_scale[j] = src_scale[r];
+            dst_live[j] = 1;
+        }
+    }
+}
+
+// value of an OCP E4M3 code (no infinities; the two NaN codes do not occur in a store)
+__device__ __forceinline__ float e4m3_value(uint32_t c) {
+    const uint32_t e = (c >> 3) & 15u, m = c & 7u;
+    const float mag = e == 0 ? (float)m * 0x1p-9f : __uint_as_float(((e + 120u) << 23) | (m << 20));
+    return (c & 0x80u) ? -mag : mag;
+}
+
+// element e of a stored row as fp32 (without the fp8 row scale)
+template <int ET>
+__device__ __forceinline__ float stored_element(const uint8_t *row, int e) {
+    if (ET == 0) return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(row)[e] << 16);
+    return e4m3_value(row[e]);
+}
+
+// K-Means update: sums[c] = sum of the (unit) rows of cluster c, fp32 [K, d]; a cluster without
+// rows keeps its centroid (its stored row is decoded instead).  One workgroup per cluster, fp64
+// accumulators, the four wavefronts' partial sums added in a fixed order.  rows are the sorted
+// copy, so the cluster is the range [offsets[c], offsets[c + 1]).
+template <int ET>
+__global__ __launch_bounds__(256) void ivf_cluster_sums(const uint8_t *__restrict__ rows, const float *__restrict__ scale,
+                                                        int row_bytes, int d, const int64_t *__restrict__ offsets,
+                                                        const uint8_t *__restrict__ cent_rows,
+                                                        const float *__restrict__ cent_scale, float *__restrict__ sums) {
+    constexpr int kMaxPerLane = 32;  // 2048 elements per row at most
+    __shared__ double part[4][64];
+    const int c = blockIdx.x;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t lo = offsets[c], hi = offsets[c + 1];
+    double acc[kMaxPerLane];
+#pragma unroll
+    for (int j = 0; j < kMaxPerLane; ++j) acc[j] = 0.0;
+    if (lo == hi) {
+        if (w == 0) {
+            const uint8_t *row = cent_rows + (int64_t)c * row_bytes;
+            const float sc = (ET == 1) ? cent_scale[c] : 1.0f;
+            for (int e = lane; e < d; e += 64) sums[(int64_t)c * d + e] = stored_element<ET>(row, e) * sc;
+        }
+        return;
+    }
+    for (int64_t r = lo + w; r < hi; r += 4) {
+        const uint8_t *row = rows + r * (int64_t)row_bytes;
+        const double sc = (ET == 1) ? (double)scale[r] : 1.0;
+#pragma unroll
+        for (int j = 0; j < kMaxPerLane; ++j) {
+            const int e = lane + 64 * j;
+            if (e < d) acc[j] += (double)stored_element<ET>(row, e) * sc;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kMaxPerLane; ++j) {
+        if (64 * j >= d) break;
+        part[w][lane] = acc[j];
+        __syncthreads();
+        if (w == 0) {
+            const int e = lane + 64 * j;
+            if (e < d) sums[(int64_t)c * d + e] = (float)(((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]);
+        }
+        __syncthreads();
+    }
+}
+
+// K-Means start: sums[c] = the stored row at position floor(c * n / K), decoded to fp32 [K, d]
+template <int ET>
+__global__ void ivf_rows_as_centroids(const uint8_t *__restrict__ rows, const float *__restrict__ scale,
+                                      int row_bytes, int d, int64_t n, int32_t K, float *__restrict__ sums) {
+    const int c = blockIdx.x;
+    const int64_t r = (int64_t)c * n / K;
+    const uint8_t *row = rows + r * (int64_t)row_bytes;
+    const float sc = (ET == 1) ? scale[r] : 1.0f;
+    for (int e = threadIdx.x; e < d; e += blockDim.x) sums[(int64_t)c * d + e] = stored_element<ET>(row, e) * sc;
+}
+
+}  // namespace ic

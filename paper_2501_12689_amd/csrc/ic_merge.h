@@ -39,6 +39,9 @@ struct MergeArgs {
     int64_t self_first;         // final: >= 0: query q is stored row self_first + q and is left out of its
                                 // own result (k_out = k - 1 entries are written); -1: off
     int k_out;                  // final: entries per row of the result
+    const int32_t *id_map;      // if not NULL: the keys' ids are positions in a reordered copy of the store;
+                                // they are replaced by id_map[position] as the keys are loaded, so that ties
+                                // are broken by the examples' own ids
 };
 
 __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
@@ -84,7 +87,12 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
         const int c = seg_cnt[s];
         const uint64_t *sp = src + (int64_t)(seg0 + s) * a.seg_stride;
         uint64_t *dp = buf + seg_off[s];
-        for (int idx = tid; idx < c; idx += 256) dp[idx] = sp[idx];
+        for (int idx = tid; idx < c; idx += 256) {
+            uint64_t key = sp[idx];
+            if (a.id_map && key > kKeyFloor)
+                key = (key & 0xFFFFFFFF00000000ull) | (uint64_t)(0xFFFFFFFFu - (uint32_t)a.id_map[key_id(key)]);
+            dp[idx] = key;
+        }
     }
 
     for (int size = 2; size <= P; size <<= 1) {

@@ -67,6 +67,13 @@ struct ScanArgs {
     // starting score is lowered by this much (absolute) plus 2^-20 of its magnitude; a lower start
     // only admits more candidates, the selection stays exact.
     float thr_slack;
+    // Task launches (TASK = true, one query group): workgroup column y is a (query, list) pair of a
+    // cluster-pruned search.  Query y / task_nprobe is compared with the rows of one cluster, the
+    // contiguous range [offsets[c], offsets[c + 1]) of a store sorted by cluster, c =
+    // task_cluster[y] (-1: no list).  regions / counts are indexed by y instead of the query.
+    const int64_t *task_cluster;
+    const int64_t *task_offsets;
+    int task_nprobe;
 };
 
 constexpr int kScanWaves = 4;
@@ -133,8 +140,9 @@ __device__ __forceinline__ void compact_region(uint64_t *reg, int c, int k, uint
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int ET, int QG, int CPW, bool PILOT>
+template <int ET, int QG, int CPW, bool PILOT, bool TASK = false>
 __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
+    static_assert(!TASK || (QG == 1 && !PILOT), "task launches use one query group and no pilot");
     constexpr int QB = QG * 16;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds_raw = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
@@ -151,6 +159,17 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     const int c4 = lane >> 4;   // 16-byte column within a 64-byte chunk; D rows 4*c4 .. 4*c4+3
     const int s = blockIdx.x;
     const int qb = blockIdx.y;
+    // rows this workgroup may select from: the whole store, or one cluster's range
+    int64_t row_lo = 0, row_hi = a.n;
+    if (TASK) {
+        const int64_t c = a.task_cluster[qb];
+        row_lo = c >= 0 ? a.task_offsets[c] : 0;
+        row_hi = c >= 0 ? a.task_offsets[c + 1] : 0;
+        if (row_lo >= row_hi) {  // no list, or an empty one: nothing to hand to the merge
+            if (tid == 0) a.counts[(int64_t)qb * a.S + s] = 0;
+            return;
+        }
+    }
     const int nchunks = a.row_bytes >> 6;
     const int chunk0 = w * CPW;
     if (a.redo && a.redo[qb] == 0) return;  // whole workgroup: this block needs no second pass
@@ -169,7 +188,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
         return ((t0 >> 32) << 32) - 1ull;
     };
     if (tid < QB && !PILOT) {
-        thr_key[tid] = start_threshold(qb * QB + tid);
+        thr_key[tid] = TASK ? kKeyFloor : start_threshold(qb * QB + tid);
         cnt[tid] = 0u;
     }
 
@@ -184,7 +203,8 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     i32x4 qf[QG][CPW];
 #pragma unroll
     for (int g = 0; g < QG; ++g) {
-        const uint8_t *qrow = a.qbuf + (int64_t)(qb * QB + g * 16 + r16) * a.row_bytes + c4 * 16;
+        // task launches: all 16 query slots hold the task's one query (slot 0 is the one that counts)
+        const uint8_t *qrow = a.qbuf + (int64_t)(TASK ? qb / a.task_nprobe : qb * QB + g * 16 + r16) * a.row_bytes + c4 * 16;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             qf[g][c] = *reinterpret_cast<const i32x4 *>(qrow + coff[c]);
@@ -194,20 +214,21 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
 
     // selection state of the query this lane serves in the epilogue (wave g == w)
     const int jl = (w < QG ? w : 0) * 16 + r16;  // query within block
-    const int jq = qb * QB + jl;                 // query within this launch
-    const bool q_live = (w < QG) && (jq < a.Q);
+    const int jq = TASK ? qb / a.task_nprobe : qb * QB + jl;  // query within this launch
+    const bool q_live = (w < QG) && (jq < a.Q) && (!TASK || r16 == 0);
     float q_scale = 1.0f;
     if (ET == 1 && q_live) q_scale = a.q_scale[jq];
     uint64_t *region = regs + jl * a.cap;
-    uint64_t thr_k = q_live ? start_threshold(jq) : kKeyFloor;
+    uint64_t thr_k = (q_live && !TASK) ? start_threshold(jq) : kKeyFloor;
     float thr_s = thr_k > kKeyFloor ? key_score(thr_k + 1ull) : -INFINITY;
     float best = -INFINITY;  // pilot mode: best score of this lane's rows
 
     __syncthreads();
 
     const int64_t tile_mul = a.tile_mul;
-    const int64_t ntiles = (((a.n + 15) >> 4) + tile_mul - 1) / tile_mul;  // tiles this launch visits
-    const int64_t last_row = a.n - 1;
+    const int64_t tile0 = row_lo >> 4;  // first tile of the range (0 unless TASK)
+    const int64_t ntiles = ((((row_hi + 15) >> 4) - tile0) + tile_mul - 1) / tile_mul;  // tiles this launch visits
+    const int64_t last_row = row_hi - 1;
     const int64_t S = a.S;
 
     // Everything a tile needs from global memory, requested kStages - 1 tiles ahead: two tiles for
@@ -223,7 +244,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     };
     Stage st[kStages];
     auto load_stage = [&](int64_t t, Stage &x) {
-        const int64_t tt = (t < ntiles ? t : ntiles - 1) * tile_mul;
+        const int64_t tt = tile0 + (t < ntiles ? t : ntiles - 1) * tile_mul;
         int64_t r = tt * 16 + r16;
         if (r > last_row) r = last_row;  // ragged tail: re-read a valid row, masked out later
         const uint8_t *p = a.store + r * (int64_t)a.row_bytes + c4 * 16;
@@ -282,7 +303,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                 __syncthreads();  // the partial tiles may be overwritten from here on
 
                 if (w < QG) {
-                    const int64_t i0 = t * tile_mul * 16 + c4 * 4;
+                    const int64_t i0 = (tile0 + t * tile_mul) * 16 + c4 * 4;
                     uint64_t key[4];
                     uint32_t pend = 0;
 #pragma unroll
@@ -290,6 +311,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                         float sc = (ET == 1) ? sum[v] * (cur.rsc[v] * q_scale) + cur.bias[v]
                                              : sum[v] + cur.bias[v];
                         if (i0 + v > last_row) sc = -INFINITY;
+                        if (TASK && i0 + v < row_lo) sc = -INFINITY;  // the first tile may start in the previous list
                         if (PILOT) {
                             best = fmaxf(best, sc);
                             continue;
@@ -350,10 +372,10 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     }
     // hand the regions to the merge kernel
     if (w < QG) {
-        for (int j = 0; j < 16; ++j) {
+        for (int j = 0; j < (TASK ? 1 : 16); ++j) {  // task launches: only slot 0 holds a result
             const int ql = w * 16 + j;
-            const int qq = qb * QB + ql;
-            if (qq >= a.Q) break;
+            const int qq = TASK ? qb : qb * QB + ql;     // row of regions / counts
+            if (!TASK && qq >= a.Q) break;
             uint32_t c = __hip_atomic_load(&cnt[ql], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
             if (c > (uint32_t)a.cap) c = (uint32_t)a.cap;
             uint64_t *out = a.regions + ((int64_t)qq * a.S + s) * a.cap;

@@ -12,6 +12,7 @@
 #include "ic_common.h"
 #include "ic_merge.h"
 #include "ic_quantize.h"
+#include "ic_ivf.h"
 #include "ic_maintain.h"
 #include "ic_scan_gemm.h"
 #include "ic_scan_stream.h"
@@ -138,6 +139,22 @@ const ScanFn kScanTable[2][2][3][8] = {
      {IC_SCAN_ROW(1, 1, true), IC_SCAN_ROW(1, 2, true), IC_SCAN_ROW(1, 4, true)}},
 };
 #undef IC_SCAN_ROW
+
+template <int ET, int CPW>
+void launch_scan_task(dim3 grid, hipStream_t st, const ic::ScanArgs &a) {
+    static const hipError_t allowed = hipFuncSetAttribute(
+        reinterpret_cast<const void *>(&ic::scan_stream<ET, 1, CPW, false, true>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::scan_lds_bytes(1, ic::kMaxCap));
+    (void)allowed;
+    hipLaunchKernelGGL((ic::scan_stream<ET, 1, CPW, false, true>), grid, dim3(256), ic::scan_lds_bytes(1, a.cap), st, a);
+}
+// cluster-range scans: [element type][chunks per wavefront - 1]
+const ScanFn kTaskTable[2][8] = {
+    {launch_scan_task<0, 1>, launch_scan_task<0, 2>, launch_scan_task<0, 3>, launch_scan_task<0, 4>,
+     launch_scan_task<0, 5>, launch_scan_task<0, 6>, launch_scan_task<0, 7>, launch_scan_task<0, 8>},
+    {launch_scan_task<1, 1>, launch_scan_task<1, 2>, launch_scan_task<1, 3>, launch_scan_task<1, 4>,
+     launch_scan_task<1, 5>, launch_scan_task<1, 6>, launch_scan_task<1, 7>, launch_scan_task<1, 8>},
+};
 
 template <int ET, bool PILOT>
 void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
@@ -447,6 +464,7 @@ void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_score
         m.seg_cap = k;
         m.seg_counts = nullptr;
         m.total_counts = nullptr;
+        m.id_map = nullptr;  // applied by the first level
         m.nseg = G;
         m.segs_per_wg = std::min(ic::kMergeMaxSegs, ic::kMergeKeys / k);
         std::swap(ping, pong);
@@ -478,42 +496,61 @@ struct Timer {  // brackets the dominant kernel of a search with events when tim
 }  // namespace
 
 namespace {
-ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k, float lambda,
-                      const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, float min_score,
-                      int32_t *out_counts_dev, int64_t self_first);
+struct SearchReq {                      // where the queries come from and how the result rows are written
+    const float *q_dev = nullptr;       // [Q, d] fp32 queries to normalise and quantise, or
+    const uint8_t *q_rows = nullptr;    // [Q] rows already in the store's format, row_bytes apart,
+    const float *q_row_scale = nullptr; //     with their scales (fp8)
+    int64_t self_first = -1;            // q_rows are this index's own rows from here on: each is left out
+    float min_score = -INFINITY;        // threshold mode
+    int32_t *counts = nullptr;
+};
+ic_status search_impl(ic_index *index, int64_t Q, int32_t k, float lambda, const uint8_t *mask_dev,
+                      float *out_scores_dev, int64_t *out_ids_dev, const SearchReq &req);
 }
 
 ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
                     const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
-    return search_impl(const_cast<ic_index *>(cindex), q_dev, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev,
-                       -INFINITY, nullptr, -1);
+    SearchReq r;
+    r.q_dev = q_dev;
+    if (Q > 0 && !q_dev) return IC_ERR_INVALID_ARG;
+    return search_impl(const_cast<ic_index *>(cindex), Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 ic_status ic_self_search(const ic_index *cindex, int64_t first_row, int64_t count, int32_t k, float lambda,
                          const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
     if (!cindex || first_row < 0 || count < 0 || first_row + count > cindex->n) return IC_ERR_INVALID_ARG;
     if (k < 1 || k + 1 > cindex->max_k) return IC_ERR_INVALID_ARG;  // the lists hold the row itself as well
-    return search_impl(const_cast<ic_index *>(cindex), nullptr, count, k, lambda, mask_dev, out_scores_dev,
-                       out_ids_dev, -INFINITY, nullptr, first_row);
+    SearchReq r;
+    r.q_rows = cindex->rows + first_row * (int64_t)cindex->L.row_bytes;
+    r.q_row_scale = cindex->scale ? cindex->scale + first_row : nullptr;
+    r.self_first = first_row;
+    return search_impl(const_cast<ic_index *>(cindex), count, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 ic_status ic_search_threshold(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
                               const uint8_t *mask_dev, float min_score, float *out_scores_dev,
                               int64_t *out_ids_dev, int32_t *out_counts_dev) {
     if (min_score != min_score) return IC_ERR_INVALID_ARG;  // NaN
-    return search_impl(const_cast<ic_index *>(cindex), q_dev, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev,
-                       min_score, out_counts_dev, -1);
+    SearchReq r;
+    r.q_dev = q_dev;
+    r.min_score = min_score;
+    r.counts = out_counts_dev;
+    if (Q > 0 && !q_dev) return IC_ERR_INVALID_ARG;
+    return search_impl(const_cast<ic_index *>(cindex), Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 namespace {
-ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k_out, float lambda,
-                      const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, float min_score,
-                      int32_t *out_counts_dev, int64_t self_first) {
+ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, const uint8_t *mask_dev,
+                      float *out_scores_dev, int64_t *out_ids_dev, const SearchReq &req) {
+    const float *q_dev = req.q_dev;
+    const float min_score = req.min_score;
+    int32_t *out_counts_dev = req.counts;
+    const int64_t self_first = req.self_first;
     const bool self = self_first >= 0;
     const int32_t k = self ? k_out + 1 : k_out;  // what the scans and merges select
     if (!index || Q < 0 || k_out < 1 || k > index->max_k) return IC_ERR_INVALID_ARG;
     if (Q == 0) return IC_OK;
-    if ((!self && !q_dev) || !out_scores_dev || !out_ids_dev) return IC_ERR_INVALID_ARG;
+    if ((!q_dev && !req.q_rows) || !out_scores_dev || !out_ids_dev) return IC_ERR_INVALID_ARG;
 
     const Layout &L = index->L;
     const int et = (index->store == IC_STORE_BF16) ? 0 : 1;
@@ -560,11 +597,11 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k_
 
         // a2: unit-normalise the queries and write them in the store's format; a self-search
         // takes the rows as they are stored (same format, already normalised)
-        if (self) {
-            if (hipMemcpyAsync(index->qbuf, index->rows + (self_first + q0) * (int64_t)L.row_bytes,
-                               (size_t)qc * L.row_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        if (req.q_rows) {
+            if (hipMemcpyAsync(index->qbuf, req.q_rows + q0 * (int64_t)L.row_bytes, (size_t)qc * L.row_bytes,
+                               hipMemcpyDeviceToDevice, st) != hipSuccess)
                 return IC_ERR_DEVICE;
-            if (et == 1 && hipMemcpyAsync(index->qscale, index->scale + self_first + q0, (size_t)qc * 4,
+            if (et == 1 && hipMemcpyAsync(index->qscale, req.q_row_scale + q0, (size_t)qc * 4,
                                           hipMemcpyDeviceToDevice, st) != hipSuccess)
                 return IC_ERR_DEVICE;
         } else {
@@ -594,7 +631,7 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k_
         }
 
         // a3-a5: similarity, score epilogue and selection
-        ic::ScanArgs a;
+        ic::ScanArgs a{};
         a.store = index->rows;
         a.n = n;
         a.row_bytes = L.row_bytes;
@@ -746,5 +783,311 @@ ic_status search_impl(ic_index *index, const float *q_dev, int64_t Q, int32_t k_
     return IC_OK;
 }
 }  // namespace
+
+// ---- cluster pruning (Sec. 4.1: K-Means clusters offline, nearest clusters first online) ------
+
+struct ic_ivf {
+    ic_index *base;      // the index being accelerated (not owned)
+    ic_index *cent;      // K centroids, same format as the store
+    ic_index *sorted;    // copy of the live rows of base, sorted by cluster
+    int32_t K, max_probe;
+    int32_t *assign;     // [base size] cluster of every row
+    int32_t *perm;       // [rows in lists] sorted position -> id in base
+    int64_t *counts, *offsets, *cursor;  // [K], [K + 1], [K]
+    float *sums;         // [K, d] K-Means update scratch
+    int64_t *tmp_ids;    // [base capacity] assignment search result
+    float *tmp_scores;
+    int64_t *probe_ids;  // [query chunk, max_probe]
+    float *probe_scores;
+    bool lists_ready;
+};
+
+namespace {
+constexpr int64_t kIvfCentQueries = 4096;  // query chunk of the centroid index (assignment passes)
+
+struct IvfLayout {
+    size_t off_cent = 0, off_sorted = 0, off_assign = 0, off_perm = 0, off_counts = 0, off_offsets = 0,
+           off_cursor = 0, off_sums = 0, off_tmp_ids = 0, off_tmp_scores = 0, off_probe_ids = 0,
+           off_probe_scores = 0, total = 0;
+    size_t cent_bytes = 0, sorted_bytes = 0;
+};
+
+bool make_ivf_layout(const ic_index *base, int32_t K, int32_t max_probe, IvfLayout &V) {
+    if (!base || K < 1 || K > (1 << 20) || max_probe < 1 || max_probe > IC_MAX_K) return false;
+    V.cent_bytes = ic_workspace_bytes(base->d, base->store, K, kIvfCentQueries, max_probe);
+    V.sorted_bytes = ic_workspace_bytes(base->d, base->store, base->capacity, base->max_q, base->max_k);
+    if (!V.cent_bytes || !V.sorted_bytes) return false;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = (size_t)round_up((int64_t)(off + bytes), kAlign);
+        return at;
+    };
+    const size_t cap = (size_t)base->L.cap_pad;
+    V.off_cent = take(V.cent_bytes);
+    V.off_sorted = take(V.sorted_bytes);
+    V.off_assign = take(cap * 4);
+    V.off_perm = take(cap * 4);
+    V.off_counts = take((size_t)K * 8);
+    V.off_offsets = take((size_t)(K + 1) * 8);
+    V.off_cursor = take((size_t)K * 8);
+    V.off_sums = take((size_t)K * (size_t)base->d * 4);
+    V.off_tmp_ids = take(cap * 8);
+    V.off_tmp_scores = take(cap * 4);
+    V.off_probe_ids = take((size_t)base->L.q_chunk * (size_t)max_probe * 8);
+    V.off_probe_scores = take((size_t)base->L.q_chunk * (size_t)max_probe * 4);
+    V.total = off;
+    return true;
+}
+
+// lists and sorted copy from ivf->assign
+ic_status ivf_build_lists(ic_ivf *v) {
+    ic_index *b = v->base, *s = v->sorted;
+    hipStream_t st = b->stream;
+    const int64_t n = b->n;
+    const unsigned gk = (unsigned)((v->K + 255) / 256), gn = (unsigned)((std::max<int64_t>(n, 1) + 255) / 256);
+    hipLaunchKernelGGL(ic::ivf_zero_i64, dim3(gk), dim3(256), 0, st, v->counts, (int64_t)v->K);
+    if (n > 0)
+        hipLaunchKernelGGL(ic::ivf_histogram, dim3(gn), dim3(256), 0, st, v->assign, b->valid, n, v->K, v->counts);
+    hipLaunchKernelGGL(ic::ivf_offsets, dim3(1), dim3(256), 0, st, v->counts, v->K, v->offsets, v->cursor);
+    if (n > 0) {
+        hipLaunchKernelGGL(ic::ivf_scatter, dim3(gn), dim3(256), 0, st, v->assign, b->valid, n, v->K, v->cursor, v->perm);
+        const int grid = std::max(8, b->compute_units) * 4;
+        hipLaunchKernelGGL(ic::ivf_gather, dim3(grid), dim3(256), 0, st, b->rows, b->util, b->scale, b->L.row_bytes,
+                           v->perm, v->offsets + v->K, s->rows, s->util, s->scale, s->valid);
+    }
+    int64_t total = 0;
+    if (hipMemcpyAsync(&total, v->offsets + v->K, sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return IC_ERR_DEVICE;
+    s->n = total;
+    s->any_invalid = false;
+    s->stream = st;
+    v->lists_ready = true;
+    return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
+}
+
+ic_status ivf_load_centroids(ic_ivf *v, const float *centroids_dev) {  // normalise, quantise, store
+    v->cent->n = 0;
+    v->cent->stream = v->base->stream;
+    return ic_index_append(v->cent, centroids_dev, nullptr, v->K, nullptr);
+}
+}  // namespace
+
+size_t ic_ivf_workspace_bytes(const ic_index *base, int32_t K, int32_t max_probe) {
+    IvfLayout V;
+    return make_ivf_layout(base, K, max_probe, V) ? V.total : 0;
+}
+
+ic_status ic_ivf_create(ic_ivf **out, ic_index *base, int32_t K, int32_t max_probe, void *arena_dev,
+                        size_t arena_bytes) {
+    if (!out || !base || !arena_dev || ((uintptr_t)arena_dev % kAlign) != 0) return IC_ERR_INVALID_ARG;
+    IvfLayout V;
+    if (!make_ivf_layout(base, K, max_probe, V)) return IC_ERR_INVALID_ARG;
+    if (arena_bytes < V.total) return IC_ERR_CAPACITY;
+    ic_ivf *v = new (std::nothrow) ic_ivf();
+    if (!v) return IC_ERR_OOM;
+    uint8_t *p = (uint8_t *)arena_dev;
+    v->base = base;
+    v->K = K;
+    v->max_probe = max_probe;
+    v->cent = nullptr;
+    v->sorted = nullptr;
+    ic_status st = ic_index_create(&v->cent, base->d, base->store, K, kIvfCentQueries, max_probe, p + V.off_cent,
+                                   V.cent_bytes, base->stream);
+    if (st == IC_OK)
+        st = ic_index_create(&v->sorted, base->d, base->store, base->capacity, base->max_q, base->max_k,
+                             p + V.off_sorted, V.sorted_bytes, base->stream);
+    if (st != IC_OK) {
+        if (v->cent) ic_index_destroy(v->cent);
+        delete v;
+        return st;
+    }
+    v->assign = (int32_t *)(p + V.off_assign);
+    v->perm = (int32_t *)(p + V.off_perm);
+    v->counts = (int64_t *)(p + V.off_counts);
+    v->offsets = (int64_t *)(p + V.off_offsets);
+    v->cursor = (int64_t *)(p + V.off_cursor);
+    v->sums = (float *)(p + V.off_sums);
+    v->tmp_ids = (int64_t *)(p + V.off_tmp_ids);
+    v->tmp_scores = (float *)(p + V.off_tmp_scores);
+    v->probe_ids = (int64_t *)(p + V.off_probe_ids);
+    v->probe_scores = (float *)(p + V.off_probe_scores);
+    v->lists_ready = false;
+    *out = v;
+    return IC_OK;
+}
+
+ic_status ic_ivf_destroy(ic_ivf *ivf) {
+    if (!ivf) return IC_ERR_INVALID_ARG;
+    ic_index_destroy(ivf->cent);
+    ic_index_destroy(ivf->sorted);
+    delete ivf;
+    return IC_OK;
+}
+
+ic_status ic_ivf_set_centroids(ic_ivf *ivf, const float *centroids_dev) {
+    if (!ivf || !centroids_dev) return IC_ERR_INVALID_ARG;
+    ivf->lists_ready = false;
+    return ivf_load_centroids(ivf, centroids_dev);
+}
+
+ic_status ic_ivf_assign(ic_ivf *ivf) {
+    if (!ivf || ivf->cent->n != ivf->K) return IC_ERR_INVALID_ARG;
+    ic_index *b = ivf->base;
+    ivf->cent->stream = b->stream;
+    if (b->n > 0) {
+        SearchReq r;
+        r.q_rows = b->rows;
+        r.q_row_scale = b->scale;
+        ic_status st = search_impl(ivf->cent, b->n, 1, 0.0f, nullptr, ivf->tmp_scores, ivf->tmp_ids, r);
+        if (st != IC_OK) return st;
+        hipLaunchKernelGGL(ic::ivf_take_assignment, dim3((unsigned)((b->n + 255) / 256)), dim3(256), 0, b->stream,
+                           ivf->tmp_ids, b->n, ivf->assign);
+    }
+    return ivf_build_lists(ivf);
+}
+
+ic_status ic_ivf_set_assignment(ic_ivf *ivf, const int32_t *assign_dev) {
+    if (!ivf || (ivf->base->n > 0 && !assign_dev)) return IC_ERR_INVALID_ARG;
+    if (ivf->base->n > 0 &&
+        hipMemcpyAsync(ivf->assign, assign_dev, (size_t)ivf->base->n * 4, hipMemcpyDeviceToDevice,
+                       ivf->base->stream) != hipSuccess)
+        return IC_ERR_DEVICE;
+    return ivf_build_lists(ivf);
+}
+
+ic_status ic_ivf_update_centroids(ic_ivf *ivf) {
+    if (!ivf || !ivf->lists_ready || ivf->cent->n != ivf->K) return IC_ERR_INVALID_ARG;
+    ic_index *s = ivf->sorted, *c = ivf->cent;
+    hipStream_t st = ivf->base->stream;
+    if (s->store == IC_STORE_BF16)
+        hipLaunchKernelGGL((ic::ivf_cluster_sums<0>), dim3(ivf->K), dim3(256), 0, st, s->rows, s->scale, s->L.row_bytes,
+                           s->d, ivf->offsets, c->rows, c->scale, ivf->sums);
+    else
+        hipLaunchKernelGGL((ic::ivf_cluster_sums<1>), dim3(ivf->K), dim3(256), 0, st, s->rows, s->scale, s->L.row_bytes,
+                           s->d, ivf->offsets, c->rows, c->scale, ivf->sums);
+    if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
+    return ivf_load_centroids(ivf, ivf->sums);
+}
+
+ic_status ic_ivf_train(ic_ivf *ivf, int32_t iters) {
+    if (!ivf || iters < 0 || ivf->base->n < 1) return IC_ERR_INVALID_ARG;
+    ic_index *b = ivf->base;
+    if (b->store == IC_STORE_BF16)
+        hipLaunchKernelGGL((ic::ivf_rows_as_centroids<0>), dim3(ivf->K), dim3(256), 0, b->stream, b->rows, b->scale,
+                           b->L.row_bytes, b->d, b->n, ivf->K, ivf->sums);
+    else
+        hipLaunchKernelGGL((ic::ivf_rows_as_centroids<1>), dim3(ivf->K), dim3(256), 0, b->stream, b->rows, b->scale,
+                           b->L.row_bytes, b->d, b->n, ivf->K, ivf->sums);
+    ic_status st = ivf_load_centroids(ivf, ivf->sums);
+    for (int32_t it = 0; st == IC_OK && it < iters; ++it) {
+        st = ic_ivf_assign(ivf);
+        if (st == IC_OK) st = ic_ivf_update_centroids(ivf);
+    }
+    if (st == IC_OK) st = ic_ivf_assign(ivf);
+    return st;
+}
+
+ic_status ic_ivf_view(const ic_ivf *ivf, const int32_t **assign_dev, const int64_t **offsets_dev,
+                      const int32_t **perm_dev, const ic_index **centroids, const ic_index **sorted) {
+    if (!ivf) return IC_ERR_INVALID_ARG;
+    if (assign_dev) *assign_dev = ivf->assign;
+    if (offsets_dev) *offsets_dev = ivf->offsets;
+    if (perm_dev) *perm_dev = ivf->perm;
+    if (centroids) *centroids = ivf->cent;
+    if (sorted) *sorted = ivf->sorted;
+    return IC_OK;
+}
+
+ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, int32_t nprobe, float lambda,
+                        float *out_scores_dev, int64_t *out_ids_dev) {
+    if (!ivf || Q < 0 || k < 1 || nprobe < 1 || nprobe > ivf->max_probe) return IC_ERR_INVALID_ARG;
+    ic_index *s = ivf->sorted, *c = ivf->cent;
+    if (k > s->max_k || !ivf->lists_ready || c->n != ivf->K) return IC_ERR_INVALID_ARG;
+    if (Q == 0) return IC_OK;
+    if (!q_dev || !out_scores_dev || !out_ids_dev) return IC_ERR_INVALID_ARG;
+    hipStream_t st = ivf->base->stream;
+    c->stream = st;
+    s->stream = st;
+    const Layout &L = s->L;
+    const int et = (s->store == IC_STORE_BF16) ? 0 : 1;
+    const int cpw = (L.row_bytes / 64 + ic::kScanWaves - 1) / ic::kScanWaves;
+    const int cap = region_cap_for(k, 0);
+    const int64_t n = s->n;
+    if (!s->consts_ready) {
+        hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)s->consts);
+        s->consts_ready = true;
+    }
+    const bool use_bias = lambda != 0.0f && n > 0;
+    if (use_bias) {
+        const int64_t n_pad = round_up(n, ic::kGemmTile);
+        hipLaunchKernelGGL(ic::make_bias, dim3((int)std::min<int64_t>((n_pad + 255) / 256, 4096)), dim3(256), 0, st,
+                           (const float *)s->util, (const uint8_t *)nullptr, (const uint8_t *)nullptr, n, n_pad, lambda,
+                           s->bias);
+    }
+    // slices per list: about 12 tiles of 16 rows each, at most 16 slices
+    const int64_t avg_tiles = std::max<int64_t>(1, n / std::max<int64_t>(1, ivf->K) / 16);
+    const int S = (int)std::min<int64_t>(16, std::max<int64_t>(1, avg_tiles / 12));
+    const int64_t qmax = std::min<int64_t>(std::min<int64_t>(L.q_chunk, ivf->base->L.q_chunk),
+                                           std::max<int64_t>(1, kRegionSlots / ((int64_t)nprobe * S)));
+    for (int64_t q0 = 0; q0 < Q; q0 += qmax) {
+        const int qc = (int)std::min<int64_t>(qmax, Q - q0);
+        // the nprobe nearest centroids of every query
+        SearchReq r;
+        r.q_dev = q_dev + q0 * (int64_t)s->d;
+        ic_status rc = search_impl(c, qc, nprobe, 0.0f, nullptr, ivf->probe_scores, ivf->probe_ids, r);
+        if (rc != IC_OK) return rc;
+        // the queries in the store's format, then one scan task per (query, list)
+        const int grid = (qc + 3) / 4;
+        if (et == 0)
+            hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
+                               s->d, L.row_bytes, s->qbuf, (float *)nullptr, (const float *)nullptr, (float *)nullptr);
+        else
+            hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
+                               s->d, L.row_bytes, s->qbuf, s->qscale, (const float *)nullptr, (float *)nullptr);
+        float *out_s = out_scores_dev + q0 * (int64_t)k;
+        int64_t *out_i = out_ids_dev + q0 * (int64_t)k;
+        const FinalOpts fo{-INFINITY, nullptr, -1};
+        ic::MergeArgs m{};
+        m.src = s->regions;
+        m.seg_stride = cap;
+        m.seg_cap = cap;
+        m.seg_counts = s->counts;
+        m.segs_per_wg = std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
+        if (n == 0) {
+            m.q_stride = 0;
+            m.nseg = 0;
+            m.segs_per_wg = 1;
+            run_merge(s, m, qc, k, out_s, out_i, nullptr, fo);
+            continue;
+        }
+        ic::ScanArgs a{};
+        a.store = s->rows;
+        a.n = n;
+        a.row_bytes = L.row_bytes;
+        a.row_scale = s->scale;
+        a.bias = use_bias ? s->bias : (const float *)s->consts;
+        a.bias_stride = use_bias ? 1 : 0;
+        a.qbuf = s->qbuf;
+        a.q_scale = s->qscale;
+        a.Q = qc;
+        a.k = k;
+        a.cap = cap;
+        a.S = S;
+        a.regions = s->regions;
+        a.counts = s->counts;
+        a.tile_mul = 1;
+        a.task_cluster = ivf->probe_ids;
+        a.task_offsets = ivf->offsets;
+        a.task_nprobe = nprobe;
+        kTaskTable[et][cpw - 1](dim3(S, qc * nprobe), st, a);
+        m.q_stride = (int64_t)nprobe * S * cap;
+        m.nseg = nprobe * S;
+        m.id_map = ivf->perm;
+        run_merge(s, m, qc, k, out_s, out_i, nullptr, fo);
+    }
+    return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
+}
 
 }  // extern "C"

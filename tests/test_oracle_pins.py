@@ -444,3 +444,74 @@ def test_self_search_hand_cases(oracle):
         Mr = M.copy(); Mr[r] = 0
         a32, ai, a64 = oracle.search(E, E[r:r + 1], 7, 0.4, U, Mr)
         assert np.array_equal(ai[0], ids[j]) and np.array_equal(a64[0], s64[j])
+
+
+# ---- cluster pruning (Sec. 4.1): each step pinned on hand-made geometry ----
+
+def _three_blobs():
+    """2-D unit rows around 0, 90 and 180 degrees (5 each), in interleaved order."""
+    deg = []
+    for j in range(5):
+        deg += [0 + 3 * j - 6, 90 + 3 * j - 6, 180 + 3 * j - 6]
+    ang = np.deg2rad(np.array(deg, dtype=np.float64))
+    return np.stack([np.cos(ang), np.sin(ang)], axis=1).astype(np.float32), np.array(deg)
+
+
+def test_ivf_assign_lists_update_hand_case(oracle):
+    E, deg = _three_blobs()
+    C = np.array([[1, 0], [0, 1], [-1, 0]], dtype=np.float32)
+    a = oracle.ivf_assign(E, C)
+    assert a.tolist() == [0, 1, 2] * 5
+    off, lists = oracle.ivf_lists(a, 3)
+    assert off.tolist() == [0, 5, 10, 15] and lists[1].tolist() == [1, 4, 7, 10, 13]
+    valid = np.ones(15, np.uint8); valid[[4, 5]] = 0
+    off, lists = oracle.ivf_lists(a, 3, valid)
+    assert off.tolist() == [0, 5, 9, 13] and lists[1].tolist() == [1, 7, 10, 13] and lists[2].tolist() == [2, 8, 11, 14]
+    # the mean direction of angles -6..6 around each axis is the axis itself (symmetric)
+    U = oracle.ivf_update(E, a, 3, C)
+    assert np.allclose(U, C, atol=1e-7)
+    # asymmetric list: rows at 0 and 90 degrees -> 45 degrees; an empty cluster keeps its centroid
+    E2 = np.array([[1, 0], [0, 1]], dtype=np.float32)
+    U2 = oracle.ivf_update(E2, [0, 0], 2, np.array([[3, 0], [0, -2]], dtype=np.float32))
+    assert np.allclose(U2[0], [2 ** -0.5, 2 ** -0.5]) and np.allclose(U2[1], [0, -1])
+    # a tie between two centroids goes to the lower id
+    assert oracle.ivf_assign(np.array([[1, 1]], np.float32), np.array([[0, 1], [1, 0]], np.float32)).tolist() == [0]
+
+
+def test_ivf_search_hand_case(oracle):
+    E, deg = _three_blobs()
+    C = np.array([[1, 0], [0, 1], [-1, 0]], dtype=np.float32)
+    a = oracle.ivf_assign(E, C)
+    q = np.array([[np.cos(np.deg2rad(80.0)), np.sin(np.deg2rad(80.0))]], dtype=np.float32)
+    s32, ids, s64, probes = oracle.ivf_search(E, C, a, q, 7, 1)
+    assert probes.tolist() == [[1]]
+    # only the 5 rows of the cluster around 90 degrees can come back, nearest angle first
+    want = sorted([i for i in range(15) if a[i] == 1], key=lambda i: abs(deg[i] - 80))
+    assert ids[0, :5].tolist() == want and ids[0, 5:].tolist() == [-1, -1]
+    assert np.allclose(s64[0, :5], np.cos(np.deg2rad(np.abs(deg[want] - 80.0))), atol=1e-7)
+    # probing every cluster is the exact search
+    full = oracle.search(E, q, 7)
+    s32b, idsb, s64b, _ = oracle.ivf_search(E, C, a, q, 7, 3)
+    assert np.array_equal(idsb, full[1]) and np.array_equal(s64b, full[2])
+    # two probes: the second nearest centroid is the one at 0 degrees
+    assert oracle.ivf_search(E, C, a, q, 7, 2)[3].tolist() == [[1, 0]]
+
+
+def test_ivf_kmeans_recovers_separated_blobs(oracle):
+    rng = np.random.default_rng(7)
+    centres = np.eye(6, dtype=np.float64)[:4]
+    lab = rng.integers(0, 4, 600)
+    E = (centres[lab] + 0.05 * rng.standard_normal((600, 6))).astype(np.float32)
+    E[[0, 150, 300, 450]] = centres.astype(np.float32)      # the start rows cover all four blobs
+    lab[[0, 150, 300, 450]] = [0, 1, 2, 3]
+    C, a = oracle.ivf_kmeans(E, 4, 5)
+    # clusters = blobs (up to naming), centroids = blob directions
+    assert all(len(set(a[lab == b].tolist())) == 1 for b in range(4)) and len(set(a.tolist())) == 4
+    for b in range(4):
+        assert abs(float(C[a[lab == b][0]] @ centres[b]) - 1.0) < 1e-3
+    # the mean cosine to the assigned centroid never decreases from one iteration to the next
+    objs = []
+    for it in range(4):
+        Ci, ai = oracle.ivf_kmeans(E, 4, it)
+        objs.append(float((oracle._unit(E) * Ci[ai]).sum(axis=1).mean()))
+    assert all(b >= a_ - 1e-12 for a_, b in zip(objs, objs[1:]))
