@@ -15,7 +15,8 @@ configuration with utility and mask (``large_batch``, ``roofline_mfma``); and th
 (N = 20,000,000, d = 1024, k = 100, built by appends of 100,000 rows) at Q = 1, 64 and 4096
 (``fp8_store``).  ``maintenance`` times the eviction of the masked rows of the d = 1024
 configuration and the compaction that squeezes them out; ``census`` runs a self-search of every
-row of a 1,000,000-row store against all the others.
+row of a 1,000,000-row store against all the others; ``cluster_pruning`` trains K = sqrt(N)
+clusters on the headline store and times the pruned search, with its recall against the exact one.
 
 Prints one JSON line.  ``roofline`` refers to the scan kernel, timed with HIP
 events on the library's stream inside the timed steps; ``cpu_baseline`` is the
@@ -163,6 +164,38 @@ def main() -> int:
             "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall, "step_ms": spread,
         }
         del qd, out_s, out_i
+    # ---- cluster pruning on the same store: K = sqrt(N) clusters, two K-Means iterations
+    ivf_leg = None
+    if not args.no_large_batch:
+        Q = 64
+        qd = wl.queries(Q, batch=Q)
+        exact_s, exact_i = ix.search(qd, cfg.k, cfg.lam)
+        K = max(1, int(round(cfg.N ** 0.5)))
+        ivf = pkg.Ivf(ix, K, 32)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ivf.train(2)
+        torch.cuda.synchronize()
+        train_s = time.perf_counter() - t0
+        ivf_leg = {"K": K, "kmeans_iterations": 2, "train_s": train_s, "Q": Q, "k": cfg.k, "per_nprobe": {}}
+        for nprobe in (1, 8, 32):
+            for _ in range(3):
+                ivf.search(qd, cfg.k, nprobe, cfg.lam)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                s_, i_ = ivf.search(qd, cfg.k, nprobe, cfg.lam)
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1) / 20
+            a, b = i_.cpu().numpy(), exact_i.cpu().numpy()
+            rec = float(np.mean([len(set(a[q].tolist()) & set(b[q].tolist())) / cfg.k for q in range(Q)]))
+            ivf_leg["per_nprobe"][str(nprobe)] = {"ms_per_step": ms, "queries_per_s": Q / (ms * 1e-3),
+                                                   f"recall_at_{cfg.k}_vs_exact": rec}
+        ivf.close()
+        ivf.arena = None
+        del ivf, qd
     ix.close()
     ix.arena = None
     del ix
@@ -353,6 +386,7 @@ def main() -> int:
         "fp8_store": fp8,
         "maintenance": maintenance,
         "census": census,
+        "cluster_pruning": ivf_leg,
     }
     print(json.dumps(line))
     return 0
