@@ -113,6 +113,30 @@ ic_status ic_search(const ic_index *index, const float *q_dev, int64_t Q, int32_
                     int64_t *out_ids_dev);
 
 /*
+ * Sharing domains (Sec. 4.3, "How Does IC-Cache Respect Privacy?": cached examples may be shared
+ * only within designated user domains).  Every stored row carries a 32-bit domain; 0, the value
+ * rows are appended with, means shared with every domain.
+ *   ids_dev      [n] int64 row ids (device); ids outside [0, size) are skipped; of duplicate ids
+ *                any one wins
+ *   domains_dev  [n] int32 (device), read during the call
+ * ic_index_compact moves the domains with their rows.  n == 0 is a no-op.
+ * Errors: INVALID_ARG, DEVICE.
+ */
+ic_status ic_index_set_domains(ic_index *index, const int64_t *ids_dev, const int32_t *domains_dev,
+                               int64_t n);
+
+/*
+ * Top-k selection under access control (same passage).  As ic_search, except that query j only
+ * sees the rows whose domain is 0 or query_domain_dev[j]; each query's result is the top k of the
+ * rows it may see (mask_dev still applies to all queries).
+ *   query_domain_dev  [Q] int32 (device).  A query of domain 0 sees only the rows of domain 0.
+ * ic_search and the other searches ignore the rows' domains.  Errors: as ic_search.
+ */
+ic_status ic_search_domains(const ic_index *index, const float *q_dev, int64_t Q, int32_t k,
+                            float lambda, const uint8_t *mask_dev, const int32_t *query_domain_dev,
+                            float *out_scores_dev, int64_t *out_ids_dev);
+
+/*
  * Top-k selection with a score threshold (Sec. 4.1, "Selecting Example Combinations": the
  * selector drops examples whose estimated helpfulness falls below a dynamic threshold, so the
  * number of examples varies per query).  Same as ic_search, except that an entry is kept only if

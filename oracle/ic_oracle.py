@@ -312,6 +312,29 @@ def search_threshold(E, queries, k: int, min_score: float, lam: float = 0.0, U=N
 
 
 # --------------------------------------------------------------------------
+# Sharing domains (Sec. 4.3, "How Does IC-Cache Respect Privacy?": cached data is shared only
+# within designated user domains).  A row of domain 0 is shared with everyone; any other row is
+# seen only by queries of its own domain.
+# --------------------------------------------------------------------------
+
+def search_domains(E, queries, k: int, row_domain, query_domain, lam: float = 0.0, U=None, mask=None,
+                   normalize: bool = True, row_scale=None, q_scale=None):
+    """One query at a time: search() with the rows the query may not see masked out."""
+    E = np.asarray(E)
+    queries = np.asarray(queries)
+    row_domain = np.asarray(row_domain, dtype=np.int64)
+    query_domain = np.asarray(query_domain, dtype=np.int64)
+    n = E.shape[0]
+    base = np.ones(n, dtype=bool) if mask is None else (np.asarray(mask) != 0)
+    out = []
+    for j in range(queries.shape[0]):
+        visible = base & ((row_domain == 0) | (row_domain == query_domain[j]))
+        qs = None if q_scale is None else np.asarray(q_scale)[j:j + 1]
+        out.append(search(E, queries[j:j + 1], k, lam, U, visible.astype(np.uint8), normalize, row_scale, qs))
+    return tuple(np.concatenate([o[t] for o in out], axis=0) for t in range(3))
+
+
+# --------------------------------------------------------------------------
 # Self-search (Sec. 2.3, "Voluminous requests lead to pervasive similarity": the top-1 similarity of
 # every request to the others): the queries are rows of the cache itself, each left out of its
 # own result.

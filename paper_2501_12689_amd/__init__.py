@@ -18,8 +18,10 @@ from .binding import (  # noqa: F401
     ic_index_destroy,
     ic_index_invalidate,
     ic_index_scale_utility,
+    ic_index_set_domains,
     ic_index_set_utility,
     ic_search,
+    ic_search_domains,
     ic_search_threshold,
     ic_self_search,
     ic_workspace_bytes,

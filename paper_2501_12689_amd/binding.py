@@ -25,7 +25,7 @@ EXPORTS = (
     "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing",
     "ic_index_scan_time_ms", "ic_status_string",
     "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
-    "ic_search_threshold", "ic_self_search",
+    "ic_search_threshold", "ic_self_search", "ic_index_set_domains", "ic_search_domains",
     "ic_ivf_workspace_bytes", "ic_ivf_create", "ic_ivf_destroy", "ic_ivf_set_centroids", "ic_ivf_assign",
     "ic_ivf_set_assignment", "ic_ivf_update_centroids", "ic_ivf_train", "ic_ivf_search", "ic_ivf_view",
 )
@@ -81,6 +81,10 @@ def load_library() -> ctypes.CDLL:
     L.ic_index_set_timing.argtypes = [vp, ctypes.c_int]
     L.ic_index_scan_time_ms.restype = ctypes.c_int
     L.ic_index_scan_time_ms.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(i64)]
+    L.ic_index_set_domains.restype = ctypes.c_int
+    L.ic_index_set_domains.argtypes = [vp, vp, vp, i64]
+    L.ic_search_domains.restype = ctypes.c_int
+    L.ic_search_domains.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp, vp]
     L.ic_index_set_utility.restype = ctypes.c_int
     L.ic_index_set_utility.argtypes = [vp, vp, vp, i64]
     L.ic_index_scale_utility.restype = ctypes.c_int
@@ -182,6 +186,23 @@ def ic_search_threshold(handle: int, queries: torch.Tensor, k: int, min_score: f
     return out_scores, out_ids, counts
 
 
+def ic_search_domains(handle: int, queries: torch.Tensor, k: int, query_domain: torch.Tensor, lam: float = 0.0,
+                      mask: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """ic_search in which query j sees only the rows of domain 0 or ``query_domain[j]`` (int32 [Q])."""
+    L = load_library()
+    Q = queries.shape[0]
+    if query_domain.numel() != Q:
+        raise ValueError("ic_search_domains: one domain per query expected")
+    out_scores = torch.empty((Q, k), dtype=torch.float32, device=queries.device)
+    out_ids = torch.empty((Q, k), dtype=torch.int64, device=queries.device)
+    _check(L.ic_search_domains(handle, _dev_ptr(queries, torch.float32, "queries"), Q, k, float(lam),
+                               _dev_ptr(mask, torch.uint8, "mask"),
+                               _dev_ptr(query_domain, torch.int32, "query_domain"),
+                               _dev_ptr(out_scores, torch.float32, "out_scores"),
+                               _dev_ptr(out_ids, torch.int64, "out_ids")), "ic_search_domains")
+    return out_scores, out_ids
+
+
 def ic_self_search(handle: int, first_row: int, count: int, k: int, lam: float, mask: Optional[torch.Tensor],
                    device) -> Tuple[torch.Tensor, torch.Tensor]:
     """Top-k of the stored rows [first_row, first_row + count) among all other rows."""
@@ -203,6 +224,15 @@ def ic_index_set_utility(handle: int, ids: torch.Tensor, util: torch.Tensor) -> 
     _check(load_library().ic_index_set_utility(handle, _dev_ptr(ids, torch.int64, "ids"),
                                                _dev_ptr(util, torch.float32, "util"), ids.numel()),
            "ic_index_set_utility")
+
+
+def ic_index_set_domains(handle: int, ids: torch.Tensor, domains: torch.Tensor) -> None:
+    """domain[ids[j]] = domains[j] (ids int64 [n], domains int32 [n], both on the GPU)."""
+    if ids.numel() != domains.numel():
+        raise ValueError("ic_index_set_domains: one domain per id expected")
+    _check(load_library().ic_index_set_domains(handle, _dev_ptr(ids, torch.int64, "ids"),
+                                               _dev_ptr(domains, torch.int32, "domains"), ids.numel()),
+           "ic_index_set_domains")
 
 
 def ic_index_scale_utility(handle: int, factor: float) -> None:
@@ -281,6 +311,13 @@ class Index:
     def self_search(self, first_row: int, count: int, k: int, lam: float = 0.0,
                     mask: Optional[torch.Tensor] = None):
         return ic_self_search(self.handle, first_row, count, k, lam, mask, self.device)
+
+    def search_domains(self, queries: torch.Tensor, k: int, query_domain: torch.Tensor, lam: float = 0.0,
+                       mask: Optional[torch.Tensor] = None):
+        return ic_search_domains(self.handle, queries, k, query_domain, lam, mask)
+
+    def set_domains(self, ids: torch.Tensor, domains: torch.Tensor) -> None:
+        ic_index_set_domains(self.handle, ids, domains)
 
     def set_utility(self, ids: torch.Tensor, util: torch.Tensor) -> None:
         ic_index_set_utility(self.handle, ids, util)

@@ -18,6 +18,15 @@ __global__ void set_utility(const int64_t *__restrict__ ids, const float *__rest
     if (id >= 0 && id < size) util[id] = u[j];
 }
 
+// domain[ids[j]] = dom[j]; ids outside [0, size) are skipped; of duplicate ids any one wins
+__global__ void set_domains(const int64_t *__restrict__ ids, const int32_t *__restrict__ dom, int64_t n,
+                            int32_t *__restrict__ domain, int64_t size) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    const int64_t id = ids[j];
+    if (id >= 0 && id < size) domain[id] = dom[j];
+}
+
 // util[i] *= factor (one fp32 multiplication per row)
 __global__ void scale_utility(float *__restrict__ util, int64_t size, float factor) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -73,6 +73,8 @@ struct GemmArgs {
     uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over a sampled tile, id = tile)
     int pilot_stride;
     int64_t tile_stride;     // the t-th row tile of the walk is tile t * tile_stride of the store (1: every tile)
+    const int32_t *row_dom;  // DOM: sharing domain of every row (0 = public), [round_up(n,256)]
+    const int32_t *q_dom;    // DOM: domain of every query, [Q]; row i is visible to q if row_dom[i] is 0 or q_dom[q]
     int64_t self_first;      // self-search: query q is stored row self_first + q and must not select
                              // itself (a tile on the diagonal would otherwise list 256 hits); -1: off
     int gq;                  // XCD mapping: query-block groups (1, 2, 4 or 8); 8/gq row classes
@@ -90,10 +92,10 @@ struct HitEntry {   // 16 scores of one lane's block that reached its query's th
 
 constexpr size_t gemm_lds_bytes() {
     return (size_t)kGemmSlots * 2 * kGemmTile * kGemmHalfBytes + 2 * kGemmTile * 4 + (size_t)kGemmPark * 12 + 16 +
-           (size_t)kGemmHits * sizeof(HitEntry);
+           (size_t)kGemmHits * sizeof(HitEntry) + kGemmTile * 4;
 }
 
-template <int ET, bool PILOT>
+template <int ET, bool PILOT, bool DOM = false>
 __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
@@ -105,6 +107,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     uint32_t *park_n = park_q + kGemmPark;   // [0] parked candidates, [1] listed blocks
     uint32_t *hit_n = park_n + 1;
     HitEntry *hits = reinterpret_cast<HitEntry *>(park_n + 4);  // [kGemmHits]
+    int32_t *dom_t = reinterpret_cast<int32_t *>(hits + kGemmHits);  // [kGemmTile] sharing domains of the tile's rows (DOM)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -276,6 +279,8 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         uint64_t thr_raw[4];
         float qs[4];
         f32x4 bias_r = {0.f, 0.f, 0.f, 0.f}, scale_r = {1.f, 1.f, 1.f, 1.f};
+        i32x4 dom_r = {0, 0, 0, 0};   // DOM: the tile's row domains and this lane's query domains
+        int qd[4] = {0, 0, 0, 0};
 
         i32x4 fa[2][2], fb[2][4];
         auto read_frags = [&](int slot, int p, i32x4 *xa, i32x4 *xb) {
@@ -339,10 +344,12 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                     if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
                     thr_raw[j] = PILOT ? 0ull : a.thr_init[q];
                     qs[j] = (ET == 1) ? a.q_scale[q] : 1.0f;
+                    if (DOM) qd[j] = a.q_dom[q];
                 }
                 if (tid < 64) {
                     bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
                     if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
+                    if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
                 }
                 if (!PILOT) {
                     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
@@ -420,10 +427,12 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                     if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
                     thr_raw[j] = PILOT ? 0ull : a.thr_init[q];
                     qs[j] = a.q_scale[q];
+                    if (DOM) qd[j] = a.q_dom[q];
                 }
                 if (tid < 64) {
                     bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
                     scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
+                    if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
                 }
                 if (!PILOT) {
                     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
@@ -471,6 +480,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             if (tid < 64) {
                 *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
                 if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
+                if (DOM) *reinterpret_cast<i32x4 *>(dom_t + tid * 4) = dom_r;
             }
             if (tid < kGemmTile) pmax[tid] = 0u;
             lds_barrier();
@@ -478,18 +488,21 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 f32x4 bs[4], rs[4];
+                i32x4 ds[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int rr = wm * 64 + i * 32 + 8 * u + 4 * h;
                     bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
                     if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
+                    if (DOM) ds[u] = *reinterpret_cast<const i32x4 *>(dom_t + rr);
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
-                                                  : acc[i][j][v] + bs[v >> 2][v & 3];
+                        float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
+                                            : acc[i][j][v] + bs[v >> 2][v & 3];
+                        if (DOM && ds[v >> 2][v & 3] != 0 && ds[v >> 2][v & 3] != qd[j]) x = -INFINITY;
                         best[j] = fmaxf(best[j], x);
                     }
             }
@@ -509,6 +522,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         if (tid < 64) {  // every wavefront is past the previous tile's epilogue (it has met this tile's barriers)
             *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
             if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
+            if (DOM) *reinterpret_cast<i32x4 *>(dom_t + tid * 4) = dom_r;
         }
         lds_barrier();   // the parked entries have been read by their flushers
         if (tid == 0) {
@@ -539,6 +553,22 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
                         if (d0 + i * 32 + 8 * (v >> 2) + (v & 3) - j * 32 == 0) acc[i][j][v] = -INFINITY;
+        }
+        // sharing domains: the dot product of a query with a row it may not see becomes -inf, so that
+        // such rows neither count against the threshold nor fill the lists
+        if (DOM) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                i32x4 ds[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    ds[u] = *reinterpret_cast<const i32x4 *>(dom_t + wm * 64 + i * 32 + 8 * u + 4 * h);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (ds[v >> 2][v & 3] != 0 && ds[v >> 2][v & 3] != qd[j]) acc[i][j][v] = -INFINITY;
+            }
         }
         // pass 1: 8 blocks of 16 scores per lane.  A lane whose block reaches the query's
         // threshold (about 17 lanes per tile) copies the block's scores to a small LDS list.
@@ -588,7 +618,8 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 const float x = he.sc[v >> 2][v & 3];
                 const uint64_t t0 = he.thr;
                 const uint64_t thr_k = t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
-                const uint64_t key = make_key(x, he.row + 8 * (v >> 2) + (v & 3));
+                const uint32_t row = he.row + 8 * (v >> 2) + (v & 3);
+                const uint64_t key = make_key(x, row);
                 if (key > thr_k && x > -INFINITY) {
                     const uint32_t slot = atomicAdd(park_n, 1u);
                     if (slot < (uint32_t)kGemmPark) {

@@ -74,6 +74,10 @@ struct ScanArgs {
     const int64_t *task_cluster;
     const int64_t *task_offsets;
     int task_nprobe;
+    // Sharing domains (DOM = true): row i is visible to query q if row_dom[i] == 0 (public) or
+    // row_dom[i] == q_dom[q].  row_dom is [round_up(n,16)] int32, q_dom [Q] int32.
+    const int32_t *row_dom;
+    const int32_t *q_dom;
 };
 
 constexpr int kScanWaves = 4;
@@ -140,7 +144,7 @@ __device__ __forceinline__ void compact_region(uint64_t *reg, int c, int k, uint
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int ET, int QG, int CPW, bool PILOT, bool TASK = false>
+template <int ET, int QG, int CPW, bool PILOT, bool TASK = false, bool DOM = false>
 __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     static_assert(!TASK || (QG == 1 && !PILOT), "task launches use one query group and no pilot");
     constexpr int QB = QG * 16;
@@ -218,6 +222,8 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     const bool q_live = (w < QG) && (jq < a.Q) && (!TASK || r16 == 0);
     float q_scale = 1.0f;
     if (ET == 1 && q_live) q_scale = a.q_scale[jq];
+    int q_dom = 0;
+    if (DOM && q_live) q_dom = a.q_dom[jq];
     uint64_t *region = regs + jl * a.cap;
     uint64_t thr_k = (q_live && !TASK) ? start_threshold(jq) : kKeyFloor;
     float thr_s = thr_k > kKeyFloor ? key_score(thr_k + 1ull) : -INFINITY;
@@ -240,6 +246,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     struct Stage {
         i32x4 rows[CPW];
         f32x4 bias;
+        i32x4 dom;   // DOM only
         f32x4 rsc;
     };
     Stage st[kStages];
@@ -252,6 +259,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
         for (int c = 0; c < CPW; ++c) x.rows[c] = *reinterpret_cast<const i32x4 *>(p + coff[c]);
         const int64_t i0 = tt * 16 + c4 * 4;
         x.bias = *reinterpret_cast<const f32x4 *>(a.bias + i0 * a.bias_stride);
+        if (DOM) x.dom = *reinterpret_cast<const i32x4 *>(a.row_dom + i0);
         if (ET == 1) x.rsc = *reinterpret_cast<const f32x4 *>(a.row_scale + i0);
     };
 
@@ -311,6 +319,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                         float sc = (ET == 1) ? sum[v] * (cur.rsc[v] * q_scale) + cur.bias[v]
                                              : sum[v] + cur.bias[v];
                         if (i0 + v > last_row) sc = -INFINITY;
+                        if (DOM && cur.dom[v] != 0 && cur.dom[v] != q_dom) sc = -INFINITY;  // another domain's row
                         if (TASK && i0 + v < row_lo) sc = -INFINITY;  // the first tile may start in the previous list
                         if (PILOT) {
                             best = fmaxf(best, sc);

@@ -61,7 +61,7 @@ struct Layout {
     int64_t cap_pad = 0;
     size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
            off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, off_pilot = 0, off_thr = 0, off_glist = 0, off_gcount = 0,
-           off_redo = 0, off_valid = 0, off_blocks = 0, total = 0;
+           off_redo = 0, off_valid = 0, off_blocks = 0, off_domain = 0, total = 0;
     int64_t list_slots = 0;
     int q_rows = 0;  // rows of the prepared query block
 };
@@ -103,6 +103,7 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_redo = take(gemm ? (size_t)(L.q_chunk / 64 + 1) * 4 : 0);
     L.off_valid = take((size_t)L.cap_pad);                                          // persistent validity, 1 B/row
     L.off_blocks = take((size_t)(L.cap_pad / ic::kScanBlock + 2) * 8);              // compaction: block offsets
+    L.off_domain = take((size_t)L.cap_pad * 4);                                      // sharing domain, 4 B/row
     L.total = off;
     return true;
 }
@@ -114,14 +115,14 @@ __global__ void init_consts(uint32_t *c) {
 
 using ScanFn = void (*)(dim3, hipStream_t, const ic::ScanArgs &);
 
-template <int ET, int QG, int CPW, bool PILOT>
+template <int ET, int QG, int CPW, bool PILOT, bool DOM = false>
 void launch_scan(dim3 grid, hipStream_t st, const ic::ScanArgs &a) {
     // more than 64 KB of dynamic LDS has to be allowed once per kernel
     static const hipError_t allowed = hipFuncSetAttribute(
-        reinterpret_cast<const void *>(&ic::scan_stream<ET, QG, CPW, PILOT>),
+        reinterpret_cast<const void *>(&ic::scan_stream<ET, QG, CPW, PILOT, false, DOM>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::scan_lds_bytes(QG, ic::kMaxCap));
     (void)allowed;
-    hipLaunchKernelGGL((ic::scan_stream<ET, QG, CPW, PILOT>), grid, dim3(256),
+    hipLaunchKernelGGL((ic::scan_stream<ET, QG, CPW, PILOT, false, DOM>), grid, dim3(256),
                        ic::scan_lds_bytes(QG, PILOT ? 0 : a.cap), st, a);
 }
 
@@ -133,6 +134,20 @@ void launch_scan(dim3 grid, hipStream_t st, const ic::ScanArgs &a) {
     }
 // [pilot][element type][query groups: 1, 2, 4][chunks per wavefront - 1]
 const ScanFn kScanTable[2][2][3][8] = {
+    {{IC_SCAN_ROW(0, 1, false), IC_SCAN_ROW(0, 2, false), IC_SCAN_ROW(0, 4, false)},
+     {IC_SCAN_ROW(1, 1, false), IC_SCAN_ROW(1, 2, false), IC_SCAN_ROW(1, 4, false)}},
+    {{IC_SCAN_ROW(0, 1, true), IC_SCAN_ROW(0, 2, true), IC_SCAN_ROW(0, 4, true)},
+     {IC_SCAN_ROW(1, 1, true), IC_SCAN_ROW(1, 2, true), IC_SCAN_ROW(1, 4, true)}},
+};
+#undef IC_SCAN_ROW
+#define IC_SCAN_ROW(ET, QG, P)                                                                              \
+    {                                                                                                       \
+        launch_scan<ET, QG, 1, P, true>, launch_scan<ET, QG, 2, P, true>, launch_scan<ET, QG, 3, P, true>,   \
+            launch_scan<ET, QG, 4, P, true>, launch_scan<ET, QG, 5, P, true>, launch_scan<ET, QG, 6, P, true>, \
+            launch_scan<ET, QG, 7, P, true>, launch_scan<ET, QG, 8, P, true>                                 \
+    }
+// the same kernels with the per-query sharing-domain test compiled in
+const ScanFn kScanTableDom[2][2][3][8] = {
     {{IC_SCAN_ROW(0, 1, false), IC_SCAN_ROW(0, 2, false), IC_SCAN_ROW(0, 4, false)},
      {IC_SCAN_ROW(1, 1, false), IC_SCAN_ROW(1, 2, false), IC_SCAN_ROW(1, 4, false)}},
     {{IC_SCAN_ROW(0, 1, true), IC_SCAN_ROW(0, 2, true), IC_SCAN_ROW(0, 4, true)},
@@ -156,13 +171,18 @@ const ScanFn kTaskTable[2][8] = {
      launch_scan_task<1, 5>, launch_scan_task<1, 6>, launch_scan_task<1, 7>, launch_scan_task<1, 8>},
 };
 
-template <int ET, bool PILOT>
-void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
+template <int ET, bool PILOT, bool DOM>
+void launch_gemm_one(int grid, hipStream_t st, const ic::GemmArgs &a) {
     static const hipError_t allowed =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET, PILOT>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET, PILOT, DOM>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::gemm_lds_bytes());
     (void)allowed;
-    hipLaunchKernelGGL((ic::scan_gemm<ET, PILOT>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(), st, a);
+    hipLaunchKernelGGL((ic::scan_gemm<ET, PILOT, DOM>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(), st, a);
+}
+template <int ET, bool PILOT>
+void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
+    if (a.q_dom) launch_gemm_one<ET, PILOT, true>(grid, st, a);
+    else launch_gemm_one<ET, PILOT, false>(grid, st, a);
 }
 
 }  // namespace
@@ -184,6 +204,7 @@ struct ic_index {
     uint8_t *valid;        // [cap_pad] 1 = row is live, 0 = invalidated (evicted) and waiting for compaction
     int64_t *block_offsets;  // compaction scratch
     bool any_invalid;      // some row has been invalidated since the last compaction
+    int32_t *domain;       // [cap_pad] sharing domain of every row; 0 = shared with every domain
     uint8_t *qbuf;
     float *qscale;
     uint64_t *regions;
@@ -261,6 +282,7 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->valid = base + L.off_valid;
     ix->block_offsets = (int64_t *)(base + L.off_blocks);
     ix->any_invalid = false;
+    ix->domain = (int32_t *)(base + L.off_domain);
     ix->qbuf = base + L.off_qbuf;
     ix->qscale = (float *)(base + L.off_qscale);
     ix->regions = (uint64_t *)(base + L.off_regions);
@@ -353,6 +375,8 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
     }
     hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream,
                        index->valid + at, n, (uint8_t)1);
+    hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n * 4 + 255) / 256)), dim3(256), 0, index->stream,
+                       (uint8_t *)(index->domain + at), n * 4, (uint8_t)0);  // new rows are shared with everyone
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     index->n += n;
     return IC_OK;
@@ -382,6 +406,14 @@ ic_status ic_index_invalidate(ic_index *index, const int64_t *ids_dev, int64_t n
     hipLaunchKernelGGL(ic::invalidate_rows, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream, ids_dev,
                        n, index->valid, index->n);
     index->any_invalid = true;
+    return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
+}
+
+ic_status ic_index_set_domains(ic_index *index, const int64_t *ids_dev, const int32_t *domains_dev, int64_t n) {
+    if (!index || n < 0 || (n > 0 && (!ids_dev || !domains_dev))) return IC_ERR_INVALID_ARG;
+    if (n == 0) return IC_OK;
+    hipLaunchKernelGGL(ic::set_domains, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream, ids_dev,
+                       domains_dev, n, index->domain, index->n);
     return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
 }
 
@@ -418,6 +450,9 @@ ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_si
         hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, index->scale, id_map_dev, n, index->bias);
         hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->bias, offs + nblocks, index->scale);
     }
+    // the domains are moved as 32-bit words (the copies do no arithmetic)
+    hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, (const float *)index->domain, id_map_dev, n, index->bias);
+    hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->bias, offs + nblocks, (float *)index->domain);
     hipLaunchKernelGGL(ic::fill_bytes, dim3(g1), dim3(256), 0, st, index->valid, n, (uint8_t)1);
     int64_t total = 0;
     if (hipMemcpyAsync(&total, offs + nblocks, sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
@@ -503,6 +538,7 @@ struct SearchReq {                      // where the queries come from and how t
     int64_t self_first = -1;            // q_rows are this index's own rows from here on: each is left out
     float min_score = -INFINITY;        // threshold mode
     int32_t *counts = nullptr;
+    const int32_t *q_domain = nullptr;  // [Q] sharing domain of every query: rows of other domains are not returned
 };
 ic_status search_impl(ic_index *index, int64_t Q, int32_t k, float lambda, const uint8_t *mask_dev,
                       float *out_scores_dev, int64_t *out_ids_dev, const SearchReq &req);
@@ -525,6 +561,16 @@ ic_status ic_self_search(const ic_index *cindex, int64_t first_row, int64_t coun
     r.q_row_scale = cindex->scale ? cindex->scale + first_row : nullptr;
     r.self_first = first_row;
     return search_impl(const_cast<ic_index *>(cindex), count, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
+}
+
+ic_status ic_search_domains(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
+                            const uint8_t *mask_dev, const int32_t *query_domain_dev, float *out_scores_dev,
+                            int64_t *out_ids_dev) {
+    if (Q > 0 && (!q_dev || !query_domain_dev)) return IC_ERR_INVALID_ARG;
+    SearchReq r;
+    r.q_dev = q_dev;
+    r.q_domain = query_domain_dev;
+    return search_impl(const_cast<ic_index *>(cindex), Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 ic_status ic_search_threshold(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
@@ -650,6 +696,9 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
         a.redo = nullptr;
         a.thr_slack = 0.0f;
         a.tile_mul = 1;
+        a.row_dom = index->domain;
+        a.q_dom = req.q_domain ? req.q_domain + q0 : nullptr;
+        const auto &scan_table = req.q_domain ? kScanTableDom : kScanTable;
 
         // Threshold pilot: a pass over a strided sample of the tiles that keeps the best score
         // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
@@ -669,6 +718,8 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             g.ntiles = (n + ic::kGemmTile - 1) / ic::kGemmTile;
             g.tile_stride = 1;
             g.self_first = fo.self_first;
+            g.row_dom = index->domain;
+            g.q_dom = a.q_dom;
             g.gq = 1;  // query-block groups: enough that a group's blocks stay in an XCD's L2
             while (g.gq < 8 && (size_t)((nqb_gemm + g.gq - 1) / g.gq) * ic::kGemmTile * L.row_bytes > kL2Share) g.gq *= 2;
         }
@@ -703,7 +754,7 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             ic::ScanArgs p = a;
             p.S = kPilotSlices;
             p.tile_mul = (int)std::min<int64_t>(64, ntiles / (kPilotSlices * 8));
-            kScanTable[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
+            scan_table[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
             ic::MergeArgs m{};
             m.src = index->pilot_keys;
             m.q_stride = kPilotSlices;
@@ -750,7 +801,7 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             // between two fp32 summation orders of a dot product of unit vectors)
             a.redo = index->redo;
             a.thr_slack = 1e-4f;
-            kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
+            scan_table[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
 
             ic::MergeArgs m{};
             m.src = index->glist;
@@ -763,7 +814,7 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             run_merge(index, m, qc, k, out_s, out_i, nullptr, fo);
         } else {
             if (!timer.start()) return IC_ERR_DEVICE;
-            kScanTable[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
+            scan_table[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
             timer.stop();
         }
 

@@ -95,16 +95,16 @@ def test_workspace_bytes_arithmetic():
     M = 1 << 20                       # capacities are padded to whole 256-row tiles
     base = w(768, pkg.STORE_BF16, M, 64, 64)
     more = w(768, pkg.STORE_BF16, 2 * M, 64, 64)
-    # M more rows: 1536 B row + 4 B utility + 4 B score bias + 1 B validity each, and 8 B of
+    # M more rows: 1536 B row + 4 B utility + 4 B score bias + 4 B sharing domain + 1 B validity each, and 8 B of
     # compaction scratch per 1024 rows (up to alignment)
-    assert abs((more - base) - M * (1536 + 4 + 4 + 1) - M // 1024 * 8) <= 1024
+    assert abs((more - base) - M * (1536 + 4 + 4 + 4 + 1) - M // 1024 * 8) <= 1024
     f8 = w(1024, pkg.STORE_FP8_E4M3, 2 * M, 64, 64) - w(1024, pkg.STORE_FP8_E4M3, M, 64, 64)
-    assert abs(f8 - M * (1024 + 4 + 4 + 4 + 1) - M // 1024 * 8) <= 1024      # + per-row scale
+    assert abs(f8 - M * (1024 + 4 + 4 + 4 + 4 + 1) - M // 1024 * 8) <= 1024      # + per-row scale
     # large batches add the per-query candidate lists of the tiled scan
     assert w(768, pkg.STORE_BF16, M, 4096, 16) > w(768, pkg.STORE_BF16, M, 64, 16) + 4096 * 2048 * 8
     # rows pad to 128 B: d = 100 bf16 -> 256 B
     a = w(100, pkg.STORE_BF16, 1 << 20, 64, 64) - w(100, pkg.STORE_BF16, 1 << 19, 64, 64)
-    assert abs(a - (1 << 19) * (256 + 4 + 4 + 1) - (1 << 9) * 8) <= 1024
+    assert abs(a - (1 << 19) * (256 + 4 + 4 + 4 + 1) - (1 << 9) * 8) <= 1024
     for bad in [(0, 0, 10, 1, 1), (1025, 0, 10, 1, 1), (2049, 1, 10, 1, 1), (64, 2, 10, 1, 1),
                 (64, 0, 0, 1, 1), (64, 0, 10, 0, 1), (64, 0, 10, 1, 0), (64, 0, 10, 1, 129)]:
         assert w(*bad) == 0, bad
@@ -144,6 +144,10 @@ def test_status_codes_without_a_gpu():
     assert L.ic_index_scale_utility(None, ctypes.c_float(0.9)) == 1 and L.ic_index_scale_utility(h, ctypes.c_float(0.9)) == 0
     assert L.ic_index_invalidate(None, fake, 1) == 1 and L.ic_index_invalidate(h, None, 1) == 1
     assert L.ic_index_invalidate(h, None, 0) == 0
+    assert L.ic_index_set_domains(None, fake, fake, 1) == 1 and L.ic_index_set_domains(h, fake, None, 1) == 1
+    assert L.ic_index_set_domains(h, None, None, 0) == 0
+    assert L.ic_search_domains(h, fake, 4, 4, 0.0, None, None, fake, fake) == 1   # no query domains
+    assert L.ic_search_domains(h, None, 0, 4, 0.0, None, None, None, None) == 0   # Q == 0: no-op
     left = ctypes.c_int64(-7)
     assert L.ic_index_compact(None, fake, None) == 1 and L.ic_index_compact(h, None, None) == 1
     assert L.ic_index_compact(h, fake, ctypes.byref(left)) == 0 and left.value == 0

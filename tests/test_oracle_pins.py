@@ -422,6 +422,41 @@ def test_threshold_mode_hand_case(oracle):
     assert np.array_equal(ids[0, :3], full[0, :3])
 
 
+def test_sharing_domains_hand_case_and_subset_property(oracle):
+    """2-D rows at known angles with domains: each query's list is the angle order of the rows it
+    may see; and in general the result equals a plain search over the visible rows alone."""
+    ang = np.deg2rad([0.0, 10.0, 20.0, 30.0, 40.0, 50.0])
+    E = np.stack([np.cos(ang), np.sin(ang)], axis=1).astype(np.float32)
+    dom = np.array([2, 0, 1, 2, 0, 1])
+    q = np.array([[1.0, 0.0]] * 4, dtype=np.float32)
+    s32, ids, s64 = oracle.search_domains(E, q, 4, dom, np.array([1, 2, 0, 7]))
+    assert ids[0].tolist() == [1, 2, 4, 5]            # domain 1: the shared rows and its own
+    assert ids[1].tolist() == [0, 1, 3, 4]            # domain 2 sees row 0, the exact match
+    assert ids[2].tolist() == [1, 4, -1, -1]          # domain 0: only the shared rows
+    assert ids[3].tolist() == [1, 4, -1, -1]          # a domain without rows of its own: the same
+    assert s64[1, 0] == 1.0 and np.allclose(s64[0], np.cos(ang[[1, 2, 4, 5]]), atol=1e-7)
+    # a mask removes rows for every query on top of the domains
+    m = np.array([1, 0, 1, 1, 1, 1], dtype=np.uint8)
+    assert oracle.search_domains(E, q, 4, dom, np.array([1, 2, 0, 7]), mask=m)[1][0].tolist() == [2, 4, 5, -1]
+    # with every row shared the domains change nothing
+    rng = np.random.default_rng(11)
+    E = rng.standard_normal((400, 12)).astype(np.float32)
+    U = rng.random(400).astype(np.float32)
+    Q = rng.standard_normal((9, 12)).astype(np.float32)
+    qd = rng.integers(0, 4, 9)
+    a = oracle.search_domains(E, Q, 7, np.zeros(400, int), qd, 0.3, U)
+    b = oracle.search(E, Q, 7, 0.3, U)
+    assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    # subset property: search over the visible rows only, ids mapped back
+    dom = rng.integers(0, 4, 400)
+    got = oracle.search_domains(E, Q, 7, dom, qd, 0.3, U)
+    for j in range(9):
+        vis = np.flatnonzero((dom == 0) | (dom == qd[j]))
+        s_, i_, s64_ = oracle.search(E[vis], Q[j:j + 1], 7, 0.3, U[vis])
+        assert np.array_equal(got[1][j], vis[i_[0]]) and np.array_equal(got[2][j], s64_[0])
+        assert np.all((dom[got[1][j]] == 0) | (dom[got[1][j]] == qd[j]))
+
+
 def test_self_search_hand_cases(oracle):
     """Duplicates find each other with cosine exactly 1; a row never returns itself; the result is
     the plain search with that one row masked out."""
