@@ -82,12 +82,18 @@ struct ScanArgs {
 
 constexpr int kScanWaves = 4;
 constexpr int kMaxCap = 192;
+// Line-mode loads (even CPW): a wavefront's private LDS buffer in which a pair of 64-byte chunks of
+// 16 rows is turned from the layout it was loaded in (8 rows x 128 B per instruction) into the MFMA
+// operand layout.  144 B per row: the 16 lanes that read the same column of 16 rows hit 16 different banks.
+constexpr int kTransRow = 144;
+constexpr int kTransBytes = 16 * kTransRow;
 
 // Dynamic LDS of scan_stream for a block of QG*16 queries with region capacity cap.
 __host__ __device__ constexpr size_t scan_lds_bytes(int qg, int cap) {
     return (size_t)kScanWaves * qg * 64 * 16   // partial score tiles
            + (size_t)qg * 16 * cap * 8         // candidate regions
-           + (size_t)qg * 16 * (8 + 4);        // threshold keys, region sizes
+           + (size_t)qg * 16 * (8 + 4)         // threshold keys, region sizes
+           + (qg < 4 ? (size_t)kScanWaves * kTransBytes : 0);  // transposition buffers (QG = 4: inside the partial tiles)
 }
 
 // Score bias of every row for one search: lambda * utility where the row is valid, -inf
@@ -153,12 +159,21 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     typedef f32x4 PartTile[kScanWaves][QG][64];
     PartTile &part = *reinterpret_cast<PartTile *>(lds_raw);
     uint64_t *regs = reinterpret_cast<uint64_t *>(lds_raw + sizeof(PartTile));  // [QB][cap]
-    uint64_t *thr_key = regs + QB * a.cap;                                        // [QB]
+    uint64_t *thr_key = regs + QB * (PILOT ? 0 : a.cap);                          // [QB]; a pilot has no regions
     uint32_t *cnt = reinterpret_cast<uint32_t *>(thr_key + QB);                   // [QB]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront index, kept scalar
+    // Line mode: with an even number of chunks per wavefront its share of a row is whole 128-byte
+    // lines, and a load instruction fetches one line of each of 8 rows (non-temporal) instead of
+    // half a line of each of 16; the fragments then pass through this wavefront's LDS buffer.
+    // With QG = 4 the buffer is the wavefront's own 4 KB of the partial tiles: it is used before
+    // the wavefront writes its partial sums, and nobody reads those until the barrier after.
+    constexpr bool LINES = (CPW % 2 == 0);
+    uint8_t *trans = (QG == 4) ? reinterpret_cast<uint8_t *>(&part[w][0][0])
+                               : reinterpret_cast<uint8_t *>(cnt + QB) + w * kTransBytes;
+    static_assert(QG < 4 || sizeof(f32x4) * QG * 64 >= (size_t)kTransBytes, "partial tiles hold the buffer");
     const int r16 = lane & 15;  // row within tile (A operand) / query within group (B, D)
     const int c4 = lane >> 4;   // 16-byte column within a 64-byte chunk; D rows 4*c4 .. 4*c4+3
     const int s = blockIdx.x;
@@ -202,6 +217,12 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     int coff[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; ++c) coff[c] = (chunk0 + c < nchunks ? chunk0 + c : nchunks - 1) * 64;
+    // line mode: byte offset of each line this wavefront owns (a surplus line re-reads the row's last)
+    int loff[(CPW + 1) / 2];
+#pragma unroll
+    for (int j = 0; j < (CPW + 1) / 2; ++j) loff[j] = (chunk0 + 2 * j < nchunks ? chunk0 + 2 * j : nchunks - 2) * 64;
+    const int l8 = lane >> 3;   // line mode: row within a half tile, and the lane's 16 bytes of the line
+    const int p8 = lane & 7;
 
     // query fragments owned by this wavefront, resident for the whole kernel
     i32x4 qf[QG][CPW];
@@ -252,11 +273,23 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     Stage st[kStages];
     auto load_stage = [&](int64_t t, Stage &x) {
         const int64_t tt = tile0 + (t < ntiles ? t : ntiles - 1) * tile_mul;
-        int64_t r = tt * 16 + r16;
-        if (r > last_row) r = last_row;  // ragged tail: re-read a valid row, masked out later
-        const uint8_t *p = a.store + r * (int64_t)a.row_bytes + c4 * 16;
+        if (LINES) {
+            int64_t r0 = tt * 16 + l8, r1 = r0 + 8;
+            if (r0 > last_row) r0 = last_row;  // ragged tail: re-read a valid row, masked out later
+            if (r1 > last_row) r1 = last_row;
+            const uint8_t *p0 = a.store + r0 * (int64_t)a.row_bytes + p8 * 16;
+            const uint8_t *p1 = a.store + r1 * (int64_t)a.row_bytes + p8 * 16;
 #pragma unroll
-        for (int c = 0; c < CPW; ++c) x.rows[c] = *reinterpret_cast<const i32x4 *>(p + coff[c]);
+            for (int c = 0; c < CPW; ++c)
+                x.rows[c] = __builtin_nontemporal_load(
+                    reinterpret_cast<const i32x4 *>(((c & 1) ? p1 : p0) + loff[c >> 1]));
+        } else {
+            int64_t r = tt * 16 + r16;
+            if (r > last_row) r = last_row;
+            const uint8_t *p = a.store + r * (int64_t)a.row_bytes + c4 * 16;
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) x.rows[c] = *reinterpret_cast<const i32x4 *>(p + coff[c]);
+        }
         const int64_t i0 = tt * 16 + c4 * 4;
         x.bias = *reinterpret_cast<const f32x4 *>(a.bias + i0 * a.bias_stride);
         if (DOM) x.dom = *reinterpret_cast<const i32x4 *>(a.row_dom + i0);
@@ -279,6 +312,28 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                 load_stage(t + (kStages - 1) * S, st[(b + kStages - 1) % kStages]);
                 const Stage &cur = st[b];
 
+                // operand fragments: lane (r16, c4) holds bytes [16*c4, 16*c4 + 16) of chunk c of row r16
+                i32x4 op[CPW];
+                if (LINES) {
+                    // The LDS unit executes a wavefront's instructions in order, so the reads below
+                    // see the writes above them without a wait, and the next pair's writes cannot
+                    // overtake these reads; the wave barriers only pin the compiler's order.
+#pragma unroll
+                    for (int j = 0; j < CPW / 2; ++j) {
+                        *reinterpret_cast<i32x4 *>(trans + l8 * kTransRow + p8 * 16) = cur.rows[2 * j];
+                        *reinterpret_cast<i32x4 *>(trans + (8 + l8) * kTransRow + p8 * 16) = cur.rows[2 * j + 1];
+                        asm volatile("" ::: "memory");
+                        __builtin_amdgcn_wave_barrier();
+                        op[2 * j] = *reinterpret_cast<const i32x4 *>(trans + r16 * kTransRow + c4 * 16);
+                        op[2 * j + 1] = *reinterpret_cast<const i32x4 *>(trans + r16 * kTransRow + 64 + c4 * 16);
+                        asm volatile("" ::: "memory");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                } else {
+#pragma unroll
+                    for (int c = 0; c < CPW; ++c) op[c] = cur.rows[c];
+                }
+
                 f32x4 acc[QG];
 #pragma unroll
                 for (int g = 0; g < QG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -288,10 +343,10 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                     for (int g = 0; g < QG; ++g) {
                         if (ET == 0) {
                             acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8, cur.rows[c]), __builtin_bit_cast(bf16x8, qf[g][c]),
+                                __builtin_bit_cast(bf16x8, op[c]), __builtin_bit_cast(bf16x8, qf[g][c]),
                                 acc[g], 0, 0, 0);
                         } else {
-                            const i64x2 ra = __builtin_bit_cast(i64x2, cur.rows[c]);
+                            const i64x2 ra = __builtin_bit_cast(i64x2, op[c]);
                             const i64x2 qa = __builtin_bit_cast(i64x2, qf[g][c]);
                             acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ra.x, qa.x, acc[g], 0, 0, 0);
                             acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ra.y, qa.y, acc[g], 0, 0, 0);
