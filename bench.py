@@ -35,11 +35,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_FP8_PEAK_TFLOPS = 5000.0
-# HBM bytes per Q = 64 scan launch on the N = 10M, d = 768 store, from two rocprofv3 counter runs
-# (FETCH_SIZE 7,501,007 KiB x 2.0000, WRITE_SIZE 3,726 KiB x 1.0000; the factors are what the same counters read
-# for a plain 1 GiB copy).  Valid for the scan_stream kernel as committed with profiles/scan_stream_c3_bf16.md;
-# set to None when that kernel changes until the counters are taken again.
-SCAN_TRAFFIC_BYTES_Q64 = (7_501_007 * (1_048_576 / 524_304) + 3_726) * 1024
+# HBM bytes per launch of the two dominant kernels, from two rocprofv3 counter runs of this program
+# (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a plain
+# 1 GiB copy: 1,048,576 / 524,304 and 1.0).  Valid for the kernels as committed with the rocprofv3
+# summaries of these runs; set to None when a kernel changes until its counters are taken again.
+SCAN_TRAFFIC_BYTES_Q64 = (7_502_531 * (1_048_576 / 524_304) + 3_553) * 1024      # scan_stream, N = 10M, d = 768, Q = 64
+GEMM_TRAFFIC_BYTES_C4 = (24_183_657 * (1_048_576 / 524_304) + 231_170) * 1024    # scan_gemm, N = 4M, d = 1024, Q = 4096
 LARGE_Q = 4096
 
 
@@ -70,6 +71,11 @@ def time_search(ix, torch, qd, k, lam, mask, out_s, out_i, warmup, steps):
     return ev[0].elapsed_time(ev[steps]) / steps, scan_ms / max(launches, 1), wall_ms / steps, spread
 
 
+def say(msg: str) -> None:
+    """Progress line on stderr (stdout carries only the JSON line)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +85,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large-batch", action="store_true", help="skip the Q = 4096 legs")
     ap.add_argument("--no-fp8", action="store_true", help="skip the fp8 (N = 20M) legs")
+    ap.add_argument("--no-cluster-pruning", action="store_true",
+                    help="skip the cluster-pruning leg (tens of thousands of small launches while training)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, so that a counter run over this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -128,6 +136,7 @@ def main() -> int:
     row_bytes = ix.store_view()[0].shape[1]
     store_bytes = cfg.N * row_bytes
 
+    say(f"index built: {cfg.N} rows")
     # ---- timed searches
     per_q = {}
     headline = None
@@ -147,6 +156,7 @@ def main() -> int:
         if Q == 64:
             headline = per_q[str(Q)]
 
+    say("small batches done")
     # ---- matrix-core regime: Q = 4096 on the same store, then the N = 4M, d = 1024 configuration
     large, roof_mfma, maintenance = None, None, None
     if not args.no_large_batch:
@@ -164,9 +174,10 @@ def main() -> int:
             "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall, "step_ms": spread,
         }
         del qd, out_s, out_i
+    say("Q=4096 on the headline store done")
     # ---- cluster pruning on the same store: K = sqrt(N) clusters, two K-Means iterations
     ivf_leg = None
-    if not args.no_large_batch:
+    if not args.no_large_batch and not args.no_cluster_pruning:
         Q = 64
         qd = wl.queries(Q, batch=Q)
         exact_s, exact_i = ix.search(qd, cfg.k, cfg.lam)
@@ -200,6 +211,7 @@ def main() -> int:
     ix.arena = None
     del ix
     torch.cuda.empty_cache()
+    say("cluster pruning done")
     if not args.no_large_batch:
         c4 = workloads.C4 if args.rows is None else workloads.C4.scaled(N=min(workloads.C4.N, args.rows))
         wl4 = workloads.Workload(c4, dev)
@@ -228,7 +240,7 @@ def main() -> int:
         roof_mfma = {
             "bound": "mfma", "kernel": f"scan_gemm (bf16 MFMA contraction + fused threshold selection), Q={c4.Q}",
             "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-            "traffic": None, "algorithmic_flops_per_launch": flop,
+            "traffic": GEMM_TRAFFIC_BYTES_C4 if args.rows is None else None, "algorithmic_flops_per_launch": flop,
         }
         # store maintenance on the same index: evict the masked rows for good, squeeze them out,
         # search the smaller store without a mask
@@ -257,6 +269,7 @@ def main() -> int:
         del ix4, mask4, masks, qd, out_s, out_i
         torch.cuda.empty_cache()
 
+    say("large-batch configuration and maintenance done")
     # ---- self-similarity census: every row of a 1M-row store against all the others, k = 1
     census = None
     if not args.no_large_batch:
@@ -289,6 +302,7 @@ def main() -> int:
         del ix2, top_s, top_i
         torch.cuda.empty_cache()
 
+    say("census done")
     # ---- fp8 store: N = 20M, d = 1024, k = 100 (built by appends of 100,000 rows), Q = 1, 64, 4096
     fp8 = None
     if not args.no_large_batch and not args.no_fp8:
@@ -333,6 +347,7 @@ def main() -> int:
             del qd, out_s, out_i
         ix5.close()
 
+    say("fp8 store done")
     # ---- CPU reference on a bounded sample (rank 0, N = 1 only)
     cpu = None
     if not args.no_cpu_baseline:
