@@ -110,51 +110,100 @@ __device__ __forceinline__ float stored_element(const uint8_t *row, int e) {
     return e4m3_value(row[e]);
 }
 
-// K-Means update: sums[c] = sum of the (unit) rows of cluster c, fp32 [K, d]; a cluster without
-// rows keeps its centroid (its stored row is decoded instead).  One workgroup per cluster, fp64
-// accumulators, the four wavefronts' partial sums added in a fixed order.  rows are the sorted
-// copy, so the cluster is the range [offsets[c], offsets[c + 1]).
+// element i of 16 stored bytes held in registers, as fp32 (without the fp8 row scale)
+template <int ET>
+__device__ __forceinline__ float piece_element(const i32x4 v, int i) {
+    if (ET == 0) {
+        const uint32_t word = (uint32_t)v[i >> 1];
+        return __uint_as_float((i & 1) ? (word & 0xFFFF0000u) : (word << 16));
+    }
+    return e4m3_value((uint8_t)(((uint32_t)v[i >> 2] >> (8 * (i & 3))) & 0xFFu));
+}
+
+// K-Means update, first step: acc[c][e] += sum over a share of cluster c's rows of element e, as
+// 64-bit fixed point with 30 fractional bits.  rows are the sorted copy, so the cluster is the range
+// [offsets[c], offsets[c + 1]); workgroup (c, y) takes the y-th of gridDim.y equal shares of it, adds
+// its rows in fp64 in a fixed order (lane l owns the 16-byte pieces l and l + 64 of every row, the
+// four wavefronts take rows round robin, their partial sums are added in wavefront order), rounds
+// each sum once to fixed point and adds it to acc with an integer atomic.  Integer addition is
+// associative, so the result does not depend on the order in which the workgroups finish.  Elements
+// of unit rows are at most 1 in magnitude: a share's sum stays below 2^31, its fixed-point value
+// below 2^61, and the rounding error of a cluster's sum is at most gridDim.y * 2^-31.
+constexpr double kIvfFixedOne = 1073741824.0;  // 2^30
 template <int ET>
 __global__ __launch_bounds__(256) void ivf_cluster_sums(const uint8_t *__restrict__ rows, const float *__restrict__ scale,
                                                         int row_bytes, int d, const int64_t *__restrict__ offsets,
-                                                        const uint8_t *__restrict__ cent_rows,
-                                                        const float *__restrict__ cent_scale, float *__restrict__ sums) {
-    constexpr int kMaxPerLane = 32;  // 2048 elements per row at most
+                                                        long long *__restrict__ acc) {
+    constexpr int E16 = (ET == 0) ? 8 : 16;  // elements in 16 bytes
+    constexpr int kRowsAhead = 4;            // rows a wavefront requests before it adds them
     __shared__ double part[4][64];
     const int c = blockIdx.x;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t lo = offsets[c], hi = offsets[c + 1];
-    double acc[kMaxPerLane];
+    const int64_t share = (hi - lo + gridDim.y - 1) / gridDim.y;
+    const int64_t first = lo + (int64_t)blockIdx.y * share;
+    const int64_t last = first + share < hi ? first + share : hi;
+    if (first >= last) return;  // whole workgroup: an empty cluster or an empty share
+    const int npieces = row_bytes / 16;  // at most 128
+    const bool own0 = lane < npieces, own1 = lane + 64 < npieces;
+    double sum[2][E16];
 #pragma unroll
-    for (int j = 0; j < kMaxPerLane; ++j) acc[j] = 0.0;
-    if (lo == hi) {
-        if (w == 0) {
-            const uint8_t *row = cent_rows + (int64_t)c * row_bytes;
-            const float sc = (ET == 1) ? cent_scale[c] : 1.0f;
-            for (int e = lane; e < d; e += 64) sums[(int64_t)c * d + e] = stored_element<ET>(row, e) * sc;
-        }
-        return;
-    }
-    for (int64_t r = lo + w; r < hi; r += 4) {
-        const uint8_t *row = rows + r * (int64_t)row_bytes;
-        const double sc = (ET == 1) ? (double)scale[r] : 1.0;
+    for (int p = 0; p < 2; ++p)
 #pragma unroll
-        for (int j = 0; j < kMaxPerLane; ++j) {
-            const int e = lane + 64 * j;
-            if (e < d) acc[j] += (double)stored_element<ET>(row, e) * sc;
+        for (int i = 0; i < E16; ++i) sum[p][i] = 0.0;
+    for (int64_t r0 = first + w * kRowsAhead; r0 < last; r0 += 4 * kRowsAhead) {
+        i32x4 piece[kRowsAhead][2];
+        float sc[kRowsAhead];
+#pragma unroll
+        for (int u = 0; u < kRowsAhead; ++u) {
+            const int64_t r = r0 + u < last ? r0 + u : last - 1;  // past the share: re-read, not added
+            const uint8_t *row = rows + r * (int64_t)row_bytes;
+            piece[u][0] = own0 ? *reinterpret_cast<const i32x4 *>(row + lane * 16) : i32x4{0, 0, 0, 0};
+            piece[u][1] = own1 ? *reinterpret_cast<const i32x4 *>(row + (lane + 64) * 16) : i32x4{0, 0, 0, 0};
+            sc[u] = (ET == 1) ? scale[r] : 1.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kRowsAhead; ++u) {
+            if (r0 + u >= last) break;
+            const double s64 = (double)sc[u];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int i = 0; i < E16; ++i) sum[p][i] += (double)piece_element<ET>(piece[u][p], i) * s64;
         }
     }
 #pragma unroll
-    for (int j = 0; j < kMaxPerLane; ++j) {
-        if (64 * j >= d) break;
-        part[w][lane] = acc[j];
-        __syncthreads();
-        if (w == 0) {
-            const int e = lane + 64 * j;
-            if (e < d) sums[(int64_t)c * d + e] = (float)(((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]);
+    for (int p = 0; p < 2; ++p) {
+#pragma unroll
+        for (int i = 0; i < E16; ++i) {
+            part[w][lane] = sum[p][i];
+            __syncthreads();
+            if (w == 0) {
+                const int e = (lane + 64 * p) * E16 + i;
+                if (e < d) {
+                    const double total = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+                    atomicAdd(reinterpret_cast<unsigned long long *>(acc + (int64_t)c * d + e),
+                              (unsigned long long)__double2ll_rn(total * kIvfFixedOne));
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
+}
+
+// K-Means update, second step: sums[c] = acc[c] as fp32 [K, d]; a cluster without rows keeps its
+// centroid (its stored row is decoded instead).
+template <int ET>
+__global__ void ivf_finish_sums(const long long *__restrict__ acc, const int64_t *__restrict__ offsets, int d,
+                                const uint8_t *__restrict__ cent_rows, int row_bytes,
+                                const float *__restrict__ cent_scale, float *__restrict__ sums) {
+    const int c = blockIdx.x;
+    const bool empty = offsets[c] == offsets[c + 1];
+    const uint8_t *row = cent_rows + (int64_t)c * row_bytes;
+    const float sc = (ET == 1) ? cent_scale[c] : 1.0f;
+    for (int e = threadIdx.x; e < d; e += blockDim.x)
+        sums[(int64_t)c * d + e] = empty ? stored_element<ET>(row, e) * sc
+                                         : (float)((double)acc[(int64_t)c * d + e] * (1.0 / kIvfFixedOne));
 }
 
 // K-Means start: sums[c] = the stored row at position floor(c * n / K), decoded to fp32 [K, d]

@@ -846,6 +846,7 @@ struct ic_ivf {
     int32_t *perm;       // [rows in lists] sorted position -> id in base
     int64_t *counts, *offsets, *cursor;  // [K], [K + 1], [K]
     float *sums;         // [K, d] K-Means update scratch
+    long long *acc64;    // [K, d] fixed-point sums of the update in progress
     int64_t *tmp_ids;    // [base capacity] assignment search result
     float *tmp_scores;
     int64_t *probe_ids;  // [query chunk, max_probe]
@@ -855,10 +856,11 @@ struct ic_ivf {
 
 namespace {
 constexpr int64_t kIvfCentQueries = 4096;  // query chunk of the centroid index (assignment passes)
+constexpr int kIvfShares = 16;             // workgroups that share the rows of one cluster in the K-Means update
 
 struct IvfLayout {
     size_t off_cent = 0, off_sorted = 0, off_assign = 0, off_perm = 0, off_counts = 0, off_offsets = 0,
-           off_cursor = 0, off_sums = 0, off_tmp_ids = 0, off_tmp_scores = 0, off_probe_ids = 0,
+           off_cursor = 0, off_sums = 0, off_acc64 = 0, off_tmp_ids = 0, off_tmp_scores = 0, off_probe_ids = 0,
            off_probe_scores = 0, total = 0;
     size_t cent_bytes = 0, sorted_bytes = 0;
 };
@@ -883,6 +885,7 @@ bool make_ivf_layout(const ic_index *base, int32_t K, int32_t max_probe, IvfLayo
     V.off_offsets = take((size_t)(K + 1) * 8);
     V.off_cursor = take((size_t)K * 8);
     V.off_sums = take((size_t)K * (size_t)base->d * 4);
+    V.off_acc64 = take((size_t)K * (size_t)base->d * 8);
     V.off_tmp_ids = take(cap * 8);
     V.off_tmp_scores = take(cap * 4);
     V.off_probe_ids = take((size_t)base->L.q_chunk * (size_t)max_probe * 8);
@@ -960,6 +963,7 @@ ic_status ic_ivf_create(ic_ivf **out, ic_index *base, int32_t K, int32_t max_pro
     v->offsets = (int64_t *)(p + V.off_offsets);
     v->cursor = (int64_t *)(p + V.off_cursor);
     v->sums = (float *)(p + V.off_sums);
+    v->acc64 = (long long *)(p + V.off_acc64);
     v->tmp_ids = (int64_t *)(p + V.off_tmp_ids);
     v->tmp_scores = (float *)(p + V.off_tmp_scores);
     v->probe_ids = (int64_t *)(p + V.off_probe_ids);
@@ -1012,12 +1016,22 @@ ic_status ic_ivf_update_centroids(ic_ivf *ivf) {
     if (!ivf || !ivf->lists_ready || ivf->cent->n != ivf->K) return IC_ERR_INVALID_ARG;
     ic_index *s = ivf->sorted, *c = ivf->cent;
     hipStream_t st = ivf->base->stream;
-    if (s->store == IC_STORE_BF16)
-        hipLaunchKernelGGL((ic::ivf_cluster_sums<0>), dim3(ivf->K), dim3(256), 0, st, s->rows, s->scale, s->L.row_bytes,
-                           s->d, ivf->offsets, c->rows, c->scale, ivf->sums);
-    else
-        hipLaunchKernelGGL((ic::ivf_cluster_sums<1>), dim3(ivf->K), dim3(256), 0, st, s->rows, s->scale, s->L.row_bytes,
-                           s->d, ivf->offsets, c->rows, c->scale, ivf->sums);
+    // every cluster's rows are shared out over kIvfShares workgroups (the lists are uneven: one
+    // workgroup per cluster left the chip waiting for the longest list)
+    const int64_t cells = (int64_t)ivf->K * s->d;
+    hipLaunchKernelGGL(ic::ivf_zero_i64, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, st,
+                       (int64_t *)ivf->acc64, cells);
+    if (s->store == IC_STORE_BF16) {
+        hipLaunchKernelGGL((ic::ivf_cluster_sums<0>), dim3(ivf->K, kIvfShares), dim3(256), 0, st, s->rows, s->scale,
+                           s->L.row_bytes, s->d, ivf->offsets, ivf->acc64);
+        hipLaunchKernelGGL((ic::ivf_finish_sums<0>), dim3(ivf->K), dim3(256), 0, st, ivf->acc64, ivf->offsets, s->d,
+                           c->rows, c->L.row_bytes, c->scale, ivf->sums);
+    } else {
+        hipLaunchKernelGGL((ic::ivf_cluster_sums<1>), dim3(ivf->K, kIvfShares), dim3(256), 0, st, s->rows, s->scale,
+                           s->L.row_bytes, s->d, ivf->offsets, ivf->acc64);
+        hipLaunchKernelGGL((ic::ivf_finish_sums<1>), dim3(ivf->K), dim3(256), 0, st, ivf->acc64, ivf->offsets, s->d,
+                           c->rows, c->L.row_bytes, c->scale, ivf->sums);
+    }
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     return ivf_load_centroids(ivf, ivf->sums);
 }

@@ -205,10 +205,14 @@ def test_results_do_not_depend_on_launch_shape(pkg):
         assert np.array_equal(i, outs[0][1]) and np.array_equal(s, outs[0][0])
 
 
-def test_adversarial_ascending_order(pkg, oracle):
-    """Rows sorted by ascending score: every row beats the running threshold."""
-    _say("ascending-score order")
-    cfg = workloads.C1.scaled(N=30000, d=384, clusters=8, Q=4, k=10)
+@pytest.mark.parametrize("d,Q", [(384, 4), (256, 64), (768, 40)], ids=["d384-q4", "d256-q64", "d768-q40"])
+def test_adversarial_ascending_order(pkg, oracle, d, Q):
+    """Rows sorted by ascending score: every row beats the running threshold, so the regions are
+    compacted all the time while the other wavefronts run ahead.  d=384 takes the direct operand
+    loads, d=256 and d=768 the full-line loads; with 64 queries per workgroup the transposition
+    buffers share their LDS with the partial-sum exchange."""
+    _say(f"ascending-score order d={d} Q={Q}")
+    cfg = workloads.C1.scaled(N=30000, d=d, clusters=8, Q=Q, k=10)
     E, U, M, Qm = _inputs(cfg)
     order = np.argsort(oracle.scores(E, Qm[:1])[0], kind="stable")
     E = np.ascontiguousarray(E[order])
@@ -219,7 +223,8 @@ def test_adversarial_ascending_order(pkg, oracle):
         os.environ.pop("IC_SLICE_BUDGET", None)
     for k in (1, 10, 100):
         s, i = _search(ix, Qm, k)
-        parity.check_batch("bf16", s, i, E, None, None, Qm, k, 0.0, f"ascending k={k}")
+        parity.check_batch("bf16", s, i, E, None, None, Qm, k, 0.0, f"ascending d={d} k={k}",
+                           queries=range(0, Q, max(1, Q // 8)))
     ix.close()
 
 
