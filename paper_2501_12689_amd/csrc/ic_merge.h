@@ -2,10 +2,11 @@
 // final top-k of each query (the "keep the most similar examples" step of IC-Cache stage 1,
 // Sec. 4.1).
 //
-// One workgroup takes a group of segments of one query (at most kMergeKeys keys in all), packs
-// their keys into LDS, sorts them with a bitonic network under the (score desc, id asc) key
-// order and writes the best k.  The network is sized to the keys actually present, so nearly
-// empty segments (the usual case once the scan starts from the pilot's threshold) cost little.
+// One workgroup takes a group of segments of one query, packs their keys into LDS, sorts them
+// with a bitonic network under the (score desc, id asc) key order and writes the best k.  The
+// network is sized to the keys actually present, so nearly empty segments (the usual case once
+// the scan starts from the pilot's threshold) cost little; a group that holds more than kMergeKeys
+// keys is taken in rounds that keep the best k so far.
 // The host chains launches until one group per query is left; the last launch decodes keys into
 // (fp32 score, int64 id).
 #pragma once
@@ -27,7 +28,7 @@ struct MergeArgs {
     const int32_t *seg_counts;
     const int32_t *total_counts;
     int nseg;                   // segments per query
-    int segs_per_wg;            // <= kMergeMaxSegs, segs_per_wg * seg_cap <= kMergeKeys
+    int segs_per_wg;            // <= kMergeMaxSegs
     int k;
     uint64_t *dst;              // non-final: lists [Q][gridDim.y][k]
     float *out_scores;          // final: [Q][k], or NULL
@@ -78,39 +79,67 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     }
     __syncthreads();
     const int total = seg_off[a.segs_per_wg];
-    int P = 2;
-    while (P < total || P < a.k) P <<= 1;
-
-    for (int e = total + tid; e < P; e += 256) buf[e] = 0;
     const uint64_t *src = a.src + (int64_t)q * a.q_stride;
-    for (int s = 0; s < a.segs_per_wg; ++s) {
-        const int c = seg_cnt[s];
-        const uint64_t *sp = src + (int64_t)(seg0 + s) * a.seg_stride;
-        uint64_t *dp = buf + seg_off[s];
-        for (int idx = tid; idx < c; idx += 256) {
-            uint64_t key = sp[idx];
-            if (a.id_map && key > kKeyFloor)
-                key = (key & 0xFFFFFFFF00000000ull) | (uint64_t)(0xFFFFFFFFu - (uint32_t)a.id_map[key_id(key)]);
-            dp[idx] = key;
-        }
-    }
+    auto fetch = [&](const uint64_t *sp, int idx) -> uint64_t {
+        uint64_t key = sp[idx];
+        if (a.id_map && key > kKeyFloor)
+            key = (key & 0xFFFFFFFF00000000ull) | (uint64_t)(0xFFFFFFFFu - (uint32_t)a.id_map[key_id(key)]);
+        return key;
+    };
 
-    for (int size = 2; size <= P; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int e = tid; e < (P >> 1); e += 256) {
-                const int i = 2 * e - (e & (stride - 1));
-                const int j = i + stride;
-                const bool descending = (i & size) == 0;
-                const uint64_t x = buf[i], y = buf[j];
-                if ((x < y) == descending) {
-                    buf[i] = y;
-                    buf[j] = x;
+    // The group's keys, segment after segment, form one sequence of `total` keys.  Usually it fits
+    // the buffer and is sorted in one go.  If not (full regions, many segments), it is taken in
+    // rounds: the best k so far stay at the front of the buffer, the rest of the buffer is
+    // refilled with the next keys of the sequence, and the buffer is sorted again.
+    int have = 0, consumed = 0;
+    do {
+        const int room = kMergeKeys - have;
+        const int take = total - consumed < room ? total - consumed : room;
+        if (take == total) {  // everything at once: all segments in parallel, a few threads each
+            const int tps = 256 / a.segs_per_wg;  // threads per segment (segs_per_wg <= 64)
+            const int s = tid / tps;
+            if (s < a.segs_per_wg) {
+                const int c = seg_cnt[s];
+                const uint64_t *sp = src + (int64_t)(seg0 + s) * a.seg_stride;
+                uint64_t *dp = buf + seg_off[s];
+                for (int idx = tid % tps; idx < c; idx += tps) dp[idx] = fetch(sp, idx);
+            }
+        } else {  // keys [consumed, consumed + take) of the sequence: find each key's segment
+            for (int e = tid; e < take; e += 256) {
+                const int pos = consumed + e;
+                int lo = 0, hi = a.segs_per_wg;  // seg_off[lo] <= pos < seg_off[hi]
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (seg_off[mid] <= pos) lo = mid;
+                    else hi = mid;
+                }
+                buf[have + e] = fetch(src + (int64_t)(seg0 + lo) * a.seg_stride, pos - seg_off[lo]);
+            }
+        }
+        const int n = have + take;
+        int P = 2;
+        while (P < n || P < a.k) P <<= 1;
+        for (int e = n + tid; e < P; e += 256) buf[e] = 0;
+
+        for (int size = 2; size <= P; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                __syncthreads();
+                for (int e = tid; e < (P >> 1); e += 256) {
+                    const int i = 2 * e - (e & (stride - 1));
+                    const int j = i + stride;
+                    const bool descending = (i & size) == 0;
+                    const uint64_t x = buf[i], y = buf[j];
+                    if ((x < y) == descending) {
+                        buf[i] = y;
+                        buf[j] = x;
+                    }
                 }
             }
         }
-    }
-    __syncthreads();
+        __syncthreads();
+        consumed += take;
+        have = n < a.k ? n : a.k;
+    } while (consumed < total);
 
     if (tid == 0) {
         kept = 0;

@@ -827,7 +827,10 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
         m.seg_cap = cap;
         m.seg_counts = index->counts;
         m.nseg = S;
-        m.segs_per_wg = std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
+        // after a pilot the regions hold a handful of keys each, so a workgroup takes as many as
+        // it may (fewer, smaller lists for the next level; a rare full group is merged in rounds);
+        // without one they may be full, and more workgroups with one round each are faster
+        m.segs_per_wg = a.thr_init ? ic::kMergeMaxSegs : std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
         run_merge(index, m, qc, k, out_s, out_i, gemm ? index->redo : nullptr, fo);
     }
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;

@@ -205,8 +205,9 @@ def test_results_do_not_depend_on_launch_shape(pkg):
         assert np.array_equal(i, outs[0][1]) and np.array_equal(s, outs[0][0])
 
 
-@pytest.mark.parametrize("d,Q", [(384, 4), (256, 64), (768, 40)], ids=["d384-q4", "d256-q64", "d768-q40"])
-def test_adversarial_ascending_order(pkg, oracle, d, Q):
+@pytest.mark.parametrize("d,Q,budget", [(384, 4, "3"), (256, 64, "3"), (768, 40, "3"), (128, 20, None)],
+                         ids=["d384-q4", "d256-q64", "d768-q40", "d128-q20-all-slices"])
+def test_adversarial_ascending_order(pkg, oracle, d, Q, budget):
     """Rows sorted by ascending score: every row beats the running threshold, so the regions are
     compacted all the time while the other wavefronts run ahead.  d=384 takes the direct operand
     loads, d=256 and d=768 the full-line loads; with 64 queries per workgroup the transposition
@@ -216,11 +217,14 @@ def test_adversarial_ascending_order(pkg, oracle, d, Q):
     E, U, M, Qm = _inputs(cfg)
     order = np.argsort(oracle.scores(E, Qm[:1])[0], kind="stable")
     E = np.ascontiguousarray(E[order])
-    os.environ["IC_SLICE_BUDGET"] = "3"
+    if budget:
+        os.environ["IC_SLICE_BUDGET"] = budget      # three long slices: regions overflow and are compacted
     try:
         ix = _build_index(pkg, "bf16", E, None, max_k=128)
     finally:
         os.environ.pop("IC_SLICE_BUDGET", None)
+    # without a budget: hundreds of short slices whose regions together hold more keys than one
+    # merge workgroup sorts at once (the merge then runs in rounds)
     for k in (1, 10, 100):
         s, i = _search(ix, Qm, k)
         parity.check_batch("bf16", s, i, E, None, None, Qm, k, 0.0, f"ascending d={d} k={k}",
@@ -242,6 +246,23 @@ def test_pilot_threshold_with_ties_and_sorted_rows(pkg, oracle):
         s, i = _search(ix, Qm, k)
         parity.check_batch("bf16", s, i, E, None, None, Qm, k, 0.0, f"pilot ties k={k}")
     assert list(i[3, :128]) == list(range(1000, 1128))      # equal scores: lowest ids win
+    ix.close()
+
+
+def test_many_ties_fill_every_region(pkg, oracle):
+    """52,000 copies of one row, which is also (nearly) query 0: after the pilot every slice still
+    keeps a region full of equal scores, so a merge workgroup's 64 regions hold more keys than it
+    sorts at once and the merge runs in rounds.  The result is the copies with the lowest ids."""
+    _say("ties in every region: merge in rounds")
+    cfg = workloads.C1.scaled(N=270000, d=64, clusters=8, Q=12, k=20)
+    E, U, M, Qm = _inputs(cfg)
+    E[10000::5] = E[7]
+    Qm[0] = E[7] + 0.01 * Qm[0]
+    ix = _build_index(pkg, "bf16", E, None, max_k=128)
+    for k in (20, 100):
+        s, i = _search(ix, Qm, k)
+        parity.check_batch("bf16", s, i, E, None, None, Qm, k, 0.0, f"ties everywhere k={k}")
+        assert list(i[0, :k]) == [7] + list(range(10000, 10000 + 5 * (k - 1), 5))
     ix.close()
 
 

@@ -60,7 +60,7 @@ class Config:
         return dataclasses.replace(self, **kw)
 
 
-# The five benchmark configurations (sizes as named by the benchmark baseline).
+# The five benchmark configurations.
 C1 = Config("C1", N=100_000, d=384, clusters=256, Q=64, k=10, seed=126891)
 C2 = Config("C2", N=1_000_000, d=768, clusters=1024, Q=256, k=32, lam=0.1, util="uniform",
             p_valid=0.95, seed=126892)
