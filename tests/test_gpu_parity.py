@@ -187,6 +187,43 @@ def test_parity_with_reference(pkg, oracle, case):
     ix.close()
 
 
+def _drawn_cases(count, seed):
+    """Seeded draw of shapes the fixed list above does not name: any d the store accepts (odd and
+    even numbers of 64-byte chunks per wavefront, rows with padding columns), ragged N down to a
+    single row, Q across the 16/32/64-query workgroup shapes and beyond one block, any k, with and
+    without utility and mask."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for n in range(count):
+        store = "fp8" if rng.random() < 0.35 else "bf16"
+        dmax = 2048 if store == "fp8" else 1024
+        d = int(rng.choice([rng.integers(1, 65), rng.integers(65, 400), rng.integers(400, dmax + 1)]))
+        N = int(rng.choice([rng.integers(1, 40), rng.integers(40, 3000), rng.integers(3000, 40000)]))
+        Q = int(rng.choice([1, rng.integers(2, 17), rng.integers(17, 65), rng.integers(65, 150)]))
+        k = int(rng.choice([1, rng.integers(2, 33), rng.integers(33, 129)]))
+        lam = float(rng.choice([0.0, 0.1, 0.5]))
+        util = "none" if lam == 0.0 else str(rng.choice(["uniform", "beta25"]))
+        pv = float(rng.choice([1.0, 0.9, 0.3]))
+        out.append((store, N, d, int(rng.integers(1, 20)), Q, k, lam, util, pv))
+    return out
+
+
+DRAWN = _drawn_cases(24, 20250112)
+
+
+@pytest.mark.parametrize("case", DRAWN, ids=lambda c: "-".join(str(x) for x in c))
+def test_parity_on_drawn_shapes(pkg, oracle, case):
+    store, N, d, C, Q, k, lam, util, pv = case
+    _say(f"drawn shape {case}")
+    cfg = workloads.Config("R", N=N, d=d, clusters=C, Q=Q, k=k, store=store, zipf=1.1, lam=lam,
+                           util=util, p_valid=pv, seed=8100 + DRAWN.index(case))
+    E, U, M, Qm = _inputs(cfg)
+    ix = _build_index(pkg, store, E, U, max_q=64, max_k=128)
+    s, i = _search(ix, Qm, k, lam, M)
+    parity.check_batch(store, s, i, E, U, M, Qm, k, lam, f"{case}", queries=range(0, Q, max(1, Q // 24)))
+    ix.close()
+
+
 def test_results_do_not_depend_on_launch_shape(pkg):
     _say("launch-shape independence / determinism")
     cfg = workloads.C3.scaled(N=50000, clusters=64, Q=64, k=64)
