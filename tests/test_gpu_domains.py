@@ -55,7 +55,7 @@ def _check(store, gs, gi, E, U, M, Qm, k, lam, dom, qd, where, per_domain=6):
 CASES = [
     # store, N, d, Q, max_q, k, lam, util, p_valid
     ("bf16", 40000, 96, 7, 8, 10, 0.0, "none", 1.0),            # streaming scan, no pilot
-    ("bf16", 90000, 128, 70, 70, 32, 0.3, "uniform", 0.9),      # streaming scan with the pilot
+    ("bf16", 290000, 128, 60, 64, 32, 0.3, "uniform", 0.9),     # streaming scan with the pilot
     ("fp8", 70000, 128, 150, 64, 16, 0.2, "beta25", 0.95),      # query chunks of 64: domains follow the chunk
     ("bf16", 300000, 128, 300, 300, 16, 0.2, "beta25", 0.95),   # tiled scan
     ("fp8", 280000, 256, 260, 260, 40, 0.0, "none", 1.0),       # tiled scan, fp8
