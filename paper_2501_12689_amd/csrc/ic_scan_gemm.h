@@ -112,7 +112,11 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w >> 1, wn = w & 1;  // 4 x 2 wavefronts of 64 rows x 128 queries
+    // 4 x 2 wavefronts of 64 rows x 128 queries.  A batch of one block with at most 128 real queries
+    // gives its first 128 queries to wavefronts 0-3 (one per SIMD), so that all four SIMDs work;
+    // otherwise the two wavefronts of a SIMD (w, w + 4) share their queries (measured slightly faster).
+    const bool half_block = a.nqb == 1 && a.Q <= 128;
+    const int wm = half_block ? (w & 3) : (w >> 1), wn = half_block ? (w >> 2) : (w & 1);
     const int r32 = lane & 31, h = lane >> 5;
     const int nhs = a.row_bytes / kGemmHalfBytes;  // pipeline steps per tile (even, >= 2)
 
@@ -257,8 +261,14 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     asm volatile("" ::: "memory");
 
     int hslot = 0;  // ring slot of the step being computed
-    auto run_tiles = [&](auto late_c) {
+    // kDead: the batch is a single query block with at most 128 real queries and this wavefront's
+    // 128 queries are all padding.  It keeps its part in the copies and the barriers and skips the
+    // operand reads and the MFMAs, so such a batch costs half the matrix work and the scan is bound
+    // by reading the store.  (In a batch of several blocks only the last block can have such
+    // wavefronts; they are not worth a second copy of the loop there.)
+    auto run_tiles = [&](auto late_c, auto dead_c) {
     constexpr bool kLate = decltype(late_c)::value;
+    constexpr bool kDead = decltype(dead_c)::value;
     for (; tw.job < work; walk_next(tw)) {
         Tile cur;
         locate(tw.ql, tw.rl, cur);
@@ -321,15 +331,17 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         auto half = [&](auto last_c) {
             constexpr bool kLast = decltype(last_c)::value;
             if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1));  // the slot freed by the previous barrier
-            read_frags(hslot, 1, fa[1], fb[1]);
-            mfma8(fa[0], fb[0]);
+            if (!kDead) {
+                read_frags(hslot, 1, fa[1], fb[1]);
+                mfma8(fa[0], fb[0]);
 #pragma unroll
-            for (int g = 0; g < 6; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);  // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // LDS read
-                if (kLate && g < 4) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                for (int g = 0; g < 6; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);  // MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // LDS read
+                    if (kLate && g < 4) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 2 * kPer, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, 2 * kPer, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (kLate) advance();
             asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
@@ -359,19 +371,21 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             }
             if (!kLate) issue(hslot);
             const int nslot = (hslot + 1) & (kGemmSlots - 1);
-            if (!kLast) read_frags(nslot, 0, fa[0], fb[0]);
-            mfma8(fa[1], fb[1]);
+            if (!kDead) {
+                if (!kLast) read_frags(nslot, 0, fa[0], fb[0]);
+                mfma8(fa[1], fb[1]);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
-                if (!kLate) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
-                if (!kLast) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            if (!kLast) {
-#pragma unroll
-                for (int g = 0; g < 2; ++g) {
+                for (int g = 0; g < 4; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if (!kLate) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                    if (!kLast) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                if (!kLast) {
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -401,17 +415,19 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             constexpr bool kLast = decltype(last_c)::value;
             constexpr int kPar = decltype(par_c)::value;
             if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1));  // the slot freed by the previous barrier
+            if (!kDead) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ga[kPar][i], gb[kPar][j], acc[i][j], 0, 0, 0,
-                                                                                 0, 0, 0);
-            if (kLate) {
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ga[kPar][i], gb[kPar][j], acc[i][j], 0,
+                                                                                     0, 0, 0, 0, 0);
+                if (kLate) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                    for (int g = 0; g < 4; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);  // direct load
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -442,29 +458,31 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             }
             if (!kLate) issue(hslot);
             const int nslot = (hslot + 1) & (kGemmSlots - 1);
-            if (!kLast) read_frags8(nslot, ga[kPar ^ 1], gb[kPar ^ 1]);
+            if (!kDead) {
+                if (!kLast) read_frags8(nslot, ga[kPar ^ 1], gb[kPar ^ 1]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 2; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ga[kPar][i], gb[kPar][j], acc[i][j], 0, 0, 0,
-                                                                                 0, 0, 0);
+                    for (int j = 2; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ga[kPar][i], gb[kPar][j], acc[i][j], 0,
+                                                                                     0, 0, 0, 0, 0);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (!kLast) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      // LDS reads
-                if (!kLate) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);      // direct load
+                for (int g = 0; g < 4; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (!kLast) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);      // LDS reads
+                    if (!kLate) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);      // direct load
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             if (!kLate) advance();
             hslot = nslot;
         };
         if constexpr (ET == 0) {
-            read_frags(hslot, 0, fa[0], fb[0]);  // the step landed before the barrier of the step before it
+            if (!kDead) read_frags(hslot, 0, fa[0], fb[0]);  // the step landed before the barrier of the step before it
             for (int hs = 0; hs + 1 < nhs; ++hs) half(std::false_type{});
             half(std::true_type{});
         } else {
-            read_frags8(hslot, ga[0], gb[0]);
+            if (!kDead) read_frags8(hslot, ga[0], gb[0]);
             for (int hs = 0; hs + 2 < nhs; hs += 2) {  // the number of steps is even
                 half8(std::false_type{}, std::integral_constant<int, 0>{});
                 half8(std::false_type{}, std::integral_constant<int, 1>{});
@@ -633,8 +651,10 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         }
     }
     };
-    if (late) run_tiles(std::true_type{});
-    else run_tiles(std::false_type{});
+    const bool dead = half_block && wn == 1;  // wave-uniform; these are wavefronts 4-7, the late ones
+    if (dead) run_tiles(std::true_type{}, std::true_type{});
+    else if (late) run_tiles(std::true_type{}, std::false_type{});
+    else run_tiles(std::false_type{}, std::false_type{});
 
     // the last tile's parked candidates; the direct loads of the unused extra stage must have landed
     // before the workgroup gives up its LDS
