@@ -270,6 +270,42 @@ def main() -> int:
         torch.cuda.empty_cache()
 
     say("large-batch configuration and maintenance done")
+    # ---- the two small configurations at their own shapes (report only: C1 fits the last-level
+    # cache and is bound by launches; C2 sits at the ridge between the two bounds)
+    small_cfgs = None
+    if not args.no_large_batch:
+        small_cfgs = {}
+        for name in ("C1", "C2"):
+            cs = workloads.CONFIGS[name]
+            if args.rows is not None:
+                cs = cs.scaled(N=min(cs.N, args.rows))
+            wls = workloads.Workload(cs, dev)
+            ixs = pkg.Index(cs.d, cs.N, pkg.STORE_BF16, cs.Q, cs.k, dev)
+            masks = []
+            for lo in range(0, cs.N, chunk):
+                n = min(chunk, cs.N - lo)
+                E, U, M = wls.rows(lo, n)
+                ixs.append(E, U)
+                masks.append(M)
+                del E
+            mask_s = torch.cat(masks) if masks[0] is not None else None
+            qd = wls.queries(cs.Q)
+            out_s = torch.empty(cs.Q, cs.k, dtype=torch.float32, device=dev)
+            out_i = torch.empty(cs.Q, cs.k, dtype=torch.int64, device=dev)
+            ms, scan, wall, spread = time_search(ixs, torch, qd, cs.k, cs.lam, mask_s, out_s, out_i, 5, 50)
+            rb = ixs.store_view()[0].shape[1]
+            small_cfgs[name] = {
+                "workload": f"{name}: N={cs.N} d={cs.d} bf16 store, Q={cs.Q}, k={cs.k}, lambda={cs.lam}, "
+                            f"{1.0 - cs.p_valid:.0%} masked rows",
+                "queries_per_s": cs.Q / (ms * 1e-3), "ms_per_step": ms, "scan_kernel_ms": scan, "step_ms": spread,
+                "step_hbm_frac": cs.N * rb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "step_mfma_frac": 2.0 * cs.Q * cs.N * cs.d / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            }
+            ixs.close()
+            ixs.arena = None
+            del ixs, qd, out_s, out_i, masks, mask_s
+            torch.cuda.empty_cache()
+        say("small configurations done")
     # ---- self-similarity census: every row of a 1M-row store against all the others, k = 1
     census = None
     if not args.no_large_batch:
@@ -398,6 +434,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "large_batch": large,
         "roofline_mfma": roof_mfma,
+        "small_configs": small_cfgs,
         "fp8_store": fp8,
         "maintenance": maintenance,
         "census": census,

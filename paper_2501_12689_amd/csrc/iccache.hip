@@ -731,7 +731,10 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             ic::GemmArgs p = g;
             const int64_t want = (k <= 16) ? 64 : 32;
             // at least max(k, 64) sampled tiles, so that the k-th largest slice maximum exists
-            p.tile_stride = std::max<int64_t>(1, std::min<int64_t>(want, g.ntiles / std::max(k, 64)));
+            // and dense enough that a tile of 256 x 256 scores has about 24 or fewer above the thresholds
+            // (256 queries x stride * k rows per query x 256 / n rows): the per-tile hit list holds 96
+            const int64_t by_hits = g.ntiles * 3 / (32 * (int64_t)k);
+            p.tile_stride = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, by_hits), g.ntiles / std::max(k, 64)));
             p.ntiles = (g.ntiles + p.tile_stride - 1) / p.tile_stride;
             p.pilot_out = index->pilot_keys;
             p.pilot_stride = kPilotSlices;
