@@ -53,6 +53,10 @@ LARGE = [
     ("fp8", 270000, 100, 16, 128, 10, 0.3, "uniform", 0.95),
     ("bf16", 262400, 1024, 16, 140, 8, 0.0, "none", 1.0),     # longest bf16 rows: 32 pipeline steps per tile
     ("fp8", 262145, 1024, 16, 129, 128, 0.05, "uniform", 0.99),  # ragged last tile of one row, largest k
+    # one block with at most 128 queries: half of the wavefronts only copy and synchronise
+    ("bf16", 280000, 192, 32, 100, 20, 0.1, "uniform", 0.9),
+    ("bf16", 263000, 768, 32, 65, 64, 0.0, "none", 1.0),
+    ("fp8", 290000, 512, 32, 97, 33, 0.0, "none", 0.8),
 ]
 
 
