@@ -11,10 +11,10 @@
 
 namespace ic {
 
-// assign[i] = cluster of row i from a k = 1 search result (ids [n] int64, -1 = none)
-__global__ void ivf_take_assignment(const int64_t *__restrict__ ids, int64_t n, int32_t *__restrict__ assign) {
+// assign[i] = cluster of row i from its key (score of the best centroid, its id); 0 = no key: -1
+__global__ void ivf_take_assignment(const uint64_t *__restrict__ keys, int64_t n, int32_t *__restrict__ assign) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) assign[i] = (int32_t)ids[i];
+    if (i < n) assign[i] = keys[i] > kKeyFloor ? (int32_t)key_id(keys[i]) : -1;
 }
 
 __global__ void ivf_zero_i64(int64_t *__restrict__ p, int64_t n) {

@@ -38,6 +38,9 @@
 //     by the streaming scan, so the result stays exact whatever the data.
 //   * Pilot launches (PILOT = true) run the same pipeline over a strided sample of the row tiles
 //     and keep, per query and slice, only the best score.
+//   * Row-maximum launches (ROWMAX = true) turn the selection around: for every cached row the
+//     best of the "queries" (with ties to the lowest query id), as one 64-bit key per row.  This
+//     is the assignment step of K-Means (Sec. 4.1): the queries are the centroids.
 #pragma once
 #include <type_traits>
 
@@ -77,6 +80,7 @@ struct GemmArgs {
     const int32_t *q_dom;    // DOM: domain of every query, [Q]; row i is visible to q if row_dom[i] is 0 or q_dom[q]
     int64_t self_first;      // self-search: query q is stored row self_first + q and must not select
                              // itself (a tile on the diagonal would otherwise list 256 hits); -1: off
+    uint64_t *row_best;      // ROWMAX: [n] keys (score of the best query, its id), zeroed before the launch
     int gq;                  // XCD mapping: query-block groups (1, 2, 4 or 8); 8/gq row classes
 };
 
@@ -95,8 +99,9 @@ constexpr size_t gemm_lds_bytes() {
            (size_t)kGemmHits * sizeof(HitEntry) + kGemmTile * 4;
 }
 
-template <int ET, bool PILOT, bool DOM = false>
+template <int ET, bool PILOT, bool DOM = false, bool ROWMAX = false>
 __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
+    static_assert(!ROWMAX || (!PILOT && !DOM), "row maxima take neither thresholds nor domains");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
     constexpr int kSlot = 2 * kGemmTile * kGemmHalfBytes;  // 32 KB: 256 rows then 256 queries, 64 B each
@@ -354,16 +359,16 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 for (int j = 0; j < 4; ++j) {
                     int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
                     if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
-                    thr_raw[j] = PILOT ? 0ull : a.thr_init[q];
+                    thr_raw[j] = (PILOT || ROWMAX) ? 0ull : a.thr_init[q];
                     qs[j] = (ET == 1) ? a.q_scale[q] : 1.0f;
                     if (DOM) qd[j] = a.q_dom[q];
                 }
-                if (tid < 64) {
+                if (tid < 64 && !ROWMAX) {
                     bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
                     if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
                     if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
                 }
-                if (!PILOT) {
+                if (!PILOT && !ROWMAX) {
                     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
                     if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
                 }
@@ -441,16 +446,16 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 for (int j = 0; j < 4; ++j) {
                     int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
                     if (q >= a.Q) q = a.Q - 1;  // padding query: read something valid, masked below
-                    thr_raw[j] = PILOT ? 0ull : a.thr_init[q];
+                    thr_raw[j] = (PILOT || ROWMAX) ? 0ull : a.thr_init[q];
                     qs[j] = a.q_scale[q];
                     if (DOM) qd[j] = a.q_dom[q];
                 }
-                if (tid < 64) {
+                if (tid < 64 && !ROWMAX) {
                     bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
                     scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
                     if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
                 }
-                if (!PILOT) {
+                if (!PILOT && !ROWMAX) {
                     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
                     if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
                 }
@@ -491,6 +496,53 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             half8(std::true_type{}, std::integral_constant<int, 1>{});
         }
 
+        if (ROWMAX) {
+            // Row maxima: for each of the tile's rows the best of this block's queries.  A row's
+            // positive scale does not change which query is best, so only the queries' scales enter.
+            // A lane holds 4 queries of 32 rows; it keeps the best key per row, the 32 lanes that
+            // share those rows combine theirs with a butterfly, and lane r32 of the group adds the
+            // key of the group's r32-th row to that row's key in global memory (64-bit atomic
+            // maximum; the other query blocks and the other half of this block do the same).
+            uint64_t best[2][16];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) best[i][v] = 0ull;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
+                if (q < a.Q) {
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const float x = (ET == 1) ? acc[i][j][v] * qs[j] : acc[i][j][v];
+                            const uint64_t key = make_key(x, (uint32_t)q);
+                            best[i][v] = key > best[i][v] ? key : best[i][v];
+                        }
+                }
+            }
+            uint64_t mine = 0ull;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    uint64_t k64 = best[i][v];
+#pragma unroll
+                    for (int m = 1; m < 32; m <<= 1) {
+                        const uint64_t o = __shfl_xor(k64, m, kWave);
+                        k64 = o > k64 ? o : k64;
+                    }
+                    if (r32 == i * 16 + v) mine = k64;
+                }
+            {
+                const int i = r32 >> 4, v = r32 & 15;
+                const int r = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (r <= cur.last && mine > 0ull)
+                    atomicMax(reinterpret_cast<unsigned long long *>(a.row_best) + row0 + r, (unsigned long long)mine);
+            }
+            continue;
+        }
         if (PILOT) {
             // Pilot launch: the best score of every query over this tile's rows, combined into the
             // query's slice (sampled tile modulo pilot_stride) with a 64-bit atomic maximum.

@@ -180,6 +180,15 @@ void launch_gemm_one(int grid, hipStream_t st, const ic::GemmArgs &a) {
     (void)allowed;
     hipLaunchKernelGGL((ic::scan_gemm<ET, PILOT, DOM>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(), st, a);
 }
+template <int ET>
+void launch_gemm_rowmax(int grid, hipStream_t st, const ic::GemmArgs &a) {
+    static const hipError_t allowed =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET, false, false, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::gemm_lds_bytes());
+    (void)allowed;
+    hipLaunchKernelGGL((ic::scan_gemm<ET, false, false, true>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(),
+                       st, a);
+}
 template <int ET, bool PILOT>
 void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
     if (a.q_dom) launch_gemm_one<ET, PILOT, true>(grid, st, a);
@@ -999,13 +1008,33 @@ ic_status ic_ivf_assign(ic_ivf *ivf) {
     ic_index *b = ivf->base;
     ivf->cent->stream = b->stream;
     if (b->n > 0) {
-        SearchReq r;
-        r.q_rows = b->rows;
-        r.q_row_scale = b->scale;
-        ic_status st = search_impl(ivf->cent, b->n, 1, 0.0f, nullptr, ivf->tmp_scores, ivf->tmp_ids, r);
-        if (st != IC_OK) return st;
-        hipLaunchKernelGGL(ic::ivf_take_assignment, dim3((unsigned)((b->n + 255) / 256)), dim3(256), 0, b->stream,
-                           ivf->tmp_ids, b->n, ivf->assign);
+        // The tiled scan with the roles turned around: the rows are the rows, the K centroids are the
+        // block of "queries", and instead of the best rows per query it keeps the best query per
+        // row (ties to the lowest centroid id) as one key per row.
+        hipStream_t st = b->stream;
+        const Layout &L = b->L;
+        ic::GemmArgs g{};
+        g.store = b->rows;
+        g.n = b->n;
+        g.row_bytes = L.row_bytes;
+        g.row_scale = b->scale;
+        g.qbuf = ivf->cent->rows;       // padded to whole tiles of 256 rows; what lies past K is never selected
+        g.q_scale = ivf->cent->scale;
+        g.Q = ivf->K;
+        g.nqb = (ivf->K + ic::kGemmTile - 1) / ic::kGemmTile;
+        g.ntiles = (b->n + ic::kGemmTile - 1) / ic::kGemmTile;
+        g.tile_stride = 1;
+        g.self_first = -1;
+        g.row_best = (uint64_t *)ivf->tmp_ids;
+        g.gq = 1;
+        while (g.gq < 8 && (size_t)((g.nqb + g.gq - 1) / g.gq) * ic::kGemmTile * L.row_bytes > kL2Share) g.gq *= 2;
+        hipLaunchKernelGGL(ic::ivf_zero_i64, dim3((unsigned)((b->n + 255) / 256)), dim3(256), 0, st, ivf->tmp_ids, b->n);
+        const int grid = std::max(8, b->compute_units / 8 * 8);
+        if (b->store == IC_STORE_BF16) launch_gemm_rowmax<0>(grid, st, g);
+        else launch_gemm_rowmax<1>(grid, st, g);
+        hipLaunchKernelGGL(ic::ivf_take_assignment, dim3((unsigned)((b->n + 255) / 256)), dim3(256), 0, st,
+                           (const uint64_t *)ivf->tmp_ids, b->n, ivf->assign);
+        if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     }
     return ivf_build_lists(ivf);
 }
