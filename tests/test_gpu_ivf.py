@@ -49,11 +49,13 @@ def _stored(oracle, store, X):
     return oracle.decode_e4m3(c).astype(np.float64) * s[:, None].astype(np.float64)
 
 
-@pytest.mark.parametrize("store", ["bf16", "fp8"])
-def test_assignment_against_given_centroids(pkg, oracle, store):
-    _say(f"ivf assign, {store}")
-    cfg, wl, ix, E, U = _setup(pkg, store)
-    K = cfg.clusters
+@pytest.mark.parametrize("store,K,N,d", [("bf16", 48, 60000, 96), ("fp8", 48, 60000, 96),
+                                         ("bf16", 300, 40001, 64),     # two blocks of centroids, ragged last row tile
+                                         ("fp8", 515, 30000, 128),     # three blocks, the last with 3 centroids
+                                         ("bf16", 129, 20000, 768)])   # one centroid past a half block, long rows
+def test_assignment_against_given_centroids(pkg, oracle, store, K, N, d):
+    _say(f"ivf assign, {store}, K={K}, N={N}, d={d}")
+    cfg, wl, ix, E, U = _setup(pkg, store, N=N, d=d, C=K)
     C = wl.centres.numpy().copy()
     C[5] = C[4]                                   # two identical centroids: the lower id must win
     ivf = pkg.Ivf(ix, K, 4)
@@ -232,6 +234,38 @@ def test_training_against_the_reference_kmeans(pkg, oracle):
         rec = np.mean([len(set(i[q].tolist()) & set(ie[q].tolist())) / 10 for q in range(64)])
         print(f"   nprobe={nprobe}: recall@10 {rec:.4f}", flush=True)
         assert rec >= floor
+    ivf.close(); ix.close()
+
+
+def test_lists_are_a_snapshot_until_assigned_again(pkg, oracle):
+    """Rows appended or evicted after the lists were built are not seen by the pruned search until
+    ic_ivf_assign is called again; afterwards it agrees with the reference on the new store."""
+    _say("ivf snapshot / re-assign")
+    N0, extra, d, K, k = 30000, 5000, 64, 40, 8
+    cfg = workloads.Config("V", N=N0 + extra, d=d, clusters=K, Q=32, k=k, store="bf16", zipf=1.1, lam=0.0,
+                           util="none", seed=9650)
+    wl = workloads.Workload(cfg, "cpu")
+    E = wl.rows(0, N0 + extra)[0]
+    ix = pkg.Index(d, N0 + extra, pkg.STORE_BF16, 64, 16, DEV)
+    ix.append(E[:N0].to(DEV), None)
+    C = wl.centres.numpy()
+    ivf = pkg.Ivf(ix, K, K)
+    ivf.set_centroids(torch.from_numpy(C).to(DEV))
+    ivf.assign()
+    Qd = wl.queries().to(DEV)
+    ix.append(E[N0:].to(DEV), None)
+    gone = torch.arange(0, N0, 3, device=DEV)
+    ix.invalidate(gone)
+    s, i = ivf.search(Qd, k, K)                  # every list probed: the exact result over the snapshot
+    torch.cuda.synchronize()
+    assert int(i.max()) < N0                      # the appended rows are not in any list yet
+    ivf.assign()
+    s, i = ivf.search(Qd, k, K)
+    se, ie = ix.search(Qd, k)                     # the exact search sees appends and evictions at once
+    torch.cuda.synchronize()
+    assert int(i.max()) >= N0
+    assert not np.isin(i.cpu().numpy(), gone.cpu().numpy()).any()
+    assert torch.allclose(s, se, atol=2e-6) and (i == ie).float().mean() > 0.995
     ivf.close(); ix.close()
 
 
