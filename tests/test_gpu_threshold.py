@@ -26,6 +26,7 @@ CASES = [
     ("bf16", 60000, 96, 20, 24, 0.0, "none", 1.0),
     ("fp8", 50000, 128, 70, 40, 0.3, "uniform", 0.9),
     ("bf16", 280000, 128, 200, 16, 0.2, "beta25", 0.95),     # tiled scan
+    ("bf16", 70000, 96, 48, 1, 0.0, "none", 1.0),            # k = 1 with a threshold: the semantic-cache baseline's lookup
 ]
 
 
