@@ -151,6 +151,19 @@ def test_status_codes_without_a_gpu():
     left = ctypes.c_int64(-7)
     assert L.ic_index_compact(None, fake, None) == 1 and L.ic_index_compact(h, None, None) == 1
     assert L.ic_index_compact(h, fake, ctypes.byref(left)) == 0 and left.value == 0
+    # cluster pruning: sizes and argument errors are host arithmetic as well
+    assert L.ic_ivf_workspace_bytes(None, 10, 4) == 0 and L.ic_ivf_workspace_bytes(h, 0, 4) == 0
+    assert L.ic_ivf_workspace_bytes(h, 10, 0) == 0 and L.ic_ivf_workspace_bytes(h, 10, 129) == 0
+    need_ivf = L.ic_ivf_workspace_bytes(h, 10, 4)
+    assert need_ivf > 2 * need                     # a centroid index and a sorted copy of the store
+    v = ctypes.c_void_p()
+    assert L.ic_ivf_create(None, h, 10, 4, fake, need_ivf) == 1 and L.ic_ivf_create(ctypes.byref(v), None, 10, 4, fake, need_ivf) == 1
+    assert L.ic_ivf_create(ctypes.byref(v), h, 10, 4, fake, need_ivf - 1) == 3
+    assert L.ic_ivf_create(ctypes.byref(v), h, 10, 4, fake, need_ivf) == 0
+    assert L.ic_ivf_search(v, fake, 1, 1, 1, 0.0, fake, fake) == 1          # no centroids, no lists yet
+    assert L.ic_ivf_assign(v) == 1 and L.ic_ivf_update_centroids(v) == 1    # no centroids yet
+    assert L.ic_ivf_train(v, 1) == 1                                         # empty base index
+    assert L.ic_ivf_destroy(v) == 0 and L.ic_ivf_destroy(None) == 1
     assert L.ic_status_string(3) == b"capacity exceeded"
     assert L.ic_index_destroy(h) == 0 and L.ic_index_destroy(None) == 1
 
