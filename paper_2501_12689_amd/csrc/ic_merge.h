@@ -3,10 +3,11 @@
 // Sec. 4.1).
 //
 // One workgroup takes a group of segments of one query, packs their keys into LDS, sorts them
-// with a bitonic network under the (score desc, id asc) key order and writes the best k.  The
-// network is sized to the keys actually present, so nearly empty segments (the usual case once
-// the scan starts from the pilot's threshold) cost little; a group that holds more than kMergeKeys
-// keys is taken in rounds that keep the best k so far.
+// with a bitonic network under the (score desc, id asc) key order and writes the best k.  Only
+// the keys present are loaded (nearly empty segments are the usual case once the scan starts from
+// the pilot's threshold) and the network is sized to them (256 to 2048 keys; mostly in registers
+// and by lane shuffles).  A group that holds more than kMergeKeys keys is taken in rounds that
+// keep the best k so far.
 // The host chains launches until one group per query is left; the last launch decodes keys into
 // (fp32 score, int64 id).
 #pragma once
@@ -44,6 +45,68 @@ struct MergeArgs {
                                 // they are replaced by id_map[position] as the keys are loaded, so that ties
                                 // are broken by the examples' own ids
 };
+
+// Sort the first 256 * R keys of buf in descending order (256 threads; buf complete and visible
+// on entry, sorted and visible on return).  Bitonic network over element index e = R * tid + r:
+// thread tid keeps elements R*tid .. R*tid + R - 1 in registers, so the compare-exchange stages
+// with a distance below R stay inside a thread, those with a distance up to 32 * R exchange with
+// another lane of the wavefront (shuffles), and only the few with a larger distance go through
+// LDS (3 of the 66 stages for R = 8).
+template <int R>
+__device__ __forceinline__ void sort_buffer(uint64_t *buf, int tid) {
+    constexpr int kLevels = (R == 1) ? 8 : (R == 2) ? 9 : (R == 4) ? 10 : 11;
+    static_assert(R == 1 || R == 2 || R == 4 || R == 8, "keys per thread");
+    static_assert(256 * 8 == kMergeKeys, "the largest network covers the buffer");
+    uint64_t x[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) x[r] = buf[R * tid + r];
+    const int base = R * tid;
+#pragma unroll
+    for (int lvl = 1; lvl <= kLevels; ++lvl) {
+        const int size = 1 << lvl;  // sorted runs of this length alternate in direction (the last level: all descending)
+#pragma unroll
+        for (int sb = lvl - 1; sb >= 0; --sb) {
+            const int stride = 1 << sb;
+            if (stride < R) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if ((r & stride) == 0) {
+                        const bool descending = ((base + r) & size) == 0;
+                        const int r2 = (r + stride) < R ? r + stride : r;  // always r + stride here
+                        const uint64_t lo = x[r] < x[r2] ? x[r] : x[r2];
+                        const uint64_t hi = x[r] < x[r2] ? x[r2] : x[r];
+                        x[r] = descending ? hi : lo;
+                        x[r2] = descending ? lo : hi;
+                    }
+                }
+            } else {
+                const bool descending = (base & size) == 0;
+                const bool keep_max = descending == ((base & stride) == 0);
+                uint64_t y[R];
+                if (stride < 64 * R) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) y[r] = __shfl_xor(x[r], stride / R, kWave);
+                } else {
+                    __syncthreads();  // the previous readers of buf are done
+#pragma unroll
+                    for (int r = 0; r < R; ++r) buf[base + r] = x[r];
+                    __syncthreads();
+#pragma unroll
+                    for (int r = 0; r < R; ++r) y[r] = buf[(base ^ stride) + r];
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const bool take_other = keep_max ? (y[r] > x[r]) : (y[r] < x[r]);
+                    x[r] = take_other ? y[r] : x[r];
+                }
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) buf[base + r] = x[r];
+    __syncthreads();
+}
 
 __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     __shared__ uint64_t buf[kMergeKeys];
@@ -117,26 +180,14 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
             }
         }
         const int n = have + take;
-        int P = 2;
+        int P = 256;  // the network is sized to the keys present
         while (P < n || P < a.k) P <<= 1;
-        for (int e = n + tid; e < P; e += 256) buf[e] = 0;
-
-        for (int size = 2; size <= P; size <<= 1) {
-            for (int stride = size >> 1; stride > 0; stride >>= 1) {
-                __syncthreads();
-                for (int e = tid; e < (P >> 1); e += 256) {
-                    const int i = 2 * e - (e & (stride - 1));
-                    const int j = i + stride;
-                    const bool descending = (i & size) == 0;
-                    const uint64_t x = buf[i], y = buf[j];
-                    if ((x < y) == descending) {
-                        buf[i] = y;
-                        buf[j] = x;
-                    }
-                }
-            }
-        }
+        for (int e = n + tid; e < P; e += 256) buf[e] = 0;  // padding sorts to the end
         __syncthreads();
+        if (P == 256) sort_buffer<1>(buf, tid);
+        else if (P == 512) sort_buffer<2>(buf, tid);
+        else if (P == 1024) sort_buffer<4>(buf, tid);
+        else sort_buffer<8>(buf, tid);
         consumed += take;
         have = n < a.k ? n : a.k;
     } while (consumed < total);
