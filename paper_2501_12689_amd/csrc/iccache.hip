@@ -24,8 +24,10 @@ constexpr int kMaxRowBytes = 2048;     // widest row the streaming scan holds in
 constexpr int kQueryChunkMax = 8192;   // queries per pass over the store
 constexpr int kSliceBudgetMax = 1024;  // most workgroups a scan launch may use
 constexpr int kPilotSlices = 512;           // slices of the threshold pilot (>= IC_MAX_K)
-constexpr int kPilotMinQueries = 9;         // smaller batches select cheaply without a pilot
-constexpr int64_t kPilotMinTiles = (int64_t)kPilotSlices * 8 * 4;  // 8 tiles per slice at tile_mul 4
+constexpr int kPilotMinQueries = 9;         // smaller batches select cheaply without a pilot, unless k is large
+constexpr int64_t kPilotMinWork = 128;      // ... that is, unless queries x k reaches this (with at least 8 queries)
+constexpr int64_t kPilotMinTiles = (int64_t)kPilotSlices * 4;       // streaming pilot: at least every 4th tile is skipped
+constexpr int64_t kGemmMinTiles = (int64_t)kPilotSlices * 8 * 4;    // the tiled scan is used from 262,144 rows on
 constexpr int kComputeUnitsDefault = 256;   // MI355X
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxTimedEvents = 1 << 16;  // event pairs kept while timing is on
@@ -618,7 +620,7 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
     const bool pilot_ok = ntiles >= kPilotMinTiles;
     // batches large enough for the matrix cores to be the bound take the MFMA-tiled scan; it
     // needs the pilot's thresholds and the per-query candidate lists
-    const bool gemm_ok = pilot_ok && index->glist != nullptr;
+    const bool gemm_ok = ntiles >= kGemmMinTiles && index->glist != nullptr;
 
     if (!index->consts_ready) {
         hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)index->consts);
@@ -710,6 +712,16 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
         a.q_dom = req.q_domain ? req.q_domain + q0 : nullptr;
         const auto &scan_table = req.q_domain ? kScanTableDom : kScanTable;
 
+        // slices of the streaming scan: one workgroup per slice and query block; by default as
+        // many as are resident at once (two per compute unit by registers, fewer when the
+        // candidate regions fill the LDS)
+        int budget = index->slice_budget;
+        if (budget == 0) {
+            const size_t lds = ic::scan_lds_bytes(1 << qg_idx, cap);
+            const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
+            budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
+        }
+        const int S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
         // Threshold pilot: a pass over a strided sample of the tiles that keeps the best score
         // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
         // k rows, so the full scan may start from it.
@@ -763,10 +775,19 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             m.kth_out = index->thr_init;
             hipLaunchKernelGGL(ic::merge_lists, dim3(qc, 1), dim3(256), 0, st, m);
             a.thr_init = index->thr_init;
-        } else if (pilot_ok && qc >= kPilotMinQueries) {
+        } else if (pilot_ok && ((qc >= 8 && (int64_t)qc * k >= kPilotMinWork) || (qc >= 4 && (int64_t)qc * k >= 6 * kPilotMinWork) ||
+                                (qc >= kPilotMinQueries && ntiles >= kGemmMinTiles))) {
+            // It pays when the selection is a visible part of the scan: several queries and a k that
+            // is not tiny (measured break-even: about 8 queries x k = 16), always from 9 queries on
+            // a large store; a single query never needs it.
+            // Stride of the sample: every slice of the pilot keeps at least one tile, and starting
+            // from its threshold about stride * k rows per query pass, which should leave a region
+            // of the full scan (S of them per query) with 8 candidates or fewer (more of them cost
+            // more in the merges than the sparser pilot saves).
             ic::ScanArgs p = a;
             p.S = kPilotSlices;
-            p.tile_mul = (int)std::min<int64_t>(64, ntiles / (kPilotSlices * 8));
+            const int64_t by_regions = std::max<int64_t>(4, 8 * (int64_t)S / k);
+            p.tile_mul = (int)std::min<int64_t>(std::min<int64_t>(128, ntiles / kPilotSlices), by_regions);
             scan_table[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
             ic::MergeArgs m{};
             m.src = index->pilot_keys;
@@ -781,16 +802,6 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             a.thr_init = index->thr_init;
         }
 
-        // slices of the streaming scan: one workgroup per slice and query block; by default as
-        // many as are resident at once (two per compute unit by registers, fewer when the
-        // candidate regions fill the LDS)
-        int budget = index->slice_budget;
-        if (budget == 0) {
-            const size_t lds = ic::scan_lds_bytes(1 << qg_idx, cap);
-            const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
-            budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
-        }
-        const int S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
         a.S = S;
         Timer timer(index);
 
