@@ -57,6 +57,10 @@ LARGE = [
     ("bf16", 280000, 192, 32, 100, 20, 0.1, "uniform", 0.9),
     ("bf16", 263000, 768, 32, 65, 64, 0.0, "none", 1.0),
     ("fp8", 290000, 512, 32, 97, 33, 0.0, "none", 0.8),
+    # stores of 65,536 to 262,143 rows take the tiled scan only for more than 128 queries
+    ("bf16", 70001, 96, 16, 200, 24, 0.1, "uniform", 0.9),
+    ("fp8", 131072, 128, 16, 513, 128, 0.0, "none", 1.0),
+    ("bf16", 65536, 64, 8, 129, 1, 0.0, "none", 1.0),
 ]
 
 
