@@ -28,7 +28,9 @@ constexpr int kPilotMinQueries = 9;         // smaller batches select cheaply wi
 constexpr int64_t kPilotMinWork = 128;      // ... that is, unless queries x k reaches this (with at least 8 queries)
 constexpr int64_t kPilotMinTiles = (int64_t)kPilotSlices * 4;       // streaming pilot: at least every 4th tile is skipped
 constexpr int64_t kGemmMinTiles = (int64_t)kPilotSlices * 8 * 4;    // the tiled scan is used from 262,144 rows on,
-constexpr int64_t kGemmSmallTiles = (int64_t)kPilotSlices * 8;      // and from 65,536 rows on for more than 128 queries
+constexpr int64_t kGemmSmallTiles = (int64_t)kPilotSlices * 8;      // and from 65,536 rows on for more than 128 queries,
+constexpr int64_t kGemmTinyTiles = (int64_t)kPilotSlices * 2;       // from 16,384 rows on if also k <= 16 (a larger k needs
+                                                                    // a pilot as dense as the scan itself on so few rows)
 constexpr int kComputeUnitsDefault = 256;   // MI355X
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxTimedEvents = 1 << 16;  // event pairs kept while timing is on
@@ -625,7 +627,8 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
     // about even at 128)
     auto gemm_for = [&](int64_t queries) {
         return index->glist != nullptr && queries >= kGemmMinQueries &&
-               (ntiles >= kGemmMinTiles || (ntiles >= kGemmSmallTiles && queries > 128));
+               (ntiles >= kGemmMinTiles || (ntiles >= kGemmSmallTiles && queries > 128) ||
+                (ntiles >= kGemmTinyTiles && queries > 128 && k <= 16));
     };
 
     if (!index->consts_ready) {

@@ -61,6 +61,9 @@ LARGE = [
     ("bf16", 70001, 96, 16, 200, 24, 0.1, "uniform", 0.9),
     ("fp8", 131072, 128, 16, 513, 128, 0.0, "none", 1.0),
     ("bf16", 65536, 64, 8, 129, 1, 0.0, "none", 1.0),
+    # and stores of 16,384 to 65,535 rows only if also k <= 16
+    ("bf16", 20000, 128, 8, 300, 16, 0.2, "beta25", 0.9),
+    ("fp8", 16385, 64, 8, 1030, 5, 0.0, "none", 1.0),
 ]
 
 
