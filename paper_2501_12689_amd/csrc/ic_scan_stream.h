@@ -9,12 +9,18 @@
 //     s, s+S, s+2S, ...  and one block of QG*16 queries.
 //   * The embedding dimension is split over the 4 wavefronts: wavefront w owns
 //     CPW consecutive 64-byte chunks of every row.  Its share of the query block
-//     stays in registers for the whole kernel (QG*CPW 16-byte fragments), and
-//     its share of each row tile goes from global memory straight into the MFMA
-//     operand registers: lane (r = lane%16, c = lane/16) reads 16 bytes of row
-//     r at chunk offset 16*c, which is exactly the A-operand layout of
-//     v_mfma_f32_16x16x32 (row r, 8 consecutive k).  Queries use the same byte
-//     mapping for the B operand, so every product pairs equal coordinates.
+//     stays in registers for the whole kernel (QG*CPW 16-byte fragments).  The
+//     MFMA operand layout is: lane (r = lane%16, c = lane/16) holds 16 bytes of
+//     row r at chunk offset 16*c, the A-operand layout of v_mfma_f32_16x16x32
+//     (row r, 8 consecutive k).  Queries use the same byte mapping for the B
+//     operand, so every product pairs equal coordinates.
+//   * Row tiles are loaded several tiles ahead into register stages.  With an
+//     even CPW a wavefront's share of a row is whole 128-byte lines, and a load
+//     instruction fetches one full line of each of 8 rows, non-temporal (the
+//     memory system serves that pattern about 12 % faster than half a line of
+//     each of 16 rows); when a stage is consumed its fragments pass through a
+//     small LDS buffer private to the wavefront into the operand layout.  With
+//     an odd CPW the loads are made directly in the operand layout.
 //   * The 4 partial 16x16 score tiles are exchanged through LDS (one buffer,
 //     two barriers per tile) and summed in a fixed order by wavefront g < QG, which owns query group g from then on:
 //     score = dot * scales + bias, where bias = lambda * utility, or -inf for an
