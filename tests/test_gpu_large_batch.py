@@ -91,6 +91,26 @@ def test_large_batch_list_overflow_is_redone_exactly(pkg, oracle):
     parity.check_batch("bf16", b[0], b[1], a[2], None, None, a[5], 16, 0.0, "overflow", queries=range(0, 200, 9))
 
 
+def test_large_batch_on_a_store_sorted_by_cluster(pkg, oracle):
+    """Rows in cluster order (a cache filled topic by topic): a query's candidates sit in a few row
+    tiles, whose hit lists overflow, so blocks are redone by the streaming scan; the result is exact."""
+    _say("tiled scan, store sorted by cluster")
+    cfg = workloads.Config("G", N=280000, d=128, clusters=40, Q=300, k=16, store="bf16", zipf=1.1, lam=0.1,
+                           util="uniform", seed=8150)
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, _ = wl.rows(0, cfg.N)
+    Qm = wl.queries()
+    order = torch.argsort((E @ wl.centres.T).argmax(1), stable=True)
+    E, U = E[order].contiguous(), U[order].contiguous()
+    ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, cfg.Q, cfg.k, DEV)
+    ix.append(E.to(DEV), U.to(DEV))
+    s, i = ix.search(Qm.to(DEV), cfg.k, cfg.lam)
+    torch.cuda.synchronize()
+    parity.check_batch("bf16", s.cpu().numpy(), i.cpu().numpy(), E.numpy(), U.numpy(), None, Qm.numpy(), cfg.k,
+                       cfg.lam, "sorted by cluster", queries=range(0, cfg.Q, 7))
+    ix.close()
+
+
 def test_large_batch_equals_small_batches(pkg):
     """The tiled scan and the streaming scan return the same rows (scores may differ in the last bits)."""
     _say("tiled scan vs streaming scan")
