@@ -34,10 +34,13 @@
 //     in a second LDS list.  That list is flushed to the queries' candidate lists in global
 //     memory (slot = atomic counter per query) while the next tile is being computed: the atomics
 //     are issued in that tile's last step and their results used after it, so nobody waits for an
-//     L2 round trip.  If a candidate list overflows, its block of 64 queries is flagged and redone
-//     by the streaming scan, so the result stays exact whatever the data.
-//   * Pilot launches (PILOT = true) run the same pipeline over a strided sample of the row tiles
-//     and keep, per query and slice, only the best score.
+//     L2 round trip.  A tile with more such blocks than the LDS list holds keeps nothing and is
+//     noted in a list; a second, small launch (AGAIN = true) computes the listed tiles again and
+//     tests every score.  If a query's candidate list in global memory overflows, its block of 64
+//     queries is flagged and redone by the streaming scan, so the result stays exact whatever the data.
+//   * Pilot launches (PILOT = true) run the same pipeline over a strided sample of the rows (every
+//     row_stride-th row; a tile takes 256 of them spread evenly over the whole store) and keep, per
+//     query and slice, only the best score.
 //   * Row-maximum launches (ROWMAX = true) turn the selection around: for every cached row the
 //     best of the "queries" (with ties to the lowest query id), as one 64-bit key per row.  This
 //     is the assignment step of K-Means (Sec. 4.1): the queries are the centroids.
@@ -71,11 +74,17 @@ struct GemmArgs {
     int gcap;
     int32_t *gcount;         // [Q] candidates appended (may exceed gcap: the list overflowed)
     int32_t *redo;           // [ceil(Q/64)] set to 1 when a list of the block overflowed
+    uint32_t *over_n;        // tiles that listed more blocks than the per-tile list holds ...
+    uint2 *over_list;        // ... as (row tile, query block), [over_cap]; AGAIN launches walk this list
+    uint32_t over_cap;
     int nqb;                 // query blocks of 256
     int64_t ntiles;          // row tiles of 256
     uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over a sampled tile, id = tile)
     int pilot_stride;
-    int64_t tile_stride;     // the t-th row tile of the walk is tile t * tile_stride of the store (1: every tile)
+    int64_t row_stride;      // PILOT: the launch scores rows 0, row_stride, 2 * row_stride, ... only.  Row r of its
+                             // t-th tile is row r * ntiles + t of that sample, so every tile, and with it every
+                             // slice, is a uniform sample of the store whatever the order the rows arrived in
+    int64_t n_sampled;       // PILOT: rows of the sample, ceil(n / row_stride); ntiles = ceil(n_sampled / 256)
     const int32_t *row_dom;  // DOM: sharing domain of every row (0 = public), [round_up(n,256)]
     const int32_t *q_dom;    // DOM: domain of every query, [Q]; row i is visible to q if row_dom[i] is 0 or q_dom[q]
     int64_t self_first;      // self-search: query q is stored row self_first + q and must not select
@@ -99,9 +108,10 @@ constexpr size_t gemm_lds_bytes() {
            (size_t)kGemmHits * sizeof(HitEntry) + kGemmTile * 4;
 }
 
-template <int ET, bool PILOT, bool DOM = false, bool ROWMAX = false>
+template <int ET, bool PILOT, bool DOM = false, bool ROWMAX = false, bool AGAIN = false>
 __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     static_assert(!ROWMAX || (!PILOT && !DOM), "row maxima take neither thresholds nor domains");
+    static_assert(!AGAIN || (!PILOT && !ROWMAX), "only the selection launch leaves tiles to be done again");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
     constexpr int kSlot = 2 * kGemmTile * kGemmHalfBytes;  // 32 KB: 256 rows then 256 queries, 64 B each
@@ -131,9 +141,12 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     const int qgroup = xcd % a.gq, rclass = xcd / a.gq;
     const int nq_x = (a.nqb - qgroup + a.gq - 1) / a.gq;              // query blocks of this XCD
     const int64_t nr_x = (a.ntiles - rclass + gr - 1) / gr;           // row tiles of this XCD
-    const int64_t work = (int64_t)nq_x * nr_x;
-    const int64_t step = gridDim.x >> 3;
-    if ((int64_t)(blockIdx.x >> 3) >= work) return;  // nothing to do: no load is ever issued
+    // AGAIN: the jobs are the entries of over_list, dealt to the workgroups in turn
+    const uint32_t listed = AGAIN ? *a.over_n : 0u;
+    const int64_t work = AGAIN ? (int64_t)(listed < a.over_cap ? listed : a.over_cap) : (int64_t)nq_x * nr_x;
+    const int64_t step = AGAIN ? gridDim.x : gridDim.x >> 3;
+    const int64_t first_job = AGAIN ? blockIdx.x : blockIdx.x >> 3;
+    if (first_job >= work) return;  // nothing to do: no load is ever issued
 
     // Everything a tile needs to address its operands.
     struct Tile {
@@ -145,11 +158,22 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     };
     auto locate = [&](int ql, int64_t rl, Tile &t) {  // ql-th query block, rl-th row tile of this XCD
         t.qb = qgroup + a.gq * ql;
-        t.row0 = (rclass + gr * rl) * a.tile_stride * kGemmTile;
-        t.rows_base = a.store + t.row0 * a.row_bytes;
+        if (AGAIN) {
+            const uint2 e = a.over_list[rl];   // ql is 0
+            t.qb = (int)e.y;
+            t.row0 = (int64_t)e.x * kGemmTile;
+        }
         t.q_base = a.qbuf + (size_t)t.qb * kGemmTile * a.row_bytes;
-        const int64_t last = a.n - 1 - t.row0;
-        t.last = (int)(last < kGemmTile - 1 ? last : kGemmTile - 1);
+        if (PILOT) {
+            t.row0 = rclass + gr * rl;   // the tile's index: its row r is row r * ntiles + row0 of the sample
+            t.rows_base = a.store + t.row0 * a.row_stride * a.row_bytes;
+            t.last = (int)((a.n_sampled - 1 - t.row0) / a.ntiles);   // 0 .. 255 since ntiles = ceil(n_sampled / 256)
+        } else {
+            if (!AGAIN) t.row0 = (rclass + gr * rl) * kGemmTile;
+            t.rows_base = a.store + t.row0 * a.row_bytes;
+            const int64_t last = a.n - 1 - t.row0;
+            t.last = (int)(last < kGemmTile - 1 ? last : kGemmTile - 1);
+        }
     };
     // job = rl * nq_x + ql walks query blocks fastest; the pair is advanced without divisions
     struct Walk {
@@ -157,21 +181,22 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         int64_t rl;
         int64_t job;
     };
-    const int step_q = (int)(step % nq_x);
-    const int64_t step_r = step / nq_x;
+    const int nq_w = AGAIN ? 1 : nq_x;   // query blocks of the walk (a list is walked entry by entry)
+    const int step_q = (int)(step % nq_w);
+    const int64_t step_r = step / nq_w;
     auto walk_next = [&](Walk &x) {
         x.job += step;
         x.ql += step_q;
         x.rl += step_r;
-        if (x.ql >= nq_x) {
-            x.ql -= nq_x;
+        if (x.ql >= nq_w) {
+            x.ql -= nq_w;
             x.rl += 1;
         }
     };
     Walk tw;  // the tile being computed
-    tw.job = blockIdx.x >> 3;
-    tw.ql = (int)(tw.job % nq_x);
-    tw.rl = tw.job / nq_x;
+    tw.job = first_job;
+    tw.ql = (int)(tw.job % nq_w);
+    tw.rl = tw.job / nq_w;
 
     // ---- copy plan.  One direct load moves 16 rows x 64 B per wavefront: lane l lands at the
     // wavefront's LDS base + 16*l, i.e. row l/4, position l%4, and therefore fetches granule
@@ -181,7 +206,11 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     typedef void __attribute__((address_space(3))) *lptr_t;
     const int crow = lane >> 2;
     const int cg = (lane & 3) ^ ((lane >> 4) & 3);
-    uint32_t off_q[2], off_r[2];  // byte offsets from a tile's first query / first row (rows clamped per tile)
+    // byte offsets from a tile's first query / first row (rows clamped per tile; 64 bits only for a
+    // pilot, whose rows lie ntiles * row_stride rows apart)
+    uint32_t off_q[2];
+    typename std::conditional<PILOT, uint64_t, uint32_t>::type off_r[2];
+    const uint64_t row_pitch = PILOT ? (uint64_t)a.ntiles * (uint64_t)a.row_stride * (uint64_t)a.row_bytes : (uint64_t)a.row_bytes;
 #pragma unroll
     for (int u = 0; u < 2; ++u) off_q[u] = (uint32_t)(((w + 8 * u) * 16 + crow) * a.row_bytes + cg * 16);
     Walk cw = tw;   // the load cursor runs kGemmSlots pipeline steps ahead of the computation
@@ -197,7 +226,8 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         for (int u = 0; u < 2; ++u) {
             int r = (w + 8 * u) * 16 + crow;
             r = r < t.last ? r : t.last;  // ragged last tile: rows past the end re-read the last valid row (bias -inf)
-            off_r[u] = (uint32_t)(r * a.row_bytes + cg * 16);
+            if (PILOT) off_r[u] = (uint64_t)r * row_pitch + (uint64_t)(cg * 16);
+            else off_r[u] = (uint32_t)(r * a.row_bytes + cg * 16);
         }
     };
     auto issue = [&](int slot) {  // request the cursor's step into an LDS slot
@@ -297,6 +327,25 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         i32x4 dom_r = {0, 0, 0, 0};   // DOM: the tile's row domains and this lane's query domains
         int qd[4] = {0, 0, 0, 0};
 
+        // bias, scale and domain of rows 4 * tid .. 4 * tid + 3 of the tile (threads 0-63)
+        auto row_terms = [&]() {
+            if (PILOT) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t sampled = (int64_t)(tid * 4 + e) * a.ntiles + row0;
+                    const bool in = sampled < a.n_sampled;
+                    const int64_t at = in ? sampled * a.row_stride : 0;   // the sampled row's place in the store
+                    bias_r[e] = in ? a.bias[at] : -INFINITY;
+                    if (ET == 1) scale_r[e] = in ? a.row_scale[at] : 1.0f;
+                    if (DOM) dom_r[e] = in ? a.row_dom[at] : 0;
+                }
+            } else {
+                bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
+                if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
+                if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
+            }
+        };
+
         i32x4 fa[2][2], fb[2][4];
         auto read_frags = [&](int slot, int p, i32x4 *xa, i32x4 *xb) {
             const uint8_t *sa = lds + slot * kSlot + a_base + frag_off[p];
@@ -363,11 +412,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                     qs[j] = (ET == 1) ? a.q_scale[q] : 1.0f;
                     if (DOM) qd[j] = a.q_dom[q];
                 }
-                if (tid < 64 && !ROWMAX) {
-                    bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
-                    if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
-                    if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
-                }
+                if (tid < 64 && !ROWMAX) row_terms();
                 if (!PILOT && !ROWMAX) {
                     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
                     if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
@@ -450,11 +495,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                     qs[j] = a.q_scale[q];
                     if (DOM) qd[j] = a.q_dom[q];
                 }
-                if (tid < 64 && !ROWMAX) {
-                    bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
-                    scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
-                    if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
-                }
+                if (tid < 64 && !ROWMAX) row_terms();
                 if (!PILOT && !ROWMAX) {
                     const uint32_t parked = min(*park_n, (uint32_t)kGemmPark);  // final: barriers since it was written
                     if ((uint32_t)tid < parked) fl_pos = atomicAdd(a.gcount + park_q[tid], 1);
@@ -544,8 +585,8 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             continue;
         }
         if (PILOT) {
-            // Pilot launch: the best score of every query over this tile's rows, combined into the
-            // query's slice (sampled tile modulo pilot_stride) with a 64-bit atomic maximum.
+            // Pilot launch: the best score of every query over this tile's 256 sampled rows, combined
+            // into the query's slice (tile of the sample modulo pilot_stride) with a 64-bit atomic maximum.
             uint32_t *pmax = reinterpret_cast<uint32_t *>(hits);  // [kGemmTile] order-preserving score bits
             if (tid < 64) {
                 *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
@@ -581,7 +622,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             lds_barrier();
             if (tid < kGemmTile) {
                 const int q = qb * kGemmTile + tid;
-                const uint32_t slice = (uint32_t)((row0 / (a.tile_stride * kGemmTile)) % a.pilot_stride);
+                const uint32_t slice = (uint32_t)(row0 % a.pilot_stride);
                 if (q < a.Q)
                     atomicMax(reinterpret_cast<unsigned long long *>(a.pilot_out) + (size_t)q * a.pilot_stride + slice,
                               ((unsigned long long)pmax[tid] << 32) | (unsigned long long)(0xFFFFFFFFu - slice));
@@ -640,6 +681,36 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                         if (ds[v >> 2][v & 3] != 0 && ds[v >> 2][v & 3] != qd[j]) acc[i][j][v] = -INFINITY;
             }
         }
+        if (AGAIN) {
+            // A tile that listed more blocks than the list holds: every score is tested exactly by
+            // the lane that holds it, and what passes is appended to its query's list at once.
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                f32x4 bs[4], rs[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int rr = wm * 64 + i * 32 + 8 * u + 4 * h;
+                    bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
+                    if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
+                    if (q >= a.Q) continue;
+                    const uint64_t t0 = thr_raw[j];
+                    const uint64_t thr_k = t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
+                                                  : acc[i][j][v] + bs[v >> 2][v & 3];
+                        const uint32_t row = (uint32_t)(row0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3));
+                        const uint64_t key = make_key(x, row);
+                        if (key > thr_k && x > -INFINITY) append_global((uint32_t)q, key, atomicAdd(a.gcount + q, 1));
+                    }
+                }
+            }
+            continue;
+        }
         // pass 1: 8 blocks of 16 scores per lane.  A lane whose block reaches the query's
         // threshold (about 17 lanes per tile) copies the block's scores to a small LDS list.
 #pragma unroll
@@ -672,16 +743,29 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                         e.q = (uint32_t)q;
                         e.row = (uint32_t)(row0 + wm * 64 + i * 32 + 4 * h);  // row of score 0; score v: + 8*(v/4) + v%4
                         e.thr = thr_raw[j];
-                    } else {
-                        a.redo[q >> 6] = 1;  // list full (never in practice): the block is redone exactly
-                    }
+                    }   // list full: the whole tile is left to a second launch, see below
                 }
             }
         }
         lds_barrier();
         // pass 2: the listed blocks, one score per thread; what passes the exact key test is parked
         {
-            const uint32_t nh = min(*hit_n, (uint32_t)kGemmHits);
+            // A tile that listed more blocks than the list holds (rows that suit many of the block's
+            // queries at once, e.g. a high utility) keeps nothing: it goes on the list of tiles that a
+            // second launch does again, testing every score; if that list is full too, the block's
+            // queries are redone by the streaming scan.
+            uint32_t nh = *hit_n;
+            if (nh > (uint32_t)kGemmHits) {
+                if (tid == 0) {
+                    const uint32_t slot = atomicAdd(a.over_n, 1u);
+                    if (slot < a.over_cap) {
+                        a.over_list[slot] = make_uint2((uint32_t)(row0 / kGemmTile), (uint32_t)qb);
+                    } else {
+                        for (int b = qb * 4; b < qb * 4 + 4 && b * 64 < a.Q; ++b) a.redo[b] = 1;
+                    }
+                }
+                nh = 0u;
+            }
             const int v = tid & 15;
             for (uint32_t e = tid >> 4; e < nh; e += kGemmThreads / 16) {
                 const HitEntry &he = hits[e];
@@ -726,10 +810,11 @@ __global__ void gemm_pilot_reset(uint64_t *keys, int64_t count) {
 }
 
 // Zero the per-query counters and the redo flags before a scan_gemm launch.
-__global__ void gemm_reset(int32_t *gcount, int nq, int32_t *redo, int nblk) {
+__global__ void gemm_reset(int32_t *gcount, int nq, int32_t *redo, int nblk, uint32_t *over_n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nq) gcount[i] = 0;
     if (i < nblk) redo[i] = 0;
+    if (i == 0) *over_n = 0u;
 }
 
 }  // namespace ic

@@ -34,8 +34,8 @@
 //     loads that are in flight.
 //   * At the end the regions and their sizes are written out; a merge kernel
 //     combines the S regions of every query.
-//   * Pilot variant (PILOT = true).  The same kernel run over every tile_mul-th tile keeps,
-//     per query, only the best score of its slice.  With S >= k slices the k-th
+//   * Pilot variant (PILOT = true).  The same kernel run over every tile_mul-th row (a uniform
+//     sample of the rows, 16 sampled rows to a tile) keeps, per query, only the best score of its slice.  With S >= k slices the k-th
 //     largest of those S maxima is a score that at least k rows reach, i.e. a
 //     valid starting threshold for the full scan, which then appends only the few
 //     rows that beat it instead of warming its thresholds up slice by slice.
@@ -63,7 +63,7 @@ struct ScanArgs {
     int S;                   // slices == gridDim.x
     uint64_t *regions;       // [Q][S][cap] keys
     int32_t *counts;         // [Q][S] keys in use
-    int tile_mul;            // the kernel visits tiles 0, tile_mul, 2*tile_mul, ... (1 = all)
+    int tile_mul;            // PILOT kernels score rows 0, tile_mul, 2*tile_mul, ... only
     uint64_t *pilot_out;     // PILOT kernels: [Q][S] keys (best score of the slice, id = slice)
     const uint64_t *thr_init;  // full scan: per query, key of a score that >= k rows reach, or NULL
     const int32_t *redo;     // if not NULL (QG == 4 only): query blocks whose flag is 0 are skipped
@@ -258,10 +258,13 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
 
     __syncthreads();
 
-    const int64_t tile_mul = a.tile_mul;
+    // A pilot scores rows 0, tile_mul, 2 * tile_mul, ... only, and row r of its t-th tile is row
+    // r * ntiles + t of that sample: every tile, and with it every slice, is a uniform sample of the
+    // store whatever the order the rows arrived in.  Below, last_row of a pilot counts sampled rows.
+    const int64_t tile_mul = PILOT ? a.tile_mul : 1;
     const int64_t tile0 = row_lo >> 4;  // first tile of the range (0 unless TASK)
-    const int64_t ntiles = ((((row_hi + 15) >> 4) - tile0) + tile_mul - 1) / tile_mul;  // tiles this launch visits
-    const int64_t last_row = row_hi - 1;
+    const int64_t last_row = PILOT ? (row_hi - 1) / tile_mul : row_hi - 1;
+    const int64_t ntiles = ((last_row + 16) >> 4) - tile0;  // tiles this launch visits
     const int64_t S = a.S;
 
     // Everything a tile needs from global memory, requested kStages - 1 tiles ahead: two tiles for
@@ -278,28 +281,39 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     };
     Stage st[kStages];
     auto load_stage = [&](int64_t t, Stage &x) {
-        const int64_t tt = tile0 + (t < ntiles ? t : ntiles - 1) * tile_mul;
+        const int64_t tt = tile0 + (t < ntiles ? t : ntiles - 1);
         if (LINES) {
-            int64_t r0 = tt * 16 + l8, r1 = r0 + 8;
+            int64_t r0 = PILOT ? l8 * ntiles + tt : tt * 16 + l8, r1 = r0 + (PILOT ? 8 * ntiles : 8);
             if (r0 > last_row) r0 = last_row;  // ragged tail: re-read a valid row, masked out later
             if (r1 > last_row) r1 = last_row;
-            const uint8_t *p0 = a.store + r0 * (int64_t)a.row_bytes + p8 * 16;
-            const uint8_t *p1 = a.store + r1 * (int64_t)a.row_bytes + p8 * 16;
+            const uint8_t *p0 = a.store + r0 * tile_mul * (int64_t)a.row_bytes + p8 * 16;
+            const uint8_t *p1 = a.store + r1 * tile_mul * (int64_t)a.row_bytes + p8 * 16;
 #pragma unroll
             for (int c = 0; c < CPW; ++c)
                 x.rows[c] = __builtin_nontemporal_load(
                     reinterpret_cast<const i32x4 *>(((c & 1) ? p1 : p0) + loff[c >> 1]));
         } else {
-            int64_t r = tt * 16 + r16;
+            int64_t r = PILOT ? r16 * ntiles + tt : tt * 16 + r16;
             if (r > last_row) r = last_row;
-            const uint8_t *p = a.store + r * (int64_t)a.row_bytes + c4 * 16;
+            const uint8_t *p = a.store + r * tile_mul * (int64_t)a.row_bytes + c4 * 16;
 #pragma unroll
             for (int c = 0; c < CPW; ++c) x.rows[c] = *reinterpret_cast<const i32x4 *>(p + coff[c]);
         }
         const int64_t i0 = tt * 16 + c4 * 4;
-        x.bias = *reinterpret_cast<const f32x4 *>(a.bias + i0 * a.bias_stride);
-        if (DOM) x.dom = *reinterpret_cast<const i32x4 *>(a.row_dom + i0);
-        if (ET == 1) x.rsc = *reinterpret_cast<const f32x4 *>(a.row_scale + i0);
+        if (PILOT) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int64_t sampled = (c4 * 4 + v) * ntiles + tt;
+                const int64_t at = (sampled <= last_row ? sampled : last_row) * tile_mul;
+                x.bias[v] = a.bias[at * a.bias_stride];
+                if (DOM) x.dom[v] = a.row_dom[at];
+                if (ET == 1) x.rsc[v] = a.row_scale[at];
+            }
+        } else {
+            x.bias = *reinterpret_cast<const f32x4 *>(a.bias + i0 * a.bias_stride);
+            if (DOM) x.dom = *reinterpret_cast<const i32x4 *>(a.row_dom + i0);
+            if (ET == 1) x.rsc = *reinterpret_cast<const f32x4 *>(a.row_scale + i0);
+        }
     };
 
     // The loop body is unrolled by kStages so that the stage buffers are addressed statically.
@@ -372,14 +386,16 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                 __syncthreads();  // the partial tiles may be overwritten from here on
 
                 if (w < QG) {
-                    const int64_t i0 = (tile0 + t * tile_mul) * 16 + c4 * 4;
+                    // first of this lane's 4 rows; a pilot's are sampled rows i0, i0 + ntiles, ...
+                    const int64_t i0 = PILOT ? c4 * 4 * ntiles + t : (tile0 + t) * 16 + c4 * 4;
+                    const int64_t i_step = PILOT ? ntiles : 1;
                     uint64_t key[4];
                     uint32_t pend = 0;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         float sc = (ET == 1) ? sum[v] * (cur.rsc[v] * q_scale) + cur.bias[v]
                                              : sum[v] + cur.bias[v];
-                        if (i0 + v > last_row) sc = -INFINITY;
+                        if (i0 + v * i_step > last_row || (PILOT && t >= ntiles)) sc = -INFINITY;
                         if (DOM && cur.dom[v] != 0 && cur.dom[v] != q_dom) sc = -INFINITY;  // another domain's row
                         if (TASK && i0 + v < row_lo) sc = -INFINITY;  // the first tile may start in the previous list
                         if (PILOT) {

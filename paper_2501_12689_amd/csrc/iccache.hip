@@ -38,6 +38,7 @@ constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on que
 constexpr int kGemmMinQueries = 65;         // batches from here on use the MFMA-tiled scan (one tile is 256 queries wide, but from
                                             // 65 queries on it already beats two passes of the streaming scan: 4.1 vs 4.7 ms at d=768)
 constexpr int kGemmListSeg = ic::kMergeKeys;  // candidate lists are merged in segments of this many keys
+constexpr uint32_t kGemmOverCap = 4096;       // tiles of one tiled scan that may be left to its second launch
 constexpr int kGemmListMax = 8 * kGemmListSeg;
 constexpr size_t kL2Share = 4u << 20;       // query-block bytes of a group of XCDs (measured: 4 MB beats 2 MB and 8 MB by about 3 %)
 
@@ -67,7 +68,7 @@ struct Layout {
     int64_t cap_pad = 0;
     size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
            off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, off_pilot = 0, off_thr = 0, off_glist = 0, off_gcount = 0,
-           off_redo = 0, off_valid = 0, off_blocks = 0, off_domain = 0, total = 0;
+           off_redo = 0, off_over = 0, off_valid = 0, off_blocks = 0, off_domain = 0, total = 0;
     int64_t list_slots = 0;
     int q_rows = 0;  // rows of the prepared query block
 };
@@ -107,6 +108,7 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_glist = take(gemm ? (size_t)L.q_chunk * (size_t)gemm_list_cap(max_k) * 8 : 0);
     L.off_gcount = take(gemm ? (size_t)L.q_chunk * 4 : 0);
     L.off_redo = take(gemm ? (size_t)(L.q_chunk / 64 + 1) * 4 : 0);
+    L.off_over = take(gemm ? 8 + (size_t)kGemmOverCap * 8 : 0);
     L.off_valid = take((size_t)L.cap_pad);                                          // persistent validity, 1 B/row
     L.off_blocks = take((size_t)(L.cap_pad / ic::kScanBlock + 2) * 8);              // compaction: block offsets
     L.off_domain = take((size_t)L.cap_pad * 4);                                      // sharing domain, 4 B/row
@@ -177,13 +179,14 @@ const ScanFn kTaskTable[2][8] = {
      launch_scan_task<1, 5>, launch_scan_task<1, 6>, launch_scan_task<1, 7>, launch_scan_task<1, 8>},
 };
 
-template <int ET, bool PILOT, bool DOM>
+template <int ET, bool PILOT, bool DOM, bool AGAIN = false>
 void launch_gemm_one(int grid, hipStream_t st, const ic::GemmArgs &a) {
     static const hipError_t allowed =
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET, PILOT, DOM>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&ic::scan_gemm<ET, PILOT, DOM, false, AGAIN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)ic::gemm_lds_bytes());
     (void)allowed;
-    hipLaunchKernelGGL((ic::scan_gemm<ET, PILOT, DOM>), dim3(grid), dim3(ic::kGemmThreads), ic::gemm_lds_bytes(), st, a);
+    hipLaunchKernelGGL((ic::scan_gemm<ET, PILOT, DOM, false, AGAIN>), dim3(grid), dim3(ic::kGemmThreads),
+                       ic::gemm_lds_bytes(), st, a);
 }
 template <int ET>
 void launch_gemm_rowmax(int grid, hipStream_t st, const ic::GemmArgs &a) {
@@ -198,6 +201,12 @@ template <int ET, bool PILOT>
 void launch_gemm(int grid, hipStream_t st, const ic::GemmArgs &a) {
     if (a.q_dom) launch_gemm_one<ET, PILOT, true>(grid, st, a);
     else launch_gemm_one<ET, PILOT, false>(grid, st, a);
+}
+// the tiles the selection launch left undone (it listed them), each computed again and tested score by score
+template <int ET>
+void launch_gemm_again(int grid, hipStream_t st, const ic::GemmArgs &a) {
+    if (a.q_dom) launch_gemm_one<ET, false, true, true>(grid, st, a);
+    else launch_gemm_one<ET, false, false, true>(grid, st, a);
 }
 
 }  // namespace
@@ -233,6 +242,7 @@ struct ic_index {
     uint64_t *glist;       // [q_chunk][gemm_list_cap(max_k)], NULL when max_queries < kGemmMinQueries
     int32_t *gcount;       // [q_chunk]
     int32_t *redo;         // [q_chunk/64 + 1]
+    uint32_t *over;        // [0]: tiles left to the second launch of the tiled scan; from [2] on: the (tile, block) pairs
     int gemm_list_cap_override;  // tests: shrink the candidate lists to force the overflow path
     bool consts_ready;  // written by the first search (creation launches nothing)
     bool timing;
@@ -312,6 +322,7 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->glist = gemm ? (uint64_t *)(base + L.off_glist) : nullptr;
     ix->gcount = gemm ? (int32_t *)(base + L.off_gcount) : nullptr;
     ix->redo = gemm ? (int32_t *)(base + L.off_redo) : nullptr;
+    ix->over = gemm ? (uint32_t *)(base + L.off_over) : nullptr;
     ix->gemm_list_cap_override = 0;
     if (const char *e = std::getenv("IC_GEMM_LIST_CAP")) {  // tests only
         int v = std::atoi(e);
@@ -747,7 +758,8 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             g.Q = qc;
             g.nqb = nqb_gemm;
             g.ntiles = (n + ic::kGemmTile - 1) / ic::kGemmTile;
-            g.tile_stride = 1;
+            g.row_stride = 1;
+            g.n_sampled = n;
             g.self_first = fo.self_first;
             g.row_dom = index->domain;
             g.q_dom = a.q_dom;
@@ -756,16 +768,19 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
         }
         if (gemm) {
             // The pilot of the tiled scan is the tiled scan itself over every 32nd (small k: 64th)
-            // tile of 256 rows; a slice is the set of sampled tiles with the same index modulo
-            // kPilotSlices.  Starting from its threshold about stride * k rows per query pass.
+            // row of the store; a tile takes 256 sampled rows spread evenly over the whole store and
+            // a slice is the set of tiles with the same index modulo kPilotSlices, so every slice is
+            // a uniform sample even when the rows arrived sorted by topic.  Starting from its
+            // threshold about stride * k rows per query pass.
             ic::GemmArgs p = g;
             const int64_t want = (k <= 16) ? 64 : 32;
             // at least max(k, 64) sampled tiles, so that the k-th largest slice maximum exists
             // and dense enough that a tile of 256 x 256 scores has about 24 or fewer above the thresholds
             // (256 queries x stride * k rows per query x 256 / n rows): the per-tile hit list holds 96
             const int64_t by_hits = g.ntiles * 3 / (32 * (int64_t)k);
-            p.tile_stride = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, by_hits), g.ntiles / std::max(k, 64)));
-            p.ntiles = (g.ntiles + p.tile_stride - 1) / p.tile_stride;
+            p.row_stride = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, by_hits), g.ntiles / std::max(k, 64)));
+            p.n_sampled = (n + p.row_stride - 1) / p.row_stride;
+            p.ntiles = (p.n_sampled + ic::kGemmTile - 1) / ic::kGemmTile;
             p.pilot_out = index->pilot_keys;
             p.pilot_stride = kPilotSlices;
             const int64_t nkeys = (int64_t)qc * kPilotSlices;
@@ -818,16 +833,23 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             const int gcap = index->gemm_list_cap_override ? index->gemm_list_cap_override : gemm_list_cap(k);
             const int nblk64 = (qc + 63) / 64;
             hipLaunchKernelGGL(ic::gemm_reset, dim3((qc + 255) / 256), dim3(256), 0, st, index->gcount, qc,
-                               index->redo, nblk64);
+                               index->redo, nblk64, index->over);
             g.thr_init = index->thr_init;
             g.glist = index->glist;
             g.gcap = gcap;
             g.gcount = index->gcount;
             g.redo = index->redo;
+            g.over_n = index->over;
+            g.over_list = reinterpret_cast<uint2 *>(index->over + 2);
+            g.over_cap = kGemmOverCap;
             if (!timer.start()) return IC_ERR_DEVICE;
             if (et == 0) launch_gemm<0, false>(gemm_grid, st, g);
             else launch_gemm<1, false>(gemm_grid, st, g);
             timer.stop();
+            // tiles with more hits than the per-tile list holds were listed instead: a second launch
+            // does them again (its workgroups find the list empty, nearly always, and return)
+            if (et == 0) launch_gemm_again<0>(gemm_grid, st, g);
+            else launch_gemm_again<1>(gemm_grid, st, g);
 
             // blocks whose candidate lists overflowed are redone by the streaming scan; the
             // thresholds come from the other kernel, hence the slack (1e-4 bounds the difference
@@ -1043,7 +1065,8 @@ ic_status ic_ivf_assign(ic_ivf *ivf) {
         g.Q = ivf->K;
         g.nqb = (ivf->K + ic::kGemmTile - 1) / ic::kGemmTile;
         g.ntiles = (b->n + ic::kGemmTile - 1) / ic::kGemmTile;
-        g.tile_stride = 1;
+        g.row_stride = 1;
+        g.n_sampled = g.n;
         g.self_first = -1;
         g.row_best = (uint64_t *)ivf->tmp_ids;
         g.gq = 1;
