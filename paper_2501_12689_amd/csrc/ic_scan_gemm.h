@@ -779,8 +779,8 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                     if (slot < (uint32_t)kGemmPark) {
                         park_key[slot] = key;
                         park_q[slot] = he.q;
-                    } else {
-                        a.redo[he.q >> 6] = 1;
+                    } else {   // more than kGemmPark candidates in one tile: appended at once
+                        append_global(he.q, key, atomicAdd(a.gcount + he.q, 1));
                     }
                 }
             }
