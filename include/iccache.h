@@ -270,6 +270,18 @@ ic_status ic_index_store_view(const ic_index *index, const void **rows_dev,
 ic_status ic_index_set_timing(ic_index *index, int enable);
 ic_status ic_index_scan_time_ms(ic_index *index, float *ms, int64_t *launches);
 
+/*
+ * Diagnostics of the last batch that took the tiled scan (large batches): how
+ * many (row tile, query block) pairs had more hits than the tile's on-chip list
+ * holds and were computed a second time, and how many blocks of 64 queries
+ * overflowed their candidate list in device memory and were redone by the
+ * streaming scan.  Both are 0 on typical data; they cost time, never
+ * exactness.  Waits for the index's stream.  Either out pointer may be NULL.
+ * An index too small for the tiled scan reports zeros.
+ */
+ic_status ic_index_tiled_scan_counts(ic_index *index, int64_t *tiles_again,
+                                     int64_t *blocks_redone);
+
 /* Static description of a status code. */
 const char *ic_status_string(ic_status s);
 

@@ -23,7 +23,7 @@ IC_ARENA_ALIGN = 256
 EXPORTS = (
     "ic_workspace_bytes", "ic_index_create", "ic_index_append", "ic_search", "ic_index_destroy",
     "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing",
-    "ic_index_scan_time_ms", "ic_status_string",
+    "ic_index_scan_time_ms", "ic_index_tiled_scan_counts", "ic_status_string",
     "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
     "ic_search_threshold", "ic_self_search", "ic_index_set_domains", "ic_search_domains",
     "ic_ivf_workspace_bytes", "ic_ivf_create", "ic_ivf_destroy", "ic_ivf_set_centroids", "ic_ivf_assign",
@@ -81,6 +81,8 @@ def load_library() -> ctypes.CDLL:
     L.ic_index_set_timing.argtypes = [vp, ctypes.c_int]
     L.ic_index_scan_time_ms.restype = ctypes.c_int
     L.ic_index_scan_time_ms.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(i64)]
+    L.ic_index_tiled_scan_counts.restype = ctypes.c_int
+    L.ic_index_tiled_scan_counts.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     L.ic_index_set_domains.restype = ctypes.c_int
     L.ic_index_set_domains.argtypes = [vp, vp, vp, i64]
     L.ic_search_domains.restype = ctypes.c_int
@@ -287,6 +289,13 @@ class Index:
         _check(load_library().ic_index_scan_time_ms(self.handle, ctypes.byref(ms), ctypes.byref(cnt)),
                "ic_index_scan_time_ms")
         return float(ms.value), int(cnt.value)
+
+    def tiled_scan_counts(self) -> Tuple[int, int]:
+        """(tiles computed a second time, blocks of 64 queries redone) of the last large batch."""
+        again, redone = ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(load_library().ic_index_tiled_scan_counts(self.handle, ctypes.byref(again), ctypes.byref(redone)),
+               "ic_index_tiled_scan_counts")
+        return int(again.value), int(redone.value)
 
     def store_view(self):
         """(rows uint8 [n, row_bytes], scale fp32 [n] | None, util fp32 [n]) as views of the arena."""

@@ -243,6 +243,7 @@ struct ic_index {
     int32_t *gcount;       // [q_chunk]
     int32_t *redo;         // [q_chunk/64 + 1]
     uint32_t *over;        // [0]: tiles left to the second launch of the tiled scan; from [2] on: the (tile, block) pairs
+    int last_nblk64 = 0;   // blocks of 64 queries of the last batch that took the tiled scan
     int gemm_list_cap_override;  // tests: shrink the candidate lists to force the overflow path
     bool consts_ready;  // written by the first search (creation launches nothing)
     bool timing;
@@ -379,6 +380,23 @@ ic_status ic_index_scan_time_ms(ic_index *index, float *ms, int64_t *launches) {
     }
     *ms = total;
     if (launches) *launches = (int64_t)(index->events_used / 2);
+    return IC_OK;
+}
+
+ic_status ic_index_tiled_scan_counts(ic_index *index, int64_t *tiles_again, int64_t *blocks_redone) {
+    if (!index) return IC_ERR_INVALID_ARG;
+    if (tiles_again) *tiles_again = 0;
+    if (blocks_redone) *blocks_redone = 0;
+    if (!index->over || index->last_nblk64 == 0) return IC_OK;
+    if (hipStreamSynchronize(index->stream) != hipSuccess) return IC_ERR_DEVICE;
+    uint32_t listed = 0;
+    std::vector<int32_t> flags((size_t)index->last_nblk64);
+    if (hipMemcpy(&listed, index->over, sizeof(listed), hipMemcpyDeviceToHost) != hipSuccess) return IC_ERR_DEVICE;
+    if (hipMemcpy(flags.data(), index->redo, flags.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return IC_ERR_DEVICE;
+    if (tiles_again) *tiles_again = (int64_t)listed;
+    if (blocks_redone)
+        for (int32_t f : flags) *blocks_redone += f != 0;
     return IC_OK;
 }
 
@@ -834,6 +852,7 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             const int nblk64 = (qc + 63) / 64;
             hipLaunchKernelGGL(ic::gemm_reset, dim3((qc + 255) / 256), dim3(256), 0, st, index->gcount, qc,
                                index->redo, nblk64, index->over);
+            index->last_nblk64 = nblk64;
             g.thr_init = index->thr_init;
             g.glist = index->glist;
             g.gcap = gcap;

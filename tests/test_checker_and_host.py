@@ -148,6 +148,12 @@ def test_status_codes_without_a_gpu():
     assert L.ic_index_set_domains(h, None, None, 0) == 0
     assert L.ic_search_domains(h, fake, 4, 4, 0.0, None, None, fake, fake) == 1   # no query domains
     assert L.ic_search_domains(h, None, 0, 4, 0.0, None, None, None, None) == 0   # Q == 0: no-op
+    again, redone = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    assert L.ic_index_tiled_scan_counts(None, ctypes.byref(again), ctypes.byref(redone)) == 1
+    # no large batch has run: zeros, and no device is touched
+    assert L.ic_index_tiled_scan_counts(h, ctypes.byref(again), ctypes.byref(redone)) == 0
+    assert again.value == 0 and redone.value == 0
+    assert L.ic_index_tiled_scan_counts(h, None, None) == 0
     left = ctypes.c_int64(-7)
     assert L.ic_index_compact(None, fake, None) == 1 and L.ic_index_compact(h, None, None) == 1
     assert L.ic_index_compact(h, fake, ctypes.byref(left)) == 0 and left.value == 0

@@ -25,7 +25,7 @@ def pkg():
     return p
 
 
-def _run(pkg, cfg, max_k=None, list_cap=None):
+def _run(pkg, cfg, max_k=None, list_cap=None, counts=None):
     wl = workloads.Workload(cfg, "cpu")
     E, U, M = wl.rows(0, cfg.N)
     Qm = wl.queries()
@@ -39,6 +39,8 @@ def _run(pkg, cfg, max_k=None, list_cap=None):
     ix.append(E.to(DEV), None if U is None else U.to(DEV))
     s, i = ix.search(Qm.to(DEV), cfg.k, cfg.lam, None if M is None else M.to(DEV))
     torch.cuda.synchronize()
+    if counts is not None:
+        counts.append(ix.tiled_scan_counts())
     ix.close()
     np_ = lambda t: None if t is None else t.numpy()
     return s.cpu().numpy(), i.cpu().numpy(), np_(E), np_(U), np_(M), Qm.numpy()
@@ -83,8 +85,10 @@ def test_large_batch_list_overflow_is_redone_exactly(pkg, oracle):
     """Candidate lists shrunk to 8 keys: every block overflows and is redone by the streaming scan."""
     _say("tiled scan, forced list overflow")
     cfg = workloads.Config("G", N=270000, d=128, clusters=64, Q=200, k=16, store="bf16", zipf=1.1, seed=8100)
-    a = _run(pkg, cfg)
-    b = _run(pkg, cfg, list_cap=8)
+    counts = []
+    a = _run(pkg, cfg, counts=counts)
+    b = _run(pkg, cfg, list_cap=8, counts=counts)
+    assert counts[0] == (0, 0) and counts[1][1] == 4   # all four blocks of 64 queries
     # the two kernels add the products in different orders: scores agree to rounding, rows may
     # swap only between scores that close
     assert np.allclose(a[0], b[0], atol=2e-6) and (a[1] == b[1]).mean() > 0.995
@@ -112,6 +116,9 @@ def test_large_batch_on_a_store_sorted_by_cluster(pkg, oracle, store):
     torch.cuda.synchronize()
     parity.check_batch(store, s.cpu().numpy(), i.cpu().numpy(), E.numpy(), U.numpy(), None, Qm.numpy(), cfg.k,
                        cfg.lam, "sorted by cluster", queries=range(0, cfg.Q, 7))
+    again, redone = ix.tiled_scan_counts()
+    print(f"   tiles done again {again}, blocks redone {redone}", flush=True)
+    assert redone == 0
     for _ in range(3):
         s2, i2 = ix.search(Qm.to(DEV), cfg.k, cfg.lam)
         torch.cuda.synchronize()
@@ -119,29 +126,59 @@ def test_large_batch_on_a_store_sorted_by_cluster(pkg, oracle, store):
     ix.close()
 
 
-@pytest.mark.parametrize("seed", [9400, 9402, 9403, 9405])
-def test_large_batch_is_repeatable_when_rows_suit_many_queries(pkg, oracle, seed):
+CLUMPED = [
+    # store, seed, with sharing domains
+    ("bf16", 9400, False), ("bf16", 9402, False), ("bf16", 9403, True), ("fp8", 9405, False), ("fp8", 9406, True),
+]
+
+
+@pytest.mark.parametrize("case", CLUMPED, ids=lambda c: "-".join(str(x) for x in c))
+def test_large_batch_is_repeatable_when_rows_suit_many_queries(pkg, oracle, case):
     """Few, large clusters and a utility bias: a row with a high utility near a centroid is a hit for
     most queries of that cluster at once, so some tiles list more blocks than their list holds.  Such
     tiles are done again, score by score, by the second launch of the same kernel: the result is
-    exact and bit for bit the same on every call."""
-    _say(f"tiled scan, clumped hits, seed {seed}")
-    cfg = workloads.Config("T", N=280000, d=128, clusters=32, Q=200, k=16, store="bf16", zipf=1.1, lam=0.2,
+    exact and bit for bit the same on every call, and no block goes to the streaming scan."""
+    store, seed, with_domains = case
+    _say(f"tiled scan, clumped hits {case}")
+    cfg = workloads.Config("T", N=280000, d=128, clusters=32, Q=200, k=16, store=store, zipf=1.1, lam=0.2,
                            util="beta25", p_valid=0.95, seed=seed)
     wl = workloads.Workload(cfg, "cpu")
     E, U, M = wl.rows(0, cfg.N)
     Qm = wl.queries()
-    ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, cfg.Q, cfg.k, DEV)
+    sid = pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3
+    ix = pkg.Index(cfg.d, cfg.N, sid, cfg.Q, cfg.k, DEV)
     ix.append(E.to(DEV), U.to(DEV))
     qd, md = Qm.to(DEV), M.to(DEV)
-    s, i = ix.search(qd, cfg.k, cfg.lam, md)
+    vis = M.numpy()
+    if with_domains:
+        # a third of the rows private to domain 1; every query belongs to domain 1 or 2
+        rng = np.random.default_rng(seed)
+        dom = (rng.random(cfg.N) < 0.33).astype(np.int32)
+        qdom = rng.integers(1, 3, cfg.Q).astype(np.int32)
+        ix.set_domains(torch.arange(cfg.N, device=DEV), torch.from_numpy(dom).to(DEV))
+        run = lambda: ix.search_domains(qd, cfg.k, torch.from_numpy(qdom).to(DEV), cfg.lam, md)
+    else:
+        run = lambda: ix.search(qd, cfg.k, cfg.lam, md)
+    s, i = run()
     torch.cuda.synchronize()
+    again, redone = ix.tiled_scan_counts()
+    print(f"   tiles done again {again}, blocks redone {redone}", flush=True)
+    assert again > 0 and redone == 0
     for _ in range(4):
-        s2, i2 = ix.search(qd, cfg.k, cfg.lam, md)
+        s2, i2 = run()
         torch.cuda.synchronize()
         assert torch.equal(i, i2) and torch.equal(s, s2)
-    parity.check_batch("bf16", s.cpu().numpy(), i.cpu().numpy(), E.numpy(), U.numpy(), M.numpy(), Qm.numpy(), cfg.k,
-                       cfg.lam, f"clumped hits {seed}", queries=range(0, cfg.Q, 9))
+        assert ix.tiled_scan_counts() == (again, redone)
+    sn, inn = s.cpu().numpy(), i.cpu().numpy()
+    if with_domains:
+        for D in (1, 2):
+            qs = np.flatnonzero(qdom == D)[::7].tolist()
+            v = (vis.astype(bool) & ((dom == 0) | (dom == D))).astype(np.uint8)
+            parity.check_batch(store, sn, inn, E.numpy(), U.numpy(), v, Qm.numpy(), cfg.k, cfg.lam,
+                               f"clumped hits {case} domain {D}", queries=qs)
+    else:
+        parity.check_batch(store, sn, inn, E.numpy(), U.numpy(), vis, Qm.numpy(), cfg.k, cfg.lam,
+                           f"clumped hits {case}", queries=range(0, cfg.Q, 9))
     ix.close()
 
 
