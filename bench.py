@@ -206,6 +206,7 @@ def main() -> int:
             "scan_TFLOPs": flop / (scan * 1e-3) / 1e12,
             "mfma_frac": flop / (scan * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall, "step_ms": spread,
+            "tiles_again_blocks_redone": list(ix.tiled_scan_counts()),
         }
         del qd, out_s, out_i
     say("Q=4096 on the headline store done")
@@ -240,7 +241,7 @@ def main() -> int:
                         f"lambda={c4.lam}, {1.0 - c4.p_valid:.0%} masked rows",
             "queries_per_s": c4.Q / (ms * 1e-3), "ms_per_step": ms, "steps": lsteps, "warmup": lwarm,
             "scan_kernel_ms": scan, "step_TFLOPs": flop / (ms * 1e-3) / 1e12, "wall_ms_per_step": wall,
-            "step_ms": spread,
+            "step_ms": spread, "tiles_again_blocks_redone": list(ix4.tiled_scan_counts()),
         }
         ach = flop / (scan * 1e-3) / 1e12
         roof_mfma = {
@@ -385,6 +386,7 @@ def main() -> int:
             rec = {"queries_per_s": Q / (ms * 1e-3), "ms_per_step": ms, "steps": st, "scan_kernel_ms": scan,
                    "step_ms": spread}
             if Q == LARGE_Q:
+                rec["tiles_again_blocks_redone"] = list(ix5.tiled_scan_counts())
                 flop = 2.0 * Q * c5.N * c5.d
                 rec["scan_TFLOPs"] = flop / (scan * 1e-3) / 1e12
                 rec["mfma_frac"] = rec["scan_TFLOPs"] / MFMA_FP8_PEAK_TFLOPS

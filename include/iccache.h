@@ -21,7 +21,7 @@
  *     host-side handle.  It never allocates or frees device memory.
  *   - All work is enqueued on the index's stream and is asynchronous; calls on
  *     one index are ordered.  No call synchronises the host except
- *     ic_index_scan_time_ms.
+ *     ic_index_scan_time_ms and ic_index_tiled_scan_counts.
  *   - Example ids are append order: 0-based, dense, stable (until ic_index_compact
  *     renumbers the surviving rows).
  *   - Errors are returned as ic_status; nothing throws or aborts.  On error the
