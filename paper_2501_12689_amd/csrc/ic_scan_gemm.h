@@ -52,7 +52,6 @@
 namespace ic {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 constexpr int kGemmTile = 256;        // rows and queries per output tile
 constexpr int kGemmStageBytes = 128;  // rows are padded to a multiple of this
