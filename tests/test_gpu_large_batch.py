@@ -127,8 +127,12 @@ def test_large_batch_on_a_store_sorted_by_cluster(pkg, oracle, store):
 
 
 CLUMPED = [
-    # store, seed, with sharing domains
-    ("bf16", 9400, False), ("bf16", 9402, False), ("bf16", 9403, True), ("fp8", 9405, False), ("fp8", 9406, True),
+    # store, seed, with sharing domains, Q, lambda
+    ("bf16", 9400, False, 200, 0.2), ("bf16", 9402, False, 200, 0.2), ("bf16", 9403, True, 200, 0.2),
+    ("fp8", 9405, False, 200, 0.2), ("fp8", 9406, True, 200, 0.2),
+    # one block of at most 128 queries (half of the wavefronts only copy); Q < 0: -Q queries that are
+    # all (nearly) the same request, so that every hit is a hit for all of them
+    ("bf16", 9410, False, -100, 0.2), ("fp8", 9411, False, -128, 0.0),
 ]
 
 
@@ -138,13 +142,16 @@ def test_large_batch_is_repeatable_when_rows_suit_many_queries(pkg, oracle, case
     most queries of that cluster at once, so some tiles list more blocks than their list holds.  Such
     tiles are done again, score by score, by the second launch of the same kernel: the result is
     exact and bit for bit the same on every call, and no block goes to the streaming scan."""
-    store, seed, with_domains = case
+    store, seed, with_domains, Q, lam = case
     _say(f"tiled scan, clumped hits {case}")
-    cfg = workloads.Config("T", N=280000, d=128, clusters=32, Q=200, k=16, store=store, zipf=1.1, lam=0.2,
+    cfg = workloads.Config("T", N=280000, d=128, clusters=32, Q=abs(Q), k=16, store=store, zipf=1.1, lam=lam,
                            util="beta25", p_valid=0.95, seed=seed)
     wl = workloads.Workload(cfg, "cpu")
     E, U, M = wl.rows(0, cfg.N)
     Qm = wl.queries()
+    if Q < 0:
+        g = torch.Generator().manual_seed(seed)
+        Qm = (Qm[:1] + 0.002 * torch.randn(Qm.shape, generator=g)).contiguous()
     sid = pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3
     ix = pkg.Index(cfg.d, cfg.N, sid, cfg.Q, cfg.k, DEV)
     ix.append(E.to(DEV), U.to(DEV))
