@@ -38,7 +38,7 @@ constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on que
 constexpr int kGemmMinQueries = 65;         // batches from here on use the MFMA-tiled scan (one tile is 256 queries wide, but from
                                             // 65 queries on it already beats two passes of the streaming scan: 4.1 vs 4.7 ms at d=768)
 constexpr int kGemmListSeg = ic::kMergeKeys;  // candidate lists are merged in segments of this many keys
-constexpr uint32_t kGemmOverCap = 4096;       // tiles of one tiled scan that may be left to its second launch
+constexpr uint32_t kGemmOverCap = 65536;      // tiles of one tiled scan that may be left to its second launch
 constexpr int kGemmListMax = 8 * kGemmListSeg;
 constexpr size_t kL2Share = 4u << 20;       // query-block bytes of a group of XCDs (measured: 4 MB beats 2 MB and 8 MB by about 3 %)
 
