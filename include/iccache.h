@@ -271,7 +271,8 @@ ic_status ic_index_set_timing(ic_index *index, int enable);
 ic_status ic_index_scan_time_ms(ic_index *index, float *ms, int64_t *launches);
 
 /*
- * Diagnostics of the last batch that took the tiled scan (large batches): how
+ * Diagnostics of the last batch that took the tiled scan (large batches; of its
+ * last chunk of max_queries queries if the batch was larger than that): how
  * many (row tile, query block) pairs had more hits than the tile's on-chip list
  * holds and were computed a second time, and how many blocks of 64 queries
  * overflowed their candidate list in device memory and were redone by the
