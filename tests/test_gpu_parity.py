@@ -166,6 +166,12 @@ CASES = [
     ("bf16", 300000, 128, 64, 24, 32, 0.0, "none", 1.0),
     ("bf16", 280001, 64, 16, 64, 64, 0.15, "uniform", 0.9),
     ("fp8", 300000, 128, 64, 40, 100, 0.0, "none", 1.0),
+    # fp8 with 49-64 queries: 2, 8 and 6 chunks of 64 bytes per wavefront go through the 128-wide
+    # MFMA in pairs, 5 chunks through the 32-wide one
+    ("fp8", 9000, 512, 16, 50, 24, 0.1, "uniform", 0.9),
+    ("fp8", 7000, 2048, 16, 64, 40, 0.0, "none", 1.0),
+    ("fp8", 6000, 1536, 8, 57, 8, 0.2, "beta25", 1.0),
+    ("fp8", 6000, 1280, 8, 64, 16, 0.0, "none", 0.9),
 ]
 
 
