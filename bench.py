@@ -71,6 +71,34 @@ def time_search(ix, torch, qd, k, lam, mask, out_s, out_i, warmup, steps):
     return ev[0].elapsed_time(ev[steps]) / steps, scan_ms / max(launches, 1), wall_ms / steps, spread
 
 
+def graph_replay_ms(pkg, torch, ix, qd, k, lam, mask, out_s, out_i, steps):
+    """The same search captured once into a HIP graph on a side stream and replayed `steps` times:
+    what a launch-bound small cache gains when the caller takes the launches off the host."""
+    L = pkg.load_library()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    L.ic_index_set_stream(ix.handle, side.cuda_stream)
+    with torch.cuda.stream(side):
+        ix.search(qd, k, lam, mask, out_s, out_i)    # one-time kernel attributes are set outside the capture
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ix.search(qd, k, lam, mask, out_s, out_i)
+    torch.cuda.synchronize()
+    L.ic_index_set_stream(ix.handle, torch.cuda.current_stream().cuda_stream)
+    for _ in range(5):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    del graph
+    return e0.elapsed_time(e1) / steps
+
+
 def say(msg: str) -> None:
     """Progress line on stderr (stdout carries only the JSON line)."""
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -121,6 +149,8 @@ def main() -> int:
     ap.add_argument("--no-fp8", action="store_true", help="skip the fp8 (N = 20M) legs")
     ap.add_argument("--no-cluster-pruning", action="store_true",
                     help="skip the cluster-pruning leg (tens of thousands of small launches while training)")
+    ap.add_argument("--no-graph-replay", action="store_true",
+                    help="skip the HIP-graph replay timing of the small configurations")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, so that a counter run over this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -308,6 +338,9 @@ def main() -> int:
                 "step_hbm_frac": cs.N * rb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "step_mfma_frac": 2.0 * cs.Q * cs.N * cs.d / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             }
+            if not args.no_graph_replay:
+                gms = graph_replay_ms(pkg, torch, ixs, qd, cs.k, cs.lam, mask_s, out_s, out_i, 50)
+                small_cfgs[name]["graph_replay"] = {"ms_per_step": gms, "queries_per_s": cs.Q / (gms * 1e-3)}
             if name == "C2" and not args.no_cluster_pruning:
                 # the same pruning on a store whose clusters are equally likely (no dominant blob);
                 # evicted rows are in no list, so the mask's rows are invalidated first
