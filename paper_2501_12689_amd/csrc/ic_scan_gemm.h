@@ -111,6 +111,12 @@ template <int ET, bool PILOT, bool DOM = false, bool ROWMAX = false, bool AGAIN 
 __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     static_assert(!ROWMAX || (!PILOT && !DOM), "row maxima take neither thresholds nor domains");
     static_assert(!AGAIN || (!PILOT && !ROWMAX), "only the selection launch leaves tiles to be done again");
+    // bf16 launches that score (selection and its pilot, which must round alike: the pilot's threshold
+    // is a score the selection has to reach again) start every accumulator at its row's bias instead
+    // of at zero, so the score is what the MFMAs leave behind and the epilogue adds nothing (128
+    // additions per lane and tile less, at a time when the matrix pipe is idle).  The bias of a tile is
+    // fetched during the tile before it.  fp8 scores need the two scales first and keep the addition.
+    constexpr bool kBiasInit = ET == 0 && !ROWMAX;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
     constexpr int kSlot = 2 * kGemmTile * kGemmHalfBytes;  // 32 KB: 256 rows then 256 queries, 64 B each
@@ -282,6 +288,25 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     const bool late = w >= 4;
     // fill the ring: the first kGemmSlots steps of this workgroup's work (the late wavefronts
     // request their share of the last one during the first step)
+    // bias of rows 4 * tid .. 4 * tid + 3 of the tile that starts at (pilot: has the index) r0
+    auto bias_of = [&](int64_t r0) {
+        f32x4 b;
+        if (PILOT) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t sampled = (int64_t)(tid * 4 + e) * a.ntiles + r0;
+                b[e] = sampled < a.n_sampled ? a.bias[sampled * a.row_stride] : -INFINITY;
+            }
+        } else {
+            b = *reinterpret_cast<const f32x4 *>(a.bias + r0 + tid * 4);
+        }
+        return b;
+    };
+    if (kBiasInit && tid < 64) {   // bias of this workgroup's first tile; the barrier below publishes it
+        Tile first;
+        locate(tw.ql, tw.rl, first);
+        *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_of(first.row0);
+    }
     cursor_tile();
 #pragma unroll
     for (int sl = 0; sl < kGemmSlots; ++sl) {
@@ -309,13 +334,35 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         const int qb = cur.qb;
         const int64_t row0 = cur.row0;
 
+        // bf16 selection launches: the first MFMA of every accumulator tile takes the bias of the
+        // tile's rows as its addend (accumulator v of tile (i, j) belongs to row
+        // wm*64 + i*32 + 8*(v/4) + 4*h + v%4, whatever j); everything else starts from zero
         f32x16 acc[2][4];
+        f32x16 bvec[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int u = 0; u < 4; ++u) {
+                f32x4 b = {0.f, 0.f, 0.f, 0.f};
+                if (kBiasInit) b = *reinterpret_cast<const f32x4 *>(bias_t + wm * 64 + i * 32 + 8 * u + 4 * h);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+                for (int e = 0; e < 4; ++e) bvec[i][4 * u + e] = b[e];
+            }
+        if (ET == 1 || kDead) {   // the fp8 loop has no first step of its own; idle wavefronts issue no MFMA at all
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = bvec[i];
+        }
+        // the tile after this one (kBiasInit: its bias is fetched in this tile's last step)
+        int64_t row0_next = row0;
+        if (kBiasInit && tw.job + step < work) {
+            Walk nx = tw;
+            walk_next(nx);
+            Tile nt;
+            locate(nx.ql, nx.rl, nt);
+            row0_next = nt.row0;
+        }
 
         // What the previous tile parked is flushed during this tile: slots are claimed (one atomic
         // per candidate) in the tile's last step and the keys are written after it.
@@ -328,18 +375,17 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 
         // bias, scale and domain of rows 4 * tid .. 4 * tid + 3 of the tile (threads 0-63)
         auto row_terms = [&]() {
+            bias_r = bias_of(kBiasInit ? row0_next : row0);
             if (PILOT) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int64_t sampled = (int64_t)(tid * 4 + e) * a.ntiles + row0;
                     const bool in = sampled < a.n_sampled;
                     const int64_t at = in ? sampled * a.row_stride : 0;   // the sampled row's place in the store
-                    bias_r[e] = in ? a.bias[at] : -INFINITY;
                     if (ET == 1) scale_r[e] = in ? a.row_scale[at] : 1.0f;
                     if (DOM) dom_r[e] = in ? a.row_dom[at] : 0;
                 }
             } else {
-                bias_r = *reinterpret_cast<const f32x4 *>(a.bias + row0 + tid * 4);
                 if (ET == 1) scale_r = *reinterpret_cast<const f32x4 *>(a.row_scale + row0 + tid * 4);
                 if (DOM) dom_r = *reinterpret_cast<const i32x4 *>(a.row_dom + row0 + tid * 4);
             }
@@ -354,14 +400,16 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) xb[j] = *reinterpret_cast<const i32x4 *>(sb + j * 32 * kGemmHalfBytes);
         };
-        auto mfma8 = [&](const i32x4 *xa, const i32x4 *xb) {
+        auto mfma8 = [&](const i32x4 *xa, const i32x4 *xb, auto first_c) {
+            constexpr bool kFirst = decltype(first_c)::value;   // the tile's first MFMAs: addend = bias (or zero)
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     if (ET == 0) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, xa[i]), __builtin_bit_cast(bf16x8, xb[j]), acc[i][j], 0, 0, 0);
+                            __builtin_bit_cast(bf16x8, xa[i]), __builtin_bit_cast(bf16x8, xb[j]),
+                            kFirst ? bvec[i] : acc[i][j], 0, 0, 0);
                     } else {
                         const i64x2 x = __builtin_bit_cast(i64x2, xa[i]);
                         const i64x2 y = __builtin_bit_cast(i64x2, xb[j]);
@@ -381,12 +429,12 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         //                step's first operands are read, MFMAs on the second operands
         // Nothing waits for a load younger than three steps, and LDS reads are always one MFMA
         // step ahead of their use.
-        auto half = [&](auto last_c) {
+        auto half = [&](auto last_c, auto first_c) {
             constexpr bool kLast = decltype(last_c)::value;
             if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1));  // the slot freed by the previous barrier
             if (!kDead) {
                 read_frags(hslot, 1, fa[1], fb[1]);
-                mfma8(fa[0], fb[0]);
+                mfma8(fa[0], fb[0], first_c);
 #pragma unroll
                 for (int g = 0; g < 6; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);  // MFMA
@@ -422,7 +470,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             const int nslot = (hslot + 1) & (kGemmSlots - 1);
             if (!kDead) {
                 if (!kLast) read_frags(nslot, 0, fa[0], fb[0]);
-                mfma8(fa[1], fb[1]);
+                mfma8(fa[1], fb[1], std::false_type{});
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     __builtin_amdgcn_sched_group_barrier(0x008, kPer, 0);
@@ -524,8 +572,9 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         };
         if constexpr (ET == 0) {
             if (!kDead) read_frags(hslot, 0, fa[0], fb[0]);  // the step landed before the barrier of the step before it
-            for (int hs = 0; hs + 1 < nhs; ++hs) half(std::false_type{});
-            half(std::true_type{});
+            half(std::false_type{}, std::true_type{});   // the number of steps is at least 2
+            for (int hs = 1; hs + 1 < nhs; ++hs) half(std::false_type{}, std::false_type{});
+            half(std::true_type{}, std::false_type{});
         } else {
             if (!kDead) read_frags8(hslot, ga[0], gb[0]);
             for (int hs = 0; hs + 2 < nhs; hs += 2) {  // the number of steps is even
@@ -602,7 +651,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int rr = wm * 64 + i * 32 + 8 * u + 4 * h;
-                    bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
+                    if (!kBiasInit) bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
                     if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
                     if (DOM) ds[u] = *reinterpret_cast<const i32x4 *>(dom_t + rr);
                 }
@@ -611,7 +660,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
-                                            : acc[i][j][v] + bs[v >> 2][v & 3];
+                                            : acc[i][j][v];   // bf16: the bias is in it from the start
                         if (DOM && ds[v >> 2][v & 3] != 0 && ds[v >> 2][v & 3] != qd[j]) x = -INFINITY;
                         best[j] = fmaxf(best[j], x);
                     }
@@ -630,7 +679,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         }
         if (fl_pos >= 0) append_global(park_q[tid], park_key[tid], fl_pos);
         if (tid < 64) {  // every wavefront is past the previous tile's epilogue (it has met this tile's barriers)
-            *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
+            *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;   // kBiasInit: the next tile's, read at its start
             if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
             if (DOM) *reinterpret_cast<i32x4 *>(dom_t + tid * 4) = dom_r;
         }
@@ -641,7 +690,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         }
         lds_barrier();
 
-        // ---- epilogue: score = dot * scales + bias, compare with the query's threshold
+        // ---- epilogue: score = dot * scales + bias (bf16: the accumulator as it is), compare with the query's threshold
         // accumulator v of tile (i, j) is row wm*64 + i*32 + 8*(v/4) + 4*h + v%4, query column wn*128 + j*32 + r32
         float thr_s[4];
 #pragma unroll
@@ -689,7 +738,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int rr = wm * 64 + i * 32 + 8 * u + 4 * h;
-                    bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
+                    if (!kBiasInit) bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
                     if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
                 }
 #pragma unroll
@@ -701,7 +750,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
-                                                  : acc[i][j][v] + bs[v >> 2][v & 3];
+                                                  : acc[i][j][v];   // bf16: the bias is in it from the start
                         const uint32_t row = (uint32_t)(row0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3));
                         const uint64_t key = make_key(x, row);
                         if (key > thr_k && x > -INFINITY) append_global((uint32_t)q, key, atomicAdd(a.gcount + q, 1));
@@ -718,7 +767,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int rr = wm * 64 + i * 32 + 8 * u + 4 * h;
-                bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
+                if (!kBiasInit) bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
                 if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
             }
 #pragma unroll
@@ -728,7 +777,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
-                                              : acc[i][j][v] + bs[v >> 2][v & 3];
+                                              : acc[i][j][v];   // bf16: the bias is in it from the start
                     sc[v >> 2][v & 3] = x;
                     best = fmaxf(best, x);
                 }
