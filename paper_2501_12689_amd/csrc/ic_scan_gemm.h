@@ -27,6 +27,9 @@
 //     owns a group of query blocks small enough to stay in its L2 and a class of row tiles, and
 //     walks query blocks fastest so that a row tile is used by consecutive tiles.  The load
 //     pipeline runs across tile boundaries: a cursor walks the same tile sequence 4 steps ahead.
+//   * Scores: bf16 accumulators start at their row's bias (lambda * utility, -inf for rows that may
+//     not be selected), passed as the addend of the tile's first MFMAs, so the finished accumulator
+//     is the score; fp8 multiplies by the row's and the query's scale and adds the bias afterwards.
 //   * Selection: thresholds come from the pilot (a score that at least k rows reach, per query).
 //     A tile's 65,536 scores are compared 16 at a time (max, then one compare); a lane whose 16
 //     scores reach the threshold copies them to an LDS list, the workgroup then tests those few
