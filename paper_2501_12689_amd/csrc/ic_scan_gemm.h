@@ -81,7 +81,7 @@ struct GemmArgs {
     uint32_t over_cap;
     int nqb;                 // query blocks of 256
     int64_t ntiles;          // row tiles of 256
-    uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over a sampled tile, id = tile)
+    uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over the slice so far, id = slice)
     int pilot_stride;
     int64_t row_stride;      // PILOT: the launch scores rows 0, row_stride, 2 * row_stride, ... only.  Row r of its
                              // t-th tile is row r * ntiles + t of that sample, so every tile, and with it every

@@ -760,7 +760,7 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
         }
         const int S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
-        // Threshold pilot: a pass over a strided sample of the tiles that keeps the best score
+        // Threshold pilot: a pass over a strided sample of the rows that keeps the best score
         // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
         // k rows, so the full scan may start from it.
         const int gemm_grid = std::max(8, index->compute_units / 8 * 8);
