@@ -21,7 +21,12 @@
  *     host-side handle.  It never allocates or frees device memory.
  *   - All work is enqueued on the index's stream and is asynchronous; calls on
  *     one index are ordered.  No call synchronises the host except
- *     ic_index_scan_time_ms and ic_index_tiled_scan_counts.
+ *     ic_index_scan_time_ms, ic_index_tiled_scan_counts, ic_index_compact and the
+ *     ic_ivf_* calls that say so.
+ *   - Calls on one index are NOT re-entrant: every search, the const ones included,
+ *     uses the index's query block and top-k workspace in the arena and a few host
+ *     fields of the handle (timing events, diagnostics).  The caller serialises the
+ *     calls on one index (one thread, or a lock); different indices are independent.
  *   - Example ids are append order: 0-based, dense, stable (until ic_index_compact
  *     renumbers the surviving rows).
  *   - Errors are returned as ic_status; nothing throws or aborts.  On error the
@@ -68,7 +73,9 @@ size_t ic_workspace_bytes(int32_t d, ic_dtype store, int64_t capacity_rows,
                           int64_t max_queries, int32_t max_k);
 
 /*
- * Create an empty index over caller-owned device memory.
+ * Create an empty index over caller-owned device memory: the cache of request-response
+ * examples that the Example Manager keeps (Sec. 3, system overview; Sec. 4.3), as the
+ * embedding store the selector searches.  Nothing is launched and the arena is not touched.
  *   out            receives the handle
  *   d              embedding dimension, 1 .. IC_MAX_DIM (2*IC_MAX_DIM for fp8)
  *   capacity_rows  most rows the store will ever hold (>= 1)
@@ -240,7 +247,11 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
 ic_status ic_ivf_view(const ic_ivf *ivf, const int32_t **assign_dev, const int64_t **offsets_dev,
                       const int32_t **perm_dev, const ic_index **centroids, const ic_index **sorted);
 
-/* Release the handle.  Device memory belongs to the caller and is not touched. */
+/*
+ * Release the handle (the counterpart of the client's stop(), Sec. 3).  Device memory belongs
+ * to the caller and is not touched; work already enqueued on the stream still needs the arena,
+ * so the caller drains the stream before freeing it.  Errors: INVALID_ARG (NULL).
+ */
 ic_status ic_index_destroy(ic_index *index);
 
 /* ---- helpers ---------------------------------------------------------- */
@@ -258,6 +269,16 @@ ic_status ic_index_set_stream(ic_index *index, void *stream);
 ic_status ic_index_store_view(const ic_index *index, const void **rows_dev,
                               int64_t *row_stride_bytes, const float **scale_dev,
                               const float **util_dev);
+
+/*
+ * Launch-shape overrides for tests and benchmark sweeps; results never depend on them.
+ *   slices     workgroups (slices of the store) per query block of the streaming scan,
+ *              1 .. 1024; 0 = as many as are resident at once (the default)
+ *   list_keys  keys of a query's candidate list in the tiled scan, at most the default
+ *              for max_k; 0 = the default.  Small values force the overflow paths.
+ * Applies to later searches.  Errors: INVALID_ARG.
+ */
+ic_status ic_index_set_tuning(ic_index *index, int32_t slices, int32_t list_keys);
 
 /*
  * Kernel timing for benchmarks.  While enabled, every ic_search brackets each

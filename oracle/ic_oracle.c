@@ -365,3 +365,11 @@ int ico_encode_e4m3(const float *x, int64_t count, uint8_t *codes)
     for (int64_t i = 0; i < count; ++i) codes[i] = f32_to_e4m3_rne_sat(x[i], tab);
     return 0;
 }
+
+/* raw bfloat16 encoder on values that are not normalised first (exposes f32_to_bf16_rne to its pins) */
+int ico_encode_bf16(const float *x, int64_t count, uint16_t *codes)
+{
+    if (count < 0 || !x || !codes) return 1;
+    for (int64_t i = 0; i < count; ++i) codes[i] = f32_to_bf16_rne(x[i]);
+    return 0;
+}

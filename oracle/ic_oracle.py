@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.ico_decode_e4m3.argtypes = [_u8p, ctypes.c_int64, _f32p]
         L.ico_encode_e4m3.restype = ctypes.c_int
         L.ico_encode_e4m3.argtypes = [_f32p, ctypes.c_int64, _u8p]
+        L.ico_encode_bf16.restype = ctypes.c_int
+        L.ico_encode_bf16.argtypes = [_f32p, ctypes.c_int64, _u16p]
         _lib = L
     return _lib
 
@@ -223,6 +225,14 @@ def encode_e4m3(x) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.float32)
     out = np.empty(x.shape, dtype=np.uint8)
     assert lib().ico_encode_e4m3(_ptr(x, _f32p), x.size, _ptr(out, _u8p)) == 0
+    return out
+
+
+def encode_bf16(x) -> np.ndarray:
+    """Raw bf16 codes of fp32 values as given (no normalisation): round to nearest, ties to even."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    assert lib().ico_encode_bf16(_ptr(x, _f32p), x.size, _ptr(out, _u16p)) == 0
     return out
 
 

@@ -22,7 +22,7 @@ IC_ARENA_ALIGN = 256
 
 EXPORTS = (
     "ic_workspace_bytes", "ic_index_create", "ic_index_append", "ic_search", "ic_index_destroy",
-    "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing",
+    "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing", "ic_index_set_tuning",
     "ic_index_scan_time_ms", "ic_index_tiled_scan_counts", "ic_status_string",
     "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
     "ic_search_threshold", "ic_self_search", "ic_index_set_domains", "ic_search_domains",
@@ -79,6 +79,8 @@ def load_library() -> ctypes.CDLL:
                                       ctypes.POINTER(vp), ctypes.POINTER(vp)]
     L.ic_index_set_timing.restype = ctypes.c_int
     L.ic_index_set_timing.argtypes = [vp, ctypes.c_int]
+    L.ic_index_set_tuning.restype = ctypes.c_int
+    L.ic_index_set_tuning.argtypes = [vp, i32, i32]
     L.ic_index_scan_time_ms.restype = ctypes.c_int
     L.ic_index_scan_time_ms.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(i64)]
     L.ic_index_tiled_scan_counts.restype = ctypes.c_int
@@ -282,6 +284,10 @@ class Index:
 
     def set_timing(self, enable: bool) -> None:
         _check(load_library().ic_index_set_timing(self.handle, int(enable)), "ic_index_set_timing")
+
+    def set_tuning(self, slices: int = 0, list_keys: int = 0) -> None:
+        """Launch-shape overrides for tests and sweeps (0 = default); results do not depend on them."""
+        _check(load_library().ic_index_set_tuning(self.handle, slices, list_keys), "ic_index_set_tuning")
 
     def scan_time_ms(self) -> Tuple[float, int]:
         """(summed scan-kernel time in ms, number of launches) since timing was switched on."""

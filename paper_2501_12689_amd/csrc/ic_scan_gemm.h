@@ -700,7 +700,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         for (int j = 0; j < 4; ++j) {
             const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
             thr_s[j] = thr_raw[j] > kKeyFloor ? key_score(thr_raw[j]) : -INFINITY;
-            if (q >= a.Q) thr_s[j] = INFINITY;  // padding query: nothing passes
+            if (q >= a.Q) thr_s[j] = __builtin_nanf("");  // padding query: no comparison with it holds, so nothing passes
         }
         // self-search: in the (at most two) row tiles that hold this query block's own rows, the
         // dot product of a query with itself is replaced by -inf before the scores are examined

@@ -5,7 +5,6 @@
 
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -121,6 +120,12 @@ __global__ void init_consts(uint32_t *c) {
     if (threadIdx.x < 16) c[threadIdx.x] = 0u;
 }
 
+// consts + 32: the largest |bias| of the search being prepared, as fp32 bits (make_bias raises it)
+__global__ void reset_bias_absmax(uint32_t *slot) {
+    if (threadIdx.x == 0) *slot = 0u;
+}
+constexpr int kConstsAbsmaxOffset = 32;
+
 using ScanFn = void (*)(dim3, hipStream_t, const ic::ScanArgs &);
 
 template <int ET, int QG, int CPW, bool PILOT, bool DOM = false>
@@ -211,6 +216,30 @@ void launch_gemm_again(int grid, hipStream_t st, const ic::GemmArgs &a) {
 
 }  // namespace
 
+// Per-search scratch: everything the kernels of one search write besides the result.  An index
+// keeps one inside the caller's arena; the entry point that allocates nothing builds one over
+// the library's static device array instead.
+struct Workspace {
+    uint8_t *qbuf = nullptr;        // prepared query block, [q_rows] rows in the store's format
+    float *qscale = nullptr;        // [q_rows]
+    uint64_t *regions = nullptr;    // candidate keys per (query, slice)
+    int32_t *counts = nullptr;
+    uint64_t *list_a = nullptr, *list_b = nullptr;  // ping-pong between merge levels
+    uint8_t *consts = nullptr;      // 64 bytes: 16 zero bytes (the bias of a search without one), then the
+                                    // largest |bias| of the current search as fp32 bits at byte 32
+    float *bias = nullptr;          // [cap_pad] per-row additive term of the current search
+    uint64_t *pilot_keys = nullptr; // [q_chunk][kPilotSlices]
+    uint64_t *thr_init = nullptr;   // [q_chunk]
+    uint64_t *glist = nullptr;      // [q_chunk][gemm_list_cap(max_k)], NULL when the tiled scan is not available
+    int32_t *gcount = nullptr;      // [q_chunk]
+    int32_t *redo = nullptr;        // [q_chunk/64 + 1]
+    uint32_t *over = nullptr;       // [0]: tiles left to the second launch of the tiled scan; from [2] on: the (tile, block) pairs
+    int q_chunk = 0;                // queries per pass over the store
+    int64_t region_slots = 0;       // bound on queries x slices of one streaming launch
+    bool *consts_ready = nullptr;   // host flag: consts has been written on this device
+    bool timed = true;              // scan launches may be bracketed with events (creates events on first use)
+};
+
 struct ic_index {
     int32_t d;
     ic_dtype store;
@@ -222,6 +251,7 @@ struct ic_index {
     hipStream_t stream;
     int slice_budget;  // 0 = derive from occupancy; otherwise forced (benchmark sweeps)
     int compute_units;
+    int device;        // the GPU that was current at creation
     uint8_t *rows;
     float *scale;
     float *util;
@@ -229,20 +259,7 @@ struct ic_index {
     int64_t *block_offsets;  // compaction scratch
     bool any_invalid;      // some row has been invalidated since the last compaction
     int32_t *domain;       // [cap_pad] sharing domain of every row; 0 = shared with every domain
-    uint8_t *qbuf;
-    float *qscale;
-    uint64_t *regions;
-    int32_t *counts;
-    uint64_t *list_a;
-    uint64_t *list_b;
-    uint8_t *consts;
-    float *bias;
-    uint64_t *pilot_keys;  // [q_chunk][kPilotSlices]
-    uint64_t *thr_init;    // [q_chunk]
-    uint64_t *glist;       // [q_chunk][gemm_list_cap(max_k)], NULL when max_queries < kGemmMinQueries
-    int32_t *gcount;       // [q_chunk]
-    int32_t *redo;         // [q_chunk/64 + 1]
-    uint32_t *over;        // [0]: tiles left to the second launch of the tiled scan; from [2] on: the (tile, block) pairs
+    Workspace ws;          // the search scratch inside the arena
     int last_nblk64 = 0;   // blocks of 64 queries of the last batch that took the tiled scan
     int gemm_list_cap_override;  // tests: shrink the candidate lists to force the overflow path
     bool consts_ready;  // written by the first search (creation launches nothing)
@@ -291,15 +308,12 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->n = 0;
     ix->stream = (hipStream_t)stream;
     ix->slice_budget = 0;
-    if (const char *e = std::getenv("IC_SLICE_BUDGET")) {  // benchmark sweeps only
-        int v = std::atoi(e);
-        if (v >= 1 && v <= kSliceBudgetMax) ix->slice_budget = v;
-    }
     ix->compute_units = kComputeUnitsDefault;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
         ix->compute_units = cus;
+    ix->device = dev;
     (void)hipGetLastError();
     uint8_t *base = (uint8_t *)arena_dev;
     ix->rows = base + L.off_rows;
@@ -309,26 +323,26 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->block_offsets = (int64_t *)(base + L.off_blocks);
     ix->any_invalid = false;
     ix->domain = (int32_t *)(base + L.off_domain);
-    ix->qbuf = base + L.off_qbuf;
-    ix->qscale = (float *)(base + L.off_qscale);
-    ix->regions = (uint64_t *)(base + L.off_regions);
-    ix->counts = (int32_t *)(base + L.off_counts);
-    ix->list_a = (uint64_t *)(base + L.off_list_a);
-    ix->list_b = (uint64_t *)(base + L.off_list_b);
-    ix->consts = base + L.off_consts;
-    ix->bias = (float *)(base + L.off_bias);
-    ix->pilot_keys = (uint64_t *)(base + L.off_pilot);
-    ix->thr_init = (uint64_t *)(base + L.off_thr);
+    Workspace &W = ix->ws;
+    W.qbuf = base + L.off_qbuf;
+    W.qscale = (float *)(base + L.off_qscale);
+    W.regions = (uint64_t *)(base + L.off_regions);
+    W.counts = (int32_t *)(base + L.off_counts);
+    W.list_a = (uint64_t *)(base + L.off_list_a);
+    W.list_b = (uint64_t *)(base + L.off_list_b);
+    W.consts = base + L.off_consts;
+    W.bias = (float *)(base + L.off_bias);
+    W.pilot_keys = (uint64_t *)(base + L.off_pilot);
+    W.thr_init = (uint64_t *)(base + L.off_thr);
     const bool gemm = L.q_chunk >= kGemmMinQueries;
-    ix->glist = gemm ? (uint64_t *)(base + L.off_glist) : nullptr;
-    ix->gcount = gemm ? (int32_t *)(base + L.off_gcount) : nullptr;
-    ix->redo = gemm ? (int32_t *)(base + L.off_redo) : nullptr;
-    ix->over = gemm ? (uint32_t *)(base + L.off_over) : nullptr;
+    W.glist = gemm ? (uint64_t *)(base + L.off_glist) : nullptr;
+    W.gcount = gemm ? (int32_t *)(base + L.off_gcount) : nullptr;
+    W.redo = gemm ? (int32_t *)(base + L.off_redo) : nullptr;
+    W.over = gemm ? (uint32_t *)(base + L.off_over) : nullptr;
+    W.q_chunk = L.q_chunk;
+    W.region_slots = kRegionSlots;
+    W.consts_ready = &ix->consts_ready;
     ix->gemm_list_cap_override = 0;
-    if (const char *e = std::getenv("IC_GEMM_LIST_CAP")) {  // tests only
-        int v = std::atoi(e);
-        if (v >= 1 && v <= gemm_list_cap(max_k)) ix->gemm_list_cap_override = v;
-    }
     ix->timing = false;
     ix->events_used = 0;
     ix->consts_ready = false;
@@ -348,6 +362,14 @@ int64_t ic_index_size(const ic_index *index) { return index ? index->n : -1; }
 ic_status ic_index_set_stream(ic_index *index, void *stream) {
     if (!index) return IC_ERR_INVALID_ARG;
     index->stream = (hipStream_t)stream;
+    return IC_OK;
+}
+
+ic_status ic_index_set_tuning(ic_index *index, int32_t slices, int32_t list_keys) {
+    if (!index || slices < 0 || slices > kSliceBudgetMax || list_keys < 0 || list_keys > gemm_list_cap(index->max_k))
+        return IC_ERR_INVALID_ARG;
+    index->slice_budget = slices;
+    index->gemm_list_cap_override = list_keys;
     return IC_OK;
 }
 
@@ -387,12 +409,12 @@ ic_status ic_index_tiled_scan_counts(ic_index *index, int64_t *tiles_again, int6
     if (!index) return IC_ERR_INVALID_ARG;
     if (tiles_again) *tiles_again = 0;
     if (blocks_redone) *blocks_redone = 0;
-    if (!index->over || index->last_nblk64 == 0) return IC_OK;
+    if (!index->ws.over || index->last_nblk64 == 0) return IC_OK;
     if (hipStreamSynchronize(index->stream) != hipSuccess) return IC_ERR_DEVICE;
     uint32_t listed = 0;
     std::vector<int32_t> flags((size_t)index->last_nblk64);
-    if (hipMemcpy(&listed, index->over, sizeof(listed), hipMemcpyDeviceToHost) != hipSuccess) return IC_ERR_DEVICE;
-    if (hipMemcpy(flags.data(), index->redo, flags.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    if (hipMemcpy(&listed, index->ws.over, sizeof(listed), hipMemcpyDeviceToHost) != hipSuccess) return IC_ERR_DEVICE;
+    if (hipMemcpy(flags.data(), index->ws.redo, flags.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
         return IC_ERR_DEVICE;
     if (tiles_again) *tiles_again = (int64_t)listed;
     if (blocks_redone)
@@ -474,7 +496,7 @@ ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_si
     hipLaunchKernelGGL(ic::scan_block_sums, dim3(1), dim3(256), 0, st, offs, nblocks);
     hipLaunchKernelGGL(ic::write_id_map, dim3((unsigned)nblocks), dim3(256), 0, st, index->valid, n, offs, id_map_dev);
     // rows, chunk by chunk through the candidate-region scratch (free between searches)
-    uint8_t *bounce = (uint8_t *)index->regions;
+    uint8_t *bounce = (uint8_t *)index->ws.regions;
     const size_t bounce_bytes = (size_t)kRegionSlots * (size_t)region_cap(index->max_k) * 8;
     const int64_t chunk = std::max<int64_t>(ic::kScanBlock,
                                             (int64_t)(bounce_bytes / (size_t)L.row_bytes) / ic::kScanBlock * ic::kScanBlock);
@@ -488,15 +510,15 @@ ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_si
     }
     // side arrays through the per-search bias scratch
     const unsigned g1 = (unsigned)((n + 255) / 256);
-    hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, index->util, id_map_dev, n, index->bias);
-    hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->bias, offs + nblocks, index->util);
+    hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, index->util, id_map_dev, n, index->ws.bias);
+    hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->ws.bias, offs + nblocks, index->util);
     if (index->scale) {
-        hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, index->scale, id_map_dev, n, index->bias);
-        hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->bias, offs + nblocks, index->scale);
+        hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, index->scale, id_map_dev, n, index->ws.bias);
+        hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->ws.bias, offs + nblocks, index->scale);
     }
     // the domains are moved as 32-bit words (the copies do no arithmetic)
-    hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, (const float *)index->domain, id_map_dev, n, index->bias);
-    hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->bias, offs + nblocks, (float *)index->domain);
+    hipLaunchKernelGGL(ic::scatter_f32, dim3(g1), dim3(256), 0, st, (const float *)index->domain, id_map_dev, n, index->ws.bias);
+    hipLaunchKernelGGL(ic::copy_f32_counted, dim3(g1), dim3(256), 0, st, index->ws.bias, offs + nblocks, (float *)index->domain);
     hipLaunchKernelGGL(ic::fill_bytes, dim3(g1), dim3(256), 0, st, index->valid, n, (uint8_t)1);
     int64_t total = 0;
     if (hipMemcpyAsync(&total, offs + nblocks, sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
@@ -519,10 +541,10 @@ struct FinalOpts {          // how the last merge level writes a query's row of 
                             // left out of its own result (the lists then hold k + 1 keys); -1: off
 };
 
-void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_scores, int64_t *out_ids,
+void run_merge(ic_index *index, const Workspace &W, ic::MergeArgs m, int qc, int k, float *out_scores, int64_t *out_ids,
                const int32_t *only_flagged, const FinalOpts &fo) {
     hipStream_t st = index->stream;
-    uint64_t *ping = index->list_a, *pong = index->list_b;
+    uint64_t *ping = W.list_a, *pong = W.list_b;
     m.k = k;
     m.kth_out = nullptr;
     m.out_scores = out_scores;
@@ -553,9 +575,10 @@ void run_merge(ic_index *index, ic::MergeArgs m, int qc, int k, float *out_score
 struct Timer {  // brackets the dominant kernel of a search with events when timing is on
     ic_index *index;
     bool on;
-    explicit Timer(ic_index *ix) : index(ix), on(false) {}
+    bool allowed;
+    Timer(ic_index *ix, bool may) : index(ix), on(false), allowed(may) {}
     bool start() {
-        on = index->timing && index->events_used + 2 <= kMaxTimedEvents;
+        on = allowed && index->timing && index->events_used + 2 <= kMaxTimedEvents;
         if (!on) return true;
         while (index->events.size() < index->events_used + 2) {
             hipEvent_t e;
@@ -584,8 +607,8 @@ struct SearchReq {                      // where the queries come from and how t
     int32_t *counts = nullptr;
     const int32_t *q_domain = nullptr;  // [Q] sharing domain of every query: rows of other domains are not returned
 };
-ic_status search_impl(ic_index *index, int64_t Q, int32_t k, float lambda, const uint8_t *mask_dev,
-                      float *out_scores_dev, int64_t *out_ids_dev, const SearchReq &req);
+ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k, float lambda,
+                      const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, const SearchReq &req);
 }
 
 ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
@@ -593,7 +616,7 @@ ic_status ic_search(const ic_index *cindex, const float *q_dev, int64_t Q, int32
     SearchReq r;
     r.q_dev = q_dev;
     if (Q > 0 && !q_dev) return IC_ERR_INVALID_ARG;
-    return search_impl(const_cast<ic_index *>(cindex), Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
+    return search_impl(const_cast<ic_index *>(cindex), cindex->ws, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 ic_status ic_self_search(const ic_index *cindex, int64_t first_row, int64_t count, int32_t k, float lambda,
@@ -604,7 +627,7 @@ ic_status ic_self_search(const ic_index *cindex, int64_t first_row, int64_t coun
     r.q_rows = cindex->rows + first_row * (int64_t)cindex->L.row_bytes;
     r.q_row_scale = cindex->scale ? cindex->scale + first_row : nullptr;
     r.self_first = first_row;
-    return search_impl(const_cast<ic_index *>(cindex), count, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
+    return search_impl(const_cast<ic_index *>(cindex), cindex->ws, count, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 ic_status ic_search_domains(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
@@ -614,7 +637,7 @@ ic_status ic_search_domains(const ic_index *cindex, const float *q_dev, int64_t 
     SearchReq r;
     r.q_dev = q_dev;
     r.q_domain = query_domain_dev;
-    return search_impl(const_cast<ic_index *>(cindex), Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
+    return search_impl(const_cast<ic_index *>(cindex), cindex->ws, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 ic_status ic_search_threshold(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
@@ -626,12 +649,12 @@ ic_status ic_search_threshold(const ic_index *cindex, const float *q_dev, int64_
     r.min_score = min_score;
     r.counts = out_counts_dev;
     if (Q > 0 && !q_dev) return IC_ERR_INVALID_ARG;
-    return search_impl(const_cast<ic_index *>(cindex), Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
+    return search_impl(const_cast<ic_index *>(cindex), cindex->ws, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
 }
 
 namespace {
-ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, const uint8_t *mask_dev,
-                      float *out_scores_dev, int64_t *out_ids_dev, const SearchReq &req) {
+ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_out, float lambda,
+                      const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev, const SearchReq &req) {
     const float *q_dev = req.q_dev;
     const float min_score = req.min_score;
     int32_t *out_counts_dev = req.counts;
@@ -655,31 +678,35 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
     // (measured on 100k-250k rows: 1.5 to 2 times faster than the streaming scan from 256 queries on,
     // about even at 128)
     auto gemm_for = [&](int64_t queries) {
-        return index->glist != nullptr && queries >= kGemmMinQueries &&
+        return W.glist != nullptr && queries >= kGemmMinQueries &&
                (ntiles >= kGemmMinTiles || (ntiles >= kGemmSmallTiles && queries > 128) ||
                 (ntiles >= kGemmTinyTiles && queries > 128 && k <= 16));
     };
 
-    if (!index->consts_ready) {
-        hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)index->consts);
-        index->consts_ready = true;
+    if (!*W.consts_ready) {
+        hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)W.consts);
+        *W.consts_ready = true;
     }
 
     // a4 (first half): per-row additive term, once per search.  The tiled scan always reads it
     // (it marks the padding rows of the last tile); the streaming scan only if it is not all zero.
-    const bool any_gemm = gemm_for(std::min<int64_t>(Q, L.q_chunk));
+    const bool any_gemm = gemm_for(std::min<int64_t>(Q, W.q_chunk));
     const bool use_bias = (lambda != 0.0f) || mask_dev != nullptr || any_gemm || index->any_invalid;
+    // The tiled scan hands thresholds to the streaming scan when a block is redone; the slack that
+    // covers their different rounding grows with the largest |bias|, which make_bias leaves here.
+    uint32_t *absmax = (any_gemm && lambda != 0.0f) ? (uint32_t *)(W.consts + kConstsAbsmaxOffset) : nullptr;
     if (use_bias && n > 0) {
         const int64_t n_pad = round_up(n, ic::kGemmTile);
         const int grid = (int)std::min<int64_t>((n_pad + 255) / 256, 4096);
+        if (absmax) hipLaunchKernelGGL(reset_bias_absmax, dim3(1), dim3(64), 0, st, absmax);
         hipLaunchKernelGGL(ic::make_bias, dim3(grid), dim3(256), 0, st,
                            (lambda != 0.0f) ? (const float *)index->util : (const float *)nullptr, mask_dev,
                            index->any_invalid ? (const uint8_t *)index->valid : (const uint8_t *)nullptr, n, n_pad,
-                           lambda, index->bias);
+                           lambda, W.bias, absmax);
     }
 
-    for (int64_t q0 = 0; q0 < Q; q0 += L.q_chunk) {
-        const int qc = (int)std::min<int64_t>(L.q_chunk, Q - q0);
+    for (int64_t q0 = 0; q0 < Q; q0 += W.q_chunk) {
+        const int qc = (int)std::min<int64_t>(W.q_chunk, Q - q0);
         const bool gemm = gemm_for(qc);
         const int qg_idx = gemm ? 2 : (qc <= 16 ? 0 : (qc <= 32 ? 1 : 2));
         const int qb_rows = 16 << qg_idx;
@@ -694,35 +721,39 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
         // a2: unit-normalise the queries and write them in the store's format; a self-search
         // takes the rows as they are stored (same format, already normalised)
         if (req.q_rows) {
-            if (hipMemcpyAsync(index->qbuf, req.q_rows + q0 * (int64_t)L.row_bytes, (size_t)qc * L.row_bytes,
+            if (hipMemcpyAsync(W.qbuf, req.q_rows + q0 * (int64_t)L.row_bytes, (size_t)qc * L.row_bytes,
                                hipMemcpyDeviceToDevice, st) != hipSuccess)
                 return IC_ERR_DEVICE;
-            if (et == 1 && hipMemcpyAsync(index->qscale, req.q_row_scale + q0, (size_t)qc * 4,
+            if (et == 1 && hipMemcpyAsync(W.qscale, req.q_row_scale + q0, (size_t)qc * 4,
                                           hipMemcpyDeviceToDevice, st) != hipSuccess)
                 return IC_ERR_DEVICE;
+            if (q_pad > qc)   // the padding queries of the last block: zero rows, like the ones quantize_rows writes
+                hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)(((int64_t)(q_pad - qc) * L.row_bytes + 255) / 256)),
+                                   dim3(256), 0, st, W.qbuf + (int64_t)qc * L.row_bytes,
+                                   (int64_t)(q_pad - qc) * L.row_bytes, (uint8_t)0);
         } else {
             const int grid = (q_pad + 3) / 4;
             const float *src = q_dev + q0 * (int64_t)index->d;
             if (et == 0)
                 hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
-                                   (int64_t)q_pad, index->d, L.row_bytes, index->qbuf, (float *)nullptr,
+                                   (int64_t)q_pad, index->d, L.row_bytes, W.qbuf, (float *)nullptr,
                                    (const float *)nullptr, (float *)nullptr);
             else
                 hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
-                                   (int64_t)q_pad, index->d, L.row_bytes, index->qbuf, index->qscale,
+                                   (int64_t)q_pad, index->d, L.row_bytes, W.qbuf, W.qscale,
                                    (const float *)nullptr, (float *)nullptr);
         }
 
         if (n == 0) {  // nothing to scan: the merge of zero segments writes the padding rows
             ic::MergeArgs m{};
-            m.src = index->regions;
+            m.src = W.regions;
             m.q_stride = 0;
             m.seg_stride = cap;
             m.seg_cap = cap;
-            m.seg_counts = index->counts;
+            m.seg_counts = W.counts;
             m.nseg = 0;
             m.segs_per_wg = 1;
-            run_merge(index, m, qc, k, out_s, out_i, nullptr, fo);
+            run_merge(index, W, m, qc, k, out_s, out_i, nullptr, fo);
             continue;
         }
 
@@ -732,16 +763,16 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
         a.n = n;
         a.row_bytes = L.row_bytes;
         a.row_scale = index->scale;
-        a.bias = use_bias ? index->bias : (const float *)index->consts;
+        a.bias = use_bias ? W.bias : (const float *)W.consts;
         a.bias_stride = use_bias ? 1 : 0;
-        a.qbuf = index->qbuf;
-        a.q_scale = index->qscale;
+        a.qbuf = W.qbuf;
+        a.q_scale = W.qscale;
         a.Q = qc;
         a.k = k;
         a.cap = cap;
-        a.regions = index->regions;
-        a.counts = index->counts;
-        a.pilot_out = index->pilot_keys;
+        a.regions = W.regions;
+        a.counts = W.counts;
+        a.pilot_out = W.pilot_keys;
         a.thr_init = nullptr;
         a.redo = nullptr;
         a.thr_slack = 0.0f;
@@ -759,6 +790,7 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             const int per_cu = (int)std::min<size_t>(2, std::max<size_t>(1, kLdsPerCu / lds));
             budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
         }
+        budget = (int)std::min<int64_t>(budget, W.region_slots / qb_rows);   // what the candidate regions hold
         const int S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
         // Threshold pilot: a pass over a strided sample of the rows that keeps the best score
         // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
@@ -770,9 +802,9 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             g.n = n;
             g.row_bytes = L.row_bytes;
             g.row_scale = index->scale;
-            g.bias = index->bias;
-            g.qbuf = index->qbuf;
-            g.q_scale = index->qscale;
+            g.bias = W.bias;
+            g.qbuf = W.qbuf;
+            g.q_scale = W.qscale;
             g.Q = qc;
             g.nqb = nqb_gemm;
             g.ntiles = (n + ic::kGemmTile - 1) / ic::kGemmTile;
@@ -799,24 +831,24 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             p.row_stride = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, by_hits), g.ntiles / std::max(k, 64)));
             p.n_sampled = (n + p.row_stride - 1) / p.row_stride;
             p.ntiles = (p.n_sampled + ic::kGemmTile - 1) / ic::kGemmTile;
-            p.pilot_out = index->pilot_keys;
+            p.pilot_out = W.pilot_keys;
             p.pilot_stride = kPilotSlices;
             const int64_t nkeys = (int64_t)qc * kPilotSlices;
             hipLaunchKernelGGL(ic::gemm_pilot_reset, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, st,
-                               index->pilot_keys, nkeys);
+                               W.pilot_keys, nkeys);
             if (et == 0) launch_gemm<0, true>(gemm_grid, st, p);
             else launch_gemm<1, true>(gemm_grid, st, p);
             ic::MergeArgs m{};
-            m.src = index->pilot_keys;
+            m.src = W.pilot_keys;
             m.q_stride = kPilotSlices;
             m.seg_stride = kPilotSlices;
             m.seg_cap = (int)std::min<int64_t>(kPilotSlices, p.ntiles);
             m.nseg = 1;
             m.segs_per_wg = 1;
             m.k = k;
-            m.kth_out = index->thr_init;
+            m.kth_out = W.thr_init;
             hipLaunchKernelGGL(ic::merge_lists, dim3(qc, 1), dim3(256), 0, st, m);
-            a.thr_init = index->thr_init;
+            a.thr_init = W.thr_init;
         } else if (pilot_ok && ((qc >= 8 && (int64_t)qc * k >= kPilotMinWork) || (qc >= 4 && (int64_t)qc * k >= 6 * kPilotMinWork) ||
                                 (qc >= kPilotMinQueries && ntiles >= kGemmMinTiles))) {
             // It pays when the selection is a visible part of the scan: several queries and a k that
@@ -832,34 +864,34 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             p.tile_mul = (int)std::min<int64_t>(std::min<int64_t>(128, ntiles / kPilotSlices), by_regions);
             scan_table[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
             ic::MergeArgs m{};
-            m.src = index->pilot_keys;
+            m.src = W.pilot_keys;
             m.q_stride = kPilotSlices;
             m.seg_stride = kPilotSlices;
             m.seg_cap = kPilotSlices;
             m.nseg = 1;
             m.segs_per_wg = 1;
             m.k = k;
-            m.kth_out = index->thr_init;
+            m.kth_out = W.thr_init;
             hipLaunchKernelGGL(ic::merge_lists, dim3(qc, 1), dim3(256), 0, st, m);
-            a.thr_init = index->thr_init;
+            a.thr_init = W.thr_init;
         }
 
         a.S = S;
-        Timer timer(index);
+        Timer timer(index, W.timed);
 
         if (gemm) {
             const int gcap = index->gemm_list_cap_override ? index->gemm_list_cap_override : gemm_list_cap(k);
             const int nblk64 = (qc + 63) / 64;
-            hipLaunchKernelGGL(ic::gemm_reset, dim3((qc + 255) / 256), dim3(256), 0, st, index->gcount, qc,
-                               index->redo, nblk64, index->over);
+            hipLaunchKernelGGL(ic::gemm_reset, dim3((qc + 255) / 256), dim3(256), 0, st, W.gcount, qc,
+                               W.redo, nblk64, W.over);
             index->last_nblk64 = nblk64;
-            g.thr_init = index->thr_init;
-            g.glist = index->glist;
+            g.thr_init = W.thr_init;
+            g.glist = W.glist;
             g.gcap = gcap;
-            g.gcount = index->gcount;
-            g.redo = index->redo;
-            g.over_n = index->over;
-            g.over_list = reinterpret_cast<uint2 *>(index->over + 2);
+            g.gcount = W.gcount;
+            g.redo = W.redo;
+            g.over_n = W.over;
+            g.over_list = reinterpret_cast<uint2 *>(W.over + 2);
             g.over_cap = kGemmOverCap;
             if (!timer.start()) return IC_ERR_DEVICE;
             if (et == 0) launch_gemm<0, false>(gemm_grid, st, g);
@@ -873,19 +905,20 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
             // blocks whose candidate lists overflowed are redone by the streaming scan; the
             // thresholds come from the other kernel, hence the slack (1e-4 bounds the difference
             // between two fp32 summation orders of a dot product of unit vectors)
-            a.redo = index->redo;
+            a.redo = W.redo;
             a.thr_slack = 1e-4f;
+            a.bias_absmax = (const float *)absmax;
             scan_table[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
 
             ic::MergeArgs m{};
-            m.src = index->glist;
+            m.src = W.glist;
             m.q_stride = gcap;
             m.seg_cap = std::min(gcap, kGemmListSeg);
             m.seg_stride = m.seg_cap;
-            m.total_counts = index->gcount;
+            m.total_counts = W.gcount;
             m.nseg = (gcap + m.seg_cap - 1) / m.seg_cap;
             m.segs_per_wg = 1;
-            run_merge(index, m, qc, k, out_s, out_i, nullptr, fo);
+            run_merge(index, W, m, qc, k, out_s, out_i, nullptr, fo);
         } else {
             if (!timer.start()) return IC_ERR_DEVICE;
             scan_table[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
@@ -895,17 +928,17 @@ ic_status search_impl(ic_index *index, int64_t Q, int32_t k_out, float lambda, c
         // a6: merge the S candidate regions of every query (after the tiled scan: only the
         // blocks that were redone)
         ic::MergeArgs m{};
-        m.src = index->regions;
+        m.src = W.regions;
         m.q_stride = (int64_t)S * cap;
         m.seg_stride = cap;
         m.seg_cap = cap;
-        m.seg_counts = index->counts;
+        m.seg_counts = W.counts;
         m.nseg = S;
         // after a pilot the regions hold a handful of keys each, so a workgroup takes as many as
         // it may (fewer, smaller lists for the next level; a rare full group is merged in rounds);
         // without one they may be full, and more workgroups with one round each are faster
         m.segs_per_wg = a.thr_init ? ic::kMergeMaxSegs : std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
-        run_merge(index, m, qc, k, out_s, out_i, gemm ? index->redo : nullptr, fo);
+        run_merge(index, W, m, qc, k, out_s, out_i, gemm ? W.redo : nullptr, fo);
     }
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     return IC_OK;
@@ -1179,7 +1212,7 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
     const int cap = region_cap_for(k, 0);
     const int64_t n = s->n;
     if (!s->consts_ready) {
-        hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)s->consts);
+        hipLaunchKernelGGL(init_consts, dim3(1), dim3(64), 0, st, (uint32_t *)s->ws.consts);
         s->consts_ready = true;
     }
     const bool use_bias = lambda != 0.0f && n > 0;
@@ -1187,7 +1220,7 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         const int64_t n_pad = round_up(n, ic::kGemmTile);
         hipLaunchKernelGGL(ic::make_bias, dim3((int)std::min<int64_t>((n_pad + 255) / 256, 4096)), dim3(256), 0, st,
                            (const float *)s->util, (const uint8_t *)nullptr, (const uint8_t *)nullptr, n, n_pad, lambda,
-                           s->bias);
+                           s->ws.bias, (uint32_t *)nullptr);
     }
     // slices per list: about 12 tiles of 16 rows each, at most 16 slices
     const int64_t avg_tiles = std::max<int64_t>(1, n / std::max<int64_t>(1, ivf->K) / 16);
@@ -1199,30 +1232,30 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         // the nprobe nearest centroids of every query
         SearchReq r;
         r.q_dev = q_dev + q0 * (int64_t)s->d;
-        ic_status rc = search_impl(c, qc, nprobe, 0.0f, nullptr, ivf->probe_scores, ivf->probe_ids, r);
+        ic_status rc = search_impl(c, c->ws, qc, nprobe, 0.0f, nullptr, ivf->probe_scores, ivf->probe_ids, r);
         if (rc != IC_OK) return rc;
         // the queries in the store's format, then one scan task per (query, list)
         const int grid = (qc + 3) / 4;
         if (et == 0)
             hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
-                               s->d, L.row_bytes, s->qbuf, (float *)nullptr, (const float *)nullptr, (float *)nullptr);
+                               s->d, L.row_bytes, s->ws.qbuf, (float *)nullptr, (const float *)nullptr, (float *)nullptr);
         else
             hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
-                               s->d, L.row_bytes, s->qbuf, s->qscale, (const float *)nullptr, (float *)nullptr);
+                               s->d, L.row_bytes, s->ws.qbuf, s->ws.qscale, (const float *)nullptr, (float *)nullptr);
         float *out_s = out_scores_dev + q0 * (int64_t)k;
         int64_t *out_i = out_ids_dev + q0 * (int64_t)k;
         const FinalOpts fo{-INFINITY, nullptr, -1};
         ic::MergeArgs m{};
-        m.src = s->regions;
+        m.src = s->ws.regions;
         m.seg_stride = cap;
         m.seg_cap = cap;
-        m.seg_counts = s->counts;
+        m.seg_counts = s->ws.counts;
         m.segs_per_wg = std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
         if (n == 0) {
             m.q_stride = 0;
             m.nseg = 0;
             m.segs_per_wg = 1;
-            run_merge(s, m, qc, k, out_s, out_i, nullptr, fo);
+            run_merge(s, s->ws, m, qc, k, out_s, out_i, nullptr, fo);
             continue;
         }
         ic::ScanArgs a{};
@@ -1230,16 +1263,16 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         a.n = n;
         a.row_bytes = L.row_bytes;
         a.row_scale = s->scale;
-        a.bias = use_bias ? s->bias : (const float *)s->consts;
+        a.bias = use_bias ? s->ws.bias : (const float *)s->ws.consts;
         a.bias_stride = use_bias ? 1 : 0;
-        a.qbuf = s->qbuf;
-        a.q_scale = s->qscale;
+        a.qbuf = s->ws.qbuf;
+        a.q_scale = s->ws.qscale;
         a.Q = qc;
         a.k = k;
         a.cap = cap;
         a.S = S;
-        a.regions = s->regions;
-        a.counts = s->counts;
+        a.regions = s->ws.regions;
+        a.counts = s->ws.counts;
         a.tile_mul = 1;
         a.task_cluster = ivf->probe_ids;
         a.task_offsets = ivf->offsets;
@@ -1248,7 +1281,7 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         m.q_stride = (int64_t)nprobe * S * cap;
         m.nseg = nprobe * S;
         m.id_map = ivf->perm;
-        run_merge(s, m, qc, k, out_s, out_i, nullptr, fo);
+        run_merge(s, s->ws, m, qc, k, out_s, out_i, nullptr, fo);
     }
     return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
 }

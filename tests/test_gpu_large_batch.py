@@ -30,12 +30,9 @@ def _run(pkg, cfg, max_k=None, list_cap=None, counts=None):
     E, U, M = wl.rows(0, cfg.N)
     Qm = wl.queries()
     sid = pkg.STORE_BF16 if cfg.store == "bf16" else pkg.STORE_FP8_E4M3
+    ix = pkg.Index(cfg.d, cfg.N, sid, cfg.Q, max_k or cfg.k, DEV)
     if list_cap is not None:
-        os.environ["IC_GEMM_LIST_CAP"] = str(list_cap)
-    try:
-        ix = pkg.Index(cfg.d, cfg.N, sid, cfg.Q, max_k or cfg.k, DEV)
-    finally:
-        os.environ.pop("IC_GEMM_LIST_CAP", None)
+        ix.set_tuning(list_keys=list_cap)
     ix.append(E.to(DEV), None if U is None else U.to(DEV))
     s, i = ix.search(Qm.to(DEV), cfg.k, cfg.lam, None if M is None else M.to(DEV))
     torch.cuda.synchronize()
@@ -242,12 +239,9 @@ def test_large_batch_queries_that_are_stored_rows(pkg, oracle, list_cap):
     E, U, M = wl.rows(0, cfg.N)
     first = 1000
     Qm = E[first:first + cfg.Q].contiguous()
+    ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, cfg.Q, cfg.k, DEV)
     if list_cap is not None:
-        os.environ["IC_GEMM_LIST_CAP"] = str(list_cap)
-    try:
-        ix = pkg.Index(cfg.d, cfg.N, pkg.STORE_BF16, cfg.Q, cfg.k, DEV)
-    finally:
-        os.environ.pop("IC_GEMM_LIST_CAP", None)
+        ix.set_tuning(list_keys=list_cap)
     ix.append(E.to(DEV), U.to(DEV))
     for k in (1, 2, 4):
         s, i = ix.search(Qm.to(DEV), k, cfg.lam, M.to(DEV))

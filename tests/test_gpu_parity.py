@@ -73,6 +73,19 @@ def test_store_matches_reference_quantiser_bit_for_bit(pkg, oracle, store, d):
     N = 1037
     E = (rng.standard_normal((N, d)) * np.exp(rng.uniform(-3, 3, (N, 1)))).astype(np.float32)
     E[5] = 0.0
+    ties = 0
+    if d >= 32:
+        # rows whose unit values are exact and lie half-way between two codes (norm a power of two)
+        T = workloads.tie_rows(store, 40, d, seed=d).numpy()
+        E[100:140] = T
+        unit = (T.astype(np.float64) / np.sqrt((T.astype(np.float64) ** 2).sum(1, keepdims=True))).astype(np.float32)
+        if store == "bf16":
+            ties = int(((unit.view(np.uint32) & 0xFFFF) == 0x8000).sum())
+        else:
+            m, _ = np.frexp(np.abs(unit.astype(np.float64)) * 1024.0)     # unit / scale: the integer entries
+            ties = int(((np.abs(unit) * 1024 >= 16) & (m * 32 == np.floor(m * 32)) &
+                        ((m * 32).astype(np.int64) & 1 == 1)).sum())
+        assert ties >= 100, ties
     U = rng.random(N).astype(np.float32)
     ix = _build_index(pkg, store, E, U, chunks=[0, 1, 300, 300, 1037])
     rows, scale, util = ix.store_view()
@@ -235,20 +248,17 @@ def test_results_do_not_depend_on_launch_shape(pkg):
     cfg = workloads.C3.scaled(N=50000, clusters=64, Q=64, k=64)
     E, U, M, Qm = _inputs(cfg)
     outs = []
-    try:
-        for budget in ("512", "7", "1", "64"):
-            os.environ["IC_SLICE_BUDGET"] = budget
-            ix = _build_index(pkg, "bf16", E, None)
-            outs.append(_search(ix, Qm, 64))
-            outs.append(_search(ix, Qm, 64))
-            ix.close()
-    finally:
-        os.environ.pop("IC_SLICE_BUDGET", None)
+    for budget in (512, 7, 1, 64):
+        ix = _build_index(pkg, "bf16", E, None)
+        ix.set_tuning(slices=budget)
+        outs.append(_search(ix, Qm, 64))
+        outs.append(_search(ix, Qm, 64))
+        ix.close()
     for s, i in outs[1:]:
         assert np.array_equal(i, outs[0][1]) and np.array_equal(s, outs[0][0])
 
 
-@pytest.mark.parametrize("d,Q,budget", [(384, 4, "3"), (256, 64, "3"), (768, 40, "3"), (128, 20, None)],
+@pytest.mark.parametrize("d,Q,budget", [(384, 4, 3), (256, 64, 3), (768, 40, 3), (128, 20, None)],
                          ids=["d384-q4", "d256-q64", "d768-q40", "d128-q20-all-slices"])
 def test_adversarial_ascending_order(pkg, oracle, d, Q, budget):
     """Rows sorted by ascending score: every row beats the running threshold, so the regions are
@@ -260,12 +270,9 @@ def test_adversarial_ascending_order(pkg, oracle, d, Q, budget):
     E, U, M, Qm = _inputs(cfg)
     order = np.argsort(oracle.scores(E, Qm[:1])[0], kind="stable")
     E = np.ascontiguousarray(E[order])
+    ix = _build_index(pkg, "bf16", E, None, max_k=128)
     if budget:
-        os.environ["IC_SLICE_BUDGET"] = budget      # three long slices: regions overflow and are compacted
-    try:
-        ix = _build_index(pkg, "bf16", E, None, max_k=128)
-    finally:
-        os.environ.pop("IC_SLICE_BUDGET", None)
+        ix.set_tuning(slices=budget)      # three long slices: regions overflow and are compacted
     # without a budget: hundreds of short slices whose regions together hold more keys than one
     # merge workgroup sorts at once (the merge then runs in rounds)
     for k in (1, 10, 100):

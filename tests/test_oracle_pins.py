@@ -269,6 +269,51 @@ def test_bf16_rounding_golden(oracle):
     assert np.array_equal(t, want)            # the table itself agrees with an independent RNE
     dec = oracle.decode_bf16(want)
     assert np.array_equal(dec.view(np.uint32), want.astype(np.uint32) << 16)
+    # the reference's own encoder, on the raw values (no normalisation in between)
+    assert np.array_equal(oracle.encode_bf16(vals), want)
+    ties = (bits & 0xFFFF) == 0x8000
+    down = ties & (((bits >> 16) & 1) == 0)
+    assert down.sum() >= 5 and (ties & ~down).sum() >= 5      # the table holds ties of both kinds
+
+
+def test_quantisers_on_rows_that_hit_exact_ties(oracle):
+    """Rows whose norm is a power of two: the unit values are exact, many of them half-way between two
+    codes.  Expected codes come from torch's casts of those exact values (an independent encoder)."""
+    import torch
+    import workloads
+    X = workloads.tie_rows("bf16", 24, 96, seed=31).numpy()
+    nrm = np.sqrt((X.astype(np.float64) ** 2).sum(1, keepdims=True))
+    assert np.all(np.log2(nrm) == np.round(np.log2(nrm)))
+    unit = (X.astype(np.float64) / nrm).astype(np.float32)
+    assert np.array_equal(unit.astype(np.float64) * nrm, X.astype(np.float64))       # exact
+    ub = unit.view(np.uint32)
+    ties = (ub & 0xFFFF) == 0x8000
+    up = ties & (((ub >> 16) & 1) == 1)
+    assert ties.sum() >= 100 and up.sum() >= 30 and (ties & ~up).sum() >= 30
+    want = torch.from_numpy(unit).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.quantize_bf16(X)
+    assert np.array_equal(got, want)
+    # by the definition itself: a tie goes to the neighbour whose last kept bit is 0
+    assert np.all((got[ties] & 1) == 0)
+    assert np.array_equal(got[ties & ~up], (ub[ties & ~up] >> 16).astype(np.uint16))
+    assert np.array_equal(got[up], ((ub[up] >> 16) + 1).astype(np.uint16))
+
+    X = workloads.tie_rows("fp8", 24, 96, seed=32).numpy()
+    nrm = np.sqrt((X.astype(np.float64) ** 2).sum(1, keepdims=True))
+    unit = (X.astype(np.float64) / nrm).astype(np.float32)
+    codes, scale = oracle.quantize_fp8(X)
+    assert np.array_equal(scale, np.full(24, 2.0 ** -10, np.float32))
+    t = unit.astype(np.float64) / scale[:, None].astype(np.float64)                  # the integer entries
+    assert np.array_equal(t, np.round(t)) and np.abs(t).max() == 448
+    m, _ = np.frexp(np.abs(t))
+    sig = m * 32                                                                   # 5-bit significand
+    ties = (np.abs(t) >= 16) & (sig == np.floor(sig)) & ((sig.astype(np.int64) & 1) == 1)
+    assert ties.sum() >= 100
+    want = torch.from_numpy(t.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(codes, want)
+    assert np.all((codes[ties] & 1) == 0)                                          # ties to the even mantissa
+    dec = oracle.decode_e4m3(codes).astype(np.float64)
+    assert (dec[ties] > t[ties]).sum() >= 20 and (dec[ties] < t[ties]).sum() >= 20   # both directions occur
 
 
 def test_bf16_quantiser_matches_independent_rne(oracle):

@@ -151,3 +151,77 @@ class Workload:
         """Query batch number ``batch``: fp32 [Q,d], unit rows near cluster centres."""
         Q = self.cfg.Q if Q is None else Q
         return self._draw(_STREAM_QUERIES, batch, Q).contiguous()
+
+
+# ---------------------------------------------------------------------------------------------
+# Rows that land exactly on rounding ties of the store formats.
+# ---------------------------------------------------------------------------------------------
+
+def _two_squares(n: int):
+    a = math.isqrt(n)
+    while a * a * 2 >= n:
+        b2 = n - a * a
+        b = math.isqrt(b2)
+        if b * b == b2:
+            return a, b
+        a -= 1
+    return None
+
+
+def _four_squares(n: int, limit: int):
+    """Non-negative integers (a, b, c, e), each <= limit, with a^2 + b^2 + c^2 + e^2 == n (Lagrange)."""
+    a = min(math.isqrt(n), limit)
+    while a >= 0:
+        r1 = n - a * a
+        b = min(math.isqrt(r1), limit)
+        while b >= 0 and 3 * b * b >= r1:      # b is the largest of the remaining three
+            two = _two_squares(r1 - b * b)
+            if two and max(two) <= limit:
+                return a, b, two[0], two[1]
+            b -= 1
+        a -= 1
+    raise ValueError(f"no decomposition of {n} within {limit}")
+
+
+def tie_rows(fmt: str, n: int, d: int, seed: int) -> torch.Tensor:
+    """fp32 rows [n, d] with integer entries (times a power of two per row) whose Euclidean norm is
+    an exact power of two, so that every ``x / |x|`` is exact in binary, and many of which sit exactly
+    half-way between two neighbouring codes of the store format ``fmt``:
+
+    * ``"bf16"``: entries ``m * 2^e`` with ``m`` odd in [257, 511] (a 9-bit significand, one bit more than
+      bfloat16 keeps) in a row of norm 4096;
+    * ``"fp8"``: a row of norm 1024 whose largest magnitude is 448, so the per-row scale is exactly
+      2^-10 and ``unit / scale`` is the integer entry itself; entries ``m * 2^e`` with ``m`` odd in
+      [17, 31] (a 5-bit significand, one more than E4M3 keeps).
+
+    Both rounding directions occur (the neighbour with the even last bit lies below for some entries,
+    above for others).  The rest of the row is what makes the sum of squares come out, then zeros.
+    """
+    assert fmt in ("bf16", "fp8") and d >= 32
+    rng = torch.Generator().manual_seed(seed)
+    ri = lambda lo, hi: int(torch.randint(lo, hi + 1, (1,), generator=rng))   # inclusive
+    rows = torch.zeros(n, d, dtype=torch.float64)
+    for i in range(n):
+        if fmt == "bf16":
+            target, limit, vals = 4096 ** 2, 4096, []
+            tie = lambda: (2 * ri(128, 255) + 1) << ri(0, 2)
+        else:
+            target, limit, vals = 1024 ** 2, 448, [448, 448, 448, 448]
+            tie = lambda: min((2 * ri(8, 15) + 1) << ri(0, 4), 432)   # 27 * 16: the largest tie below 448
+        rem = target - sum(v * v for v in vals)
+        floor_rem = 20_000 if fmt == "fp8" else 200_000
+        while len(vals) < d - 4:
+            t = tie()
+            if rem - t * t < floor_rem:
+                if fmt == "fp8" and rem > limit * limit:
+                    continue       # what is left has to fit four entries of at most 448
+                break
+            vals.append(t)
+            rem -= t * t
+        vals.extend(_four_squares(rem, limit))
+        assert sum(v * v for v in vals) == target and len(vals) <= d
+        v = torch.tensor(vals, dtype=torch.float64)
+        v = v * (torch.randint(0, 2, (len(vals),), generator=rng).to(torch.float64) * 2 - 1)
+        pos = torch.randperm(d, generator=rng)[: len(vals)]
+        rows[i, pos] = v * 2.0 ** ri(-3, 3)
+    return rows.to(torch.float32)
