@@ -120,6 +120,28 @@ ic_status ic_search(const ic_index *index, const float *q_dev, int64_t Q, int32_
                     int64_t *out_ids_dev);
 
 /*
+ * ic_search for callers that cannot allocate device memory or hand over a large workspace
+ * at the time of the call: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same result (bit for bit) as ic_search,
+ * but every buffer the search writes besides its outputs (prepared queries, per-row bias,
+ * candidate regions, merge lists, pilot keys) lies in a static device array inside the
+ * library (IC_STATIC_SCRATCH_BYTES per GPU the library is used on, held until the process
+ * ends) instead of the index's arena; the call allocates nothing and creates no events
+ * (kernel timing does not cover it).
+ * Limits: Q <= IC_STATIC_MAX_QUERIES, index size <= IC_STATIC_MAX_ROWS (rounded up to 256);
+ * beyond them IC_ERR_UNSUPPORTED and nothing is launched.  The index must live on the current
+ * GPU (INVALID_ARG otherwise).  Such batches always take the streaming scan.
+ * All calls on one GPU share the one array: calls that overlap on a GPU (two streams, two
+ * threads, two indices) race; the caller orders them.  Errors otherwise as ic_search.
+ */
+#define IC_STATIC_MAX_QUERIES 64
+#define IC_STATIC_MAX_ROWS 4194304
+#define IC_STATIC_SCRATCH_BYTES (80u << 20)
+ic_status ic_search_static(const ic_index *index, const float *q_dev, int64_t Q, int32_t k,
+                           float lambda, const uint8_t *mask_dev, float *out_scores_dev,
+                           int64_t *out_ids_dev);
+
+/*
  * Sharing domains (Sec. 4.3, "How Does IC-Cache Respect Privacy?": cached examples may be shared
  * only within designated user domains).  Every stored row carries a 32-bit domain; 0, the value
  * rows are appended with, means shared with every domain.

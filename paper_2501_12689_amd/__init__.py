@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     ic_index_set_utility,
     ic_search,
     ic_search_domains,
+    ic_search_static,
     ic_search_threshold,
     ic_self_search,
     ic_workspace_bytes,

@@ -21,7 +21,7 @@ IC_MAX_K = 128
 IC_ARENA_ALIGN = 256
 
 EXPORTS = (
-    "ic_workspace_bytes", "ic_index_create", "ic_index_append", "ic_search", "ic_index_destroy",
+    "ic_workspace_bytes", "ic_index_create", "ic_index_append", "ic_search", "ic_search_static", "ic_index_destroy",
     "ic_index_size", "ic_index_set_stream", "ic_index_store_view", "ic_index_set_timing", "ic_index_set_tuning",
     "ic_index_scan_time_ms", "ic_index_tiled_scan_counts", "ic_status_string",
     "ic_index_set_utility", "ic_index_scale_utility", "ic_index_invalidate", "ic_index_compact",
@@ -64,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     L.ic_index_append.argtypes = [vp, vp, vp, i64, ctypes.POINTER(i64)]
     L.ic_search.restype = ctypes.c_int
     L.ic_search.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp]
+    L.ic_search_static.restype = ctypes.c_int
+    L.ic_search_static.argtypes = [vp, vp, i64, i32, f32, vp, vp, vp]
     L.ic_search_threshold.restype = ctypes.c_int
     L.ic_search_threshold.argtypes = [vp, vp, i64, i32, f32, vp, f32, vp, vp, vp]
     L.ic_self_search.restype = ctypes.c_int
@@ -172,6 +174,15 @@ def ic_search(handle: int, queries: torch.Tensor, k: int, lam: float = 0.0,
                        _dev_ptr(out_scores, torch.float32, "out_scores"),
                        _dev_ptr(out_ids, torch.int64, "out_ids")), "ic_search")
     return out_scores, out_ids
+
+
+def ic_search_static(handle: int, queries: torch.Tensor, k: int, lam: float, mask: Optional[torch.Tensor],
+                     out_scores: torch.Tensor, out_ids: torch.Tensor) -> None:
+    """``ic_search`` with the library's static scratch; the caller passes the outputs (nothing is allocated)."""
+    _check(load_library().ic_search_static(handle, _dev_ptr(queries, torch.float32, "queries"), queries.shape[0], k,
+                                           float(lam), _dev_ptr(mask, torch.uint8, "mask"),
+                                           _dev_ptr(out_scores, torch.float32, "out_scores"),
+                                           _dev_ptr(out_ids, torch.int64, "out_ids")), "ic_search_static")
 
 
 def ic_search_threshold(handle: int, queries: torch.Tensor, k: int, min_score: float, lam: float = 0.0,

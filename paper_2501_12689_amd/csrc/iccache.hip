@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -944,6 +945,92 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
     return IC_OK;
 }
 }  // namespace
+
+// ---- a search whose scratch is a static device array (for callers that cannot allocate) -------
+
+namespace {
+constexpr int kStaticQueries = IC_STATIC_MAX_QUERIES;
+constexpr int64_t kStaticRows = IC_STATIC_MAX_ROWS;
+constexpr int64_t kStaticRegionSlots = (int64_t)kStaticQueries * 512;   // 64 queries x 512 slices
+constexpr int kStaticDevices = 64;
+
+struct StaticLayout {
+    size_t off_qbuf, off_qscale, off_consts, off_pilot, off_thr, off_counts, off_list_a, off_list_b, off_bias,
+        off_regions, total;
+};
+constexpr size_t static_up(size_t x) { return (x + (size_t)kAlign - 1) / (size_t)kAlign * (size_t)kAlign; }
+constexpr StaticLayout make_static_layout() {
+    StaticLayout S{};
+    size_t off = 0;
+    S.off_qbuf = off;     off = static_up(off + (size_t)kStaticQueries * kMaxRowBytes);
+    S.off_qscale = off;   off = static_up(off + (size_t)kStaticQueries * 4);
+    S.off_consts = off;   off = static_up(off + 64);
+    S.off_pilot = off;    off = static_up(off + (size_t)kStaticQueries * kPilotSlices * 8);
+    S.off_thr = off;      off = static_up(off + (size_t)kStaticQueries * 8);
+    S.off_counts = off;   off = static_up(off + (size_t)kStaticRegionSlots * 4);
+    S.off_list_a = off;   off = static_up(off + (size_t)(kStaticRegionSlots / 8 + kStaticQueries) * IC_MAX_K * 8);
+    S.off_list_b = off;   off = static_up(off + (size_t)(kStaticRegionSlots / 8 + kStaticQueries) * IC_MAX_K * 8);
+    S.off_bias = off;     off = static_up(off + (size_t)kStaticRows * 4);
+    S.off_regions = off;  off = static_up(off + (size_t)kStaticRegionSlots * ic::kMaxCap * 8);
+    S.total = off;
+    return S;
+}
+constexpr StaticLayout kStaticLayout = make_static_layout();
+static_assert(kStaticLayout.total <= (size_t)IC_STATIC_SCRATCH_BYTES, "the static scratch holds the workspace");
+}  // namespace
+
+// The scratch itself: one copy per GPU the library runs on, held until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; the device address it yields is what
+// the kernels get.
+static __device__ __align__(256) unsigned char scratch[IC_STATIC_SCRATCH_BYTES];
+
+namespace {
+struct StaticState {
+    unsigned char *ptr = nullptr;   // device address of `scratch` on this GPU
+    bool consts_ready = false;
+};
+StaticState g_static[kStaticDevices];
+std::mutex g_static_mutex;
+}  // namespace
+
+extern "C" ic_status ic_search_static(const ic_index *cindex, const float *q_dev, int64_t Q, int32_t k, float lambda,
+                                      const uint8_t *mask_dev, float *out_scores_dev, int64_t *out_ids_dev) {
+    if (!cindex || Q < 0 || (Q > 0 && !q_dev)) return IC_ERR_INVALID_ARG;
+    if (Q > kStaticQueries || round_up(cindex->n, ic::kGemmTile) > kStaticRows) return IC_ERR_UNSUPPORTED;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return IC_ERR_DEVICE;
+    if (dev < 0 || dev >= kStaticDevices) return IC_ERR_UNSUPPORTED;
+    if (dev != cindex->device) return IC_ERR_INVALID_ARG;   // the index lives on another GPU than the current one
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticState &st = g_static[dev];
+    if (!st.ptr) {   // once per device, with that device current: every GPU has its own copy at its own address
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return IC_ERR_DEVICE;
+        }
+        st.ptr = static_cast<unsigned char *>(p);
+    }
+    constexpr StaticLayout S = kStaticLayout;
+    Workspace W;
+    W.qbuf = st.ptr + S.off_qbuf;
+    W.qscale = (float *)(st.ptr + S.off_qscale);
+    W.consts = st.ptr + S.off_consts;
+    W.pilot_keys = (uint64_t *)(st.ptr + S.off_pilot);
+    W.thr_init = (uint64_t *)(st.ptr + S.off_thr);
+    W.counts = (int32_t *)(st.ptr + S.off_counts);
+    W.list_a = (uint64_t *)(st.ptr + S.off_list_a);
+    W.list_b = (uint64_t *)(st.ptr + S.off_list_b);
+    W.bias = (float *)(st.ptr + S.off_bias);
+    W.regions = (uint64_t *)(st.ptr + S.off_regions);
+    W.q_chunk = kStaticQueries;
+    W.region_slots = kStaticRegionSlots;
+    W.consts_ready = &st.consts_ready;
+    W.timed = false;   // timing creates events; this call creates nothing
+    SearchReq r;
+    r.q_dev = q_dev;
+    return search_impl(const_cast<ic_index *>(cindex), W, Q, k, lambda, mask_dev, out_scores_dev, out_ids_dev, r);
+}
 
 // ---- cluster pruning (Sec. 4.1: K-Means clusters offline, nearest clusters first online) ------
 
