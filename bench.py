@@ -12,8 +12,9 @@ example, not per batch; its rate is reported separately under ``append``.
 The matrix-core regime is timed as well (fewer steps, they are long): Q = 4096 on
 the same store (``config.per_Q["4096"]``) and the N = 4,000,000, d = 1024, k = 16
 configuration with utility and mask (``large_batch``, ``roofline_mfma``); and the fp8 store
-(N = 20,000,000, d = 1024, k = 100, built by appends of 100,000 rows) at Q = 1, 64 and 4096
-(``fp8_store``).  ``maintenance`` times the eviction of the masked rows of the d = 1024
+(N = 20,000,000, d = 1024, k = 100, built by appends of 100,000 rows) with Q swept over the powers of
+two from 1 to 8192, 100,000 more rows appended (and timed) before every batch size after the first
+(``fp8_store``: both roofline fractions per Q).  ``maintenance`` times the eviction of the masked rows of the d = 1024
 configuration and the compaction that squeezes them out; ``census`` runs a self-search of every
 row of a 1,000,000-row store against all the others; ``cluster_pruning`` trains K = sqrt(N)
 clusters on the headline store and times the pruned search, with its recall against the exact one.
@@ -117,7 +118,10 @@ def cluster_pruning_leg(pkg, torch, np, ix, wl, cfg, Q, k, probes):
     torch.cuda.synchronize()
     leg = {"N": len(ix), "K": K, "kmeans_iterations": 2, "train_s": time.perf_counter() - t0, "Q": Q, "k": k,
            "per_nprobe": {}}
+    sizes = ivf.view()[1].diff()                     # rows per cluster list
     for nprobe in probes:
+        # comparisons per query against the paper's cost model K + N/K (times the lists probed)
+        scanned = float(sizes[ivf.probed_clusters(qd, nprobe)].sum(1).double().mean())
         for _ in range(3):
             ivf.search(qd, k, nprobe, cfg.lam)
         torch.cuda.synchronize()
@@ -132,7 +136,12 @@ def cluster_pruning_leg(pkg, torch, np, ix, wl, cfg, Q, k, probes):
         rec = float(np.mean([len(set(a[q].tolist()) & set(b[q].tolist()) - {-1}) / max(1, int((b[q] >= 0).sum()))
                              for q in range(Q)]))
         leg["per_nprobe"][str(nprobe)] = {"ms_per_step": ms, "queries_per_s": Q / (ms * 1e-3),
-                                          f"recall_at_{k}_vs_exact": rec}
+                                          f"recall_at_{k}_vs_exact": rec,
+                                          "comparisons_per_query": K + scanned,
+                                          "cost_model_K_plus_nprobe_N_over_K": K + nprobe * len(ix) / K,
+                                          "exact_scan_comparisons": len(ix)}
+    # every queued launch has finished before the structure's arena is released
+    torch.cuda.synchronize()
     ivf.close()
     ivf.arena = None
     return leg
@@ -390,44 +399,64 @@ def main() -> int:
     if not args.no_large_batch and not args.no_fp8:
         c5 = workloads.C5 if args.rows is None else workloads.C5.scaled(N=min(workloads.C5.N, args.rows))
         wl5 = workloads.Workload(c5, dev)
-        ix5 = pkg.Index(c5.d, c5.N, pkg.STORE_FP8_E4M3, LARGE_Q, c5.k, dev)
+        sweep = [1 << e for e in range(14)]                      # Q = 1 .. 8192
+        step_rows = 100_000                                       # rows appended between search batches
+        ix5 = pkg.Index(c5.d, c5.N + len(sweep) * step_rows, pkg.STORE_FP8_E4M3, sweep[-1], c5.k, dev)
         app_ms, app_rows = 0.0, 0
+
+        def timed_append(E):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ix5.append(E, None)
+            e1.record()
+            e1.synchronize()
+            return e0.elapsed_time(e1)
+
         for lo in range(0, c5.N, chunk):
             n = min(chunk, c5.N - lo)
             E, U, M = wl5.rows(lo, n)
-            for a0 in range(0, n, 100_000):
-                a1 = min(n, a0 + 100_000)
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                ix5.append(E[a0:a1], None)
-                e1.record()
-                e1.synchronize()
-                app_ms += e0.elapsed_time(e1)
+            for a0 in range(0, n, step_rows):
+                a1 = min(n, a0 + step_rows)
+                app_ms += timed_append(E[a0:a1])
                 app_rows += a1 - a0
             del E
         row5 = ix5.store_view()[0].shape[1]
-        bytes5 = c5.N * (row5 + 4)   # rows + per-row scale
-        fp8 = {"workload": f"C5: N={c5.N} d={c5.d} fp8 e4m3 store with per-row scale, {c5.clusters}-cluster "
-                           f"Zipf(1.1) mixture, k={c5.k}, lambda=0, no mask",
-               "append_rows_per_s": app_rows / (app_ms * 1e-3), "per_Q": {}}
-        for Q in (1, 64, LARGE_Q):
+        fp8 = {"workload": f"C5: N={c5.N} (+{step_rows} rows appended before every batch size after the first) d={c5.d} "
+                           f"fp8 e4m3 store with per-row scale, {c5.clusters}-cluster Zipf(1.1) mixture, k={c5.k}, "
+                           "lambda=0, no mask; Q swept 1..8192",
+               "append_rows_per_s": app_rows / (app_ms * 1e-3), "between_batches": [], "per_Q": {}}
+        for Q in sweep:
+            if Q > 1:                                             # the cache grows while it is being served
+                E, U, M = wl5.rows(len(ix5), step_rows)
+                ms_a = timed_append(E)
+                fp8["between_batches"].append({"rows": step_rows, "ms": ms_a, "rows_per_s": step_rows / (ms_a * 1e-3),
+                                               "GBps_in_plus_out": step_rows * (c5.d * 4 + row5 + 4) / (ms_a * 1e-3) / 1e9})
+                del E
+            n5 = len(ix5)
+            bytes5 = n5 * (row5 + 4)   # rows + per-row scale
             qd = wl5.queries(Q, batch=Q)
             out_s = torch.empty(Q, c5.k, dtype=torch.float32, device=dev)
             out_i = torch.empty(Q, c5.k, dtype=torch.int64, device=dev)
-            st, wu = (lsteps, lwarm) if Q == LARGE_Q else (max(10, args.steps // 4), max(2, args.warmup // 4))
-            ms, scan, wall, spread = time_search(ix5, torch, qd, c5.k, c5.lam, None, out_s, out_i, wu, st)
-            rec = {"queries_per_s": Q / (ms * 1e-3), "ms_per_step": ms, "steps": st, "scan_kernel_ms": scan,
-                   "step_ms": spread}
-            if Q == LARGE_Q:
-                rec["tiles_again_blocks_redone"] = list(ix5.tiled_scan_counts())
-                flop = 2.0 * Q * c5.N * c5.d
-                rec["scan_TFLOPs"] = flop / (scan * 1e-3) / 1e12
-                rec["mfma_frac"] = rec["scan_TFLOPs"] / MFMA_FP8_PEAK_TFLOPS
+            if Q >= 1024:
+                st, wu = max(3, min(5, args.steps)), 1
+            elif Q > 64:
+                st, wu = max(3, min(10, args.steps)), 2
             else:
-                rec["scan_GBps"] = bytes5 / (scan * 1e-3) / 1e9
-                rec["hbm_frac"] = rec["scan_GBps"] / HBM_PEAK_GBS
+                st, wu = max(10, args.steps // 4), max(2, args.warmup // 4)
+            ms, scan, wall, spread = time_search(ix5, torch, qd, c5.k, c5.lam, None, out_s, out_i, wu, st)
+            flop = 2.0 * Q * n5 * c5.d
+            rec = {"rows": n5, "queries_per_s": Q / (ms * 1e-3), "ms_per_step": ms, "steps": st, "scan_kernel_ms": scan,
+                   "step_ms": spread, "scan_GBps": bytes5 / (scan * 1e-3) / 1e9,
+                   "hbm_frac": bytes5 / (scan * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                   "scan_TFLOPs": flop / (scan * 1e-3) / 1e12,
+                   "mfma_frac": flop / (scan * 1e-3) / 1e12 / MFMA_FP8_PEAK_TFLOPS,
+                   "step_hbm_frac": bytes5 / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                   "step_mfma_frac": flop / (ms * 1e-3) / 1e12 / MFMA_FP8_PEAK_TFLOPS}
+            if Q > 64:
+                rec["tiles_again_blocks_redone"] = list(ix5.tiled_scan_counts())
             fp8["per_Q"][str(Q)] = rec
             del qd, out_s, out_i
+            say(f"fp8 store Q={Q}: {ms:.2f} ms per step")
         ix5.close()
 
     say("fp8 store done")

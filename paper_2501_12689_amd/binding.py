@@ -414,6 +414,14 @@ class Ivf:
                                             float(lam), out_scores.data_ptr(), out_ids.data_ptr()), "ic_ivf_search")
         return out_scores, out_ids
 
+    def probed_clusters(self, queries: torch.Tensor, nprobe: int) -> torch.Tensor:
+        """The nprobe nearest centroids of every query (int64 [Q, nprobe]): the same ``ic_search`` on the
+        centroid index that ``ic_ivf_search`` starts with."""
+        L = load_library()
+        c = ctypes.c_void_p()
+        _check(L.ic_ivf_view(self.handle, None, None, None, ctypes.byref(c), None), "ic_ivf_view")
+        return ic_search(c.value, queries, nprobe)[1]
+
     def view(self):
         """(assign int32 [size], offsets int64 [K+1], perm int32 [listed rows], centroid rows uint8 [K, row_bytes],
         centroid scales | None) as views of the arena."""

@@ -11,7 +11,8 @@ Two checks, both phrased with reference values only:
 
 * **sharp** (against the reference fed with the values the store holds, from
   the reference's own quantiser; ``tau_q`` = 1e-4 covers fp32 accumulation
-  order): over a candidate pool (all rows, or the returned ids plus the
+  order for scores of order 1; a case with a large ``lambda * utility`` passes
+  the same bound scaled to the fp32 spacing at that magnitude): over a candidate pool (all rows, or the returned ids plus the
   reference's top-K'), returned scores match within ``tau_q`` and the returned
   set equals the pool's top-k except for members within ``tau_q`` of the k-th.
 
@@ -65,7 +66,7 @@ def check_structure(gs: np.ndarray, gi: np.ndarray, n_valid: int, k: int,
 def check_query(store: str, gs: np.ndarray, gi: np.ndarray, k: int, lam: float,
                 q_vec: np.ndarray, ref_ids: np.ndarray, ref_s64: np.ndarray, n_valid: int,
                 fetch: Callable[[np.ndarray], tuple], is_valid: Callable[[np.ndarray], np.ndarray],
-                where: str, sharp: bool = True) -> dict:
+                where: str, sharp: bool = True, tau_q: float = TAU_Q) -> dict:
     """Check one query.  ``ref_*`` is the reference's best-K' list (K' >= min(k+1, n_valid))
     on the fp32 masters; ``fetch(ids)`` returns (E rows fp32, U or None) for given ids."""
     tau = TAU[store]
@@ -100,22 +101,22 @@ def check_query(store: str, gs: np.ndarray, gi: np.ndarray, k: int, lam: float,
         s_ret = np.array([s_hat[pos[int(i)]] for i in ret])
         err_q = np.abs(gs[:m].astype(np.float64) - s_ret)
         stats["max_err_q"] = float(err_q.max())
-        assert err_q.max() <= TAU_Q, f"{where}: stored-value score off by {err_q.max():.3e}"
+        assert err_q.max() <= tau_q, f"{where}: stored-value score off by {err_q.max():.3e}"
         order = np.lexsort((pool, -s_hat))
         top = pool[order][:m]
         kth = s_hat[order][m - 1]
         extra = np.setdiff1d(ret, top)       # returned but not in the pool's top-m
         lost = np.setdiff1d(top, ret)        # in the pool's top-m but not returned
         for i in extra:
-            assert s_hat[pos[int(i)]] > kth - TAU_Q, f"{where}: id {i} returned from below the cut"
+            assert s_hat[pos[int(i)]] > kth - tau_q, f"{where}: id {i} returned from below the cut"
         for i in lost:
-            assert s_hat[pos[int(i)]] < kth + TAU_Q, f"{where}: id {i} (score above the cut) missing"
+            assert s_hat[pos[int(i)]] < kth + tau_q, f"{where}: id {i} (score above the cut) missing"
     return stats
 
 
 def check_batch(store: str, gpu_scores: np.ndarray, gpu_ids: np.ndarray, E: np.ndarray,
                 U: Optional[np.ndarray], mask: Optional[np.ndarray], Qm: np.ndarray, k: int,
-                lam: float, where: str, queries=None, sharp: bool = True) -> dict:
+                lam: float, where: str, queries=None, sharp: bool = True, tau_q: float = TAU_Q) -> dict:
     """Whole-cache check for host-resident masters (small and medium sizes)."""
     N = E.shape[0]
     valid = np.ones(N, bool) if mask is None else (mask != 0)
@@ -131,7 +132,7 @@ def check_batch(store: str, gpu_scores: np.ndarray, gpu_ids: np.ndarray, E: np.n
     agg = {"recall": [], "max_err": 0.0, "max_err_q": 0.0}
     for j, q in enumerate(qs):
         st = check_query(store, gpu_scores[q], gpu_ids[q], k, lam, Qm[q], ref_i[j], ref_s[j], n_valid,
-                         fetch, lambda ids: valid[ids], f"{where} q={q}", sharp=sharp)
+                         fetch, lambda ids: valid[ids], f"{where} q={q}", sharp=sharp, tau_q=tau_q)
         agg["recall"].append(st["recall"])
         agg["max_err"] = max(agg["max_err"], st["max_err"])
         agg["max_err_q"] = max(agg["max_err_q"], st["max_err_q"])

@@ -113,23 +113,25 @@ def _search(run, Q=None, mask=True):
     return s, i
 
 
-def _tiled_batch_check(pkg, run, ref, where, Q=4096):
-    """The same store searched with a batch large enough for the MFMA-tiled scan: a second index
-    (max_queries = Q) is filled from the masters on the GPU, the referenced queries sit at the
-    front of a batch of Q, and their rows of the result go through the same checks."""
+def _tiled_batch_check(pkg, run, ref, where, Qs=(4096,)):
+    """The same store searched with batches large enough for the MFMA-tiled scan: a second index
+    (max_queries = the largest batch) is filled from the masters on the GPU, the referenced queries
+    sit at the front of every batch, and their rows of the result go through the same checks."""
     cfg = run.cfg
     store = pkg.STORE_BF16 if cfg.store == "bf16" else pkg.STORE_FP8_E4M3
-    ix2 = pkg.Index(cfg.d, cfg.N, store, Q, cfg.k, DEV)
+    ix2 = pkg.Index(cfg.d, cfg.N, store, max(Qs), cfg.k, DEV)
     for lo in range(0, cfg.N, CHUNK):
         hi = min(cfg.N, lo + CHUNK)
         ix2.append(run.E[lo:hi], None if run.U is None else run.U[lo:hi])
-    big = run.wl.queries(Q, batch=3)
-    big[: run.Qd.shape[0]] = run.Qd
-    t0 = time.time()
-    s, i = ix2.search(big, cfg.k, cfg.lam, run.M)
-    torch.cuda.synchronize()
-    print(f"   search Q={Q} (tiled) took {1e3 * (time.time() - t0):.2f} ms (incl. launch)", flush=True)
-    run.check(s, i, ref, where)
+    for Q in Qs:
+        big = run.wl.queries(Q, batch=3)
+        big[: run.Qd.shape[0]] = run.Qd
+        t0 = time.time()
+        s, i = ix2.search(big, cfg.k, cfg.lam, run.M)
+        torch.cuda.synchronize()
+        print(f"   search Q={Q} (tiled) took {1e3 * (time.time() - t0):.2f} ms (incl. launch); "
+              f"tiles done again, blocks redone: {ix2.tiled_scan_counts()}", flush=True)
+        run.check(s, i, ref, f"{where} Q={Q}")
     ix2.close()
 
 
@@ -163,7 +165,7 @@ def test_c3_full(pkg, oracle):
         s, i = _search(run, Q)
         assert torch.equal(i, i64[:Q]) and torch.equal(s, s64[:Q])
         run.check(s, i, ref, f"C3 Q={Q}")
-    _tiled_batch_check(pkg, run, ref, "C3 Q=4096 (tiled)")
+    _tiled_batch_check(pkg, run, ref, "C3 (tiled)", Qs=(4096,))
 
 
 def test_c4_full(pkg, oracle):
@@ -181,20 +183,25 @@ def test_c5_full_with_appends(pkg, oracle):
     run = _Run(pkg, oracle, cfg, [0, 1, 9, 17, 33, 40, 62, 63])
     step = 100_000
     run.feed(cfg.N - 2 * step)
+    ref = run.reference()                   # the reference's lists over the rows fed so far
     for Q in (1, 64):
         s, i = _search(run, Q)
-        assert int(i.max()) < len(run.ix) and int(i.min()) >= 0
+        run.check(s, i, ref, f"C5 Q={Q}, {len(run.ix)} rows")
     run.feed(cfg.N - step)                  # append 100k rows between search batches
     s, i = _search(run, 16)
-    assert int(i.max()) < len(run.ix)
+    run.check(s, i, run.reference(), f"C5 Q=16, {len(run.ix)} rows")
     run.feed(cfg.N)
     ref = run.reference()
     s, i = _search(run)
     run.check(s, i, ref, "C5 Q=64")
-    # larger batches reuse the same store: several passes of 64 queries
+    for Q in (2, 4, 8, 32):                 # the rest of the streaming half of the sweep
+        s2, i2 = _search(run, Q)
+        assert torch.equal(i2, i[:Q]) and torch.equal(s2, s[:Q])
+    # larger batches on an index made for 64 queries: several passes of 64 queries
     big = workloads.Workload(cfg, DEV).queries(512, batch=1)
     s2, i2 = run.ix.search(big, cfg.k, cfg.lam)
     s3, i3 = run.ix.search(big[100:101].contiguous(), cfg.k, cfg.lam)
     torch.cuda.synchronize()
     assert torch.equal(i2[100], i3[0]) and torch.equal(s2[100], s3[0])
-    _tiled_batch_check(pkg, run, ref, "C5 Q=4096 (tiled, fp8)")
+    # the tiled half of the sweep, up to the largest batch the layout allows
+    _tiled_batch_check(pkg, run, ref, "C5 (tiled, fp8)", Qs=(128, 256, 512, 1024, 2048, 4096, 8192))

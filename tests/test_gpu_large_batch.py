@@ -92,6 +92,34 @@ def test_large_batch_list_overflow_is_redone_exactly(pkg, oracle):
     parity.check_batch("bf16", b[0], b[1], a[2], None, None, a[5], 16, 0.0, "overflow", queries=range(0, 200, 9))
 
 
+@pytest.mark.parametrize("lam", [50.0, 2000.0])
+@pytest.mark.parametrize("store", ["bf16", "fp8"])
+def test_large_bias_through_the_redo_path(pkg, oracle, store, lam):
+    """lambda * utility far above the cosine's range.  The tiled bf16 scan starts its sums at the bias,
+    so each of its d/16 partial sums is rounded at that magnitude, and the thresholds its pilot hands
+    to the streaming scan (lists shrunk to 8 keys: every block is redone) differ from what that kernel
+    computes for the same rows by correspondingly more; no result may be lost.  The stored-value
+    tolerance is the same accumulation bound, (d/16 + 2) roundings of half a unit in the last place,
+    taken at the magnitude of the largest score."""
+    _say(f"tiled scan, lambda={lam}, forced list overflow, {store}")
+    d = 1024
+    cfg = workloads.Config("G", N=270000, d=d, clusters=32, Q=200, k=16, store=store, zipf=1.1, lam=lam,
+                           util="uniform", p_valid=0.9, seed=8150)
+    counts = []
+    s, i, E, U, M, Qm = _run(pkg, cfg, list_cap=8, counts=counts)
+    assert counts[0][1] == 4, counts             # all four blocks of 64 queries went through the redo
+    assert np.all(i >= 0), f"queries {np.flatnonzero((i < 0).any(1))[:8]} lost results"
+    top = 2.0 ** np.ceil(np.log2(1.0 + lam))      # scores lie below this power of two
+    tau_q = (d / 16 + 2) * 2.0 ** -24 * top
+    st = parity.check_batch(store, s, i, E, U, M, Qm, cfg.k, lam, f"bias {lam} {store}", queries=range(0, 200, 7),
+                            tau_q=max(parity.TAU_Q, tau_q))
+    print("   stats", st, "tau_q", tau_q, flush=True)
+    # and without the overflow (lists at their normal size), same rules
+    s, i, E, U, M, Qm = _run(pkg, cfg)
+    parity.check_batch(store, s, i, E, U, M, Qm, cfg.k, lam, f"bias {lam} {store} lists", queries=range(0, 200, 7),
+                       tau_q=max(parity.TAU_Q, tau_q))
+
+
 @pytest.mark.parametrize("store", ["bf16", "fp8"])
 def test_large_batch_on_a_store_sorted_by_cluster(pkg, oracle, store):
     """Rows in cluster order (a cache filled topic by topic): a query's candidates sit in a few row
