@@ -160,6 +160,8 @@ def main() -> int:
                     help="skip the cluster-pruning leg (tens of thousands of small launches while training)")
     ap.add_argument("--no-graph-replay", action="store_true",
                     help="skip the HIP-graph replay timing of the small configurations")
+    ap.add_argument("--fp8-sweep", type=str, default=None,
+                    help="comma-separated batch sizes of the fp8 leg (default: every power of two from 1 to 8192)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, so that a counter run over this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -400,8 +402,10 @@ def main() -> int:
         c5 = workloads.C5 if args.rows is None else workloads.C5.scaled(N=min(workloads.C5.N, args.rows))
         wl5 = workloads.Workload(c5, dev)
         sweep = [1 << e for e in range(14)]                      # Q = 1 .. 8192
+        if args.fp8_sweep:
+            sweep = sorted(int(x) for x in args.fp8_sweep.split(","))
         step_rows = 100_000                                       # rows appended between search batches
-        ix5 = pkg.Index(c5.d, c5.N + len(sweep) * step_rows, pkg.STORE_FP8_E4M3, sweep[-1], c5.k, dev)
+        ix5 = pkg.Index(c5.d, c5.N + len(sweep) * step_rows, pkg.STORE_FP8_E4M3, max(64, sweep[-1]), c5.k, dev)
         app_ms, app_rows = 0.0, 0
 
         def timed_append(E):
@@ -426,7 +430,7 @@ def main() -> int:
                            "lambda=0, no mask; Q swept 1..8192",
                "append_rows_per_s": app_rows / (app_ms * 1e-3), "between_batches": [], "per_Q": {}}
         for Q in sweep:
-            if Q > 1:                                             # the cache grows while it is being served
+            if Q != sweep[0]:                                     # the cache grows while it is being served
                 E, U, M = wl5.rows(len(ix5), step_rows)
                 ms_a = timed_append(E)
                 fp8["between_batches"].append({"rows": step_rows, "ms": ms_a, "rows_per_s": step_rows / (ms_a * 1e-3),

@@ -70,12 +70,12 @@ struct ScanArgs {
     // Set when thr_init was computed by a different kernel (the tiled scan's pilot): that kernel adds
     // the products in another order, so the score it saw for the k-th row may be a few ulps above
     // what this kernel computes for the same row, which would then miss its own threshold.  The
-    // starting score is lowered by this much (absolute) plus 2^-17 of its magnitude and of the
-    // largest |bias| of the search (*bias_absmax, if given: the tiled bf16 scan starts its sums at
-    // the bias, so each of its d/16 <= 64 partial sums is rounded at that magnitude); a lower start
-    // only admits more candidates, the selection stays exact.
+    // starting score s is lowered by this much (absolute) plus 2^-17 (|s| + 2).  The tiled bf16 scan
+    // starts its sums at the bias b, so each of its d/16 <= 64 partial sums is rounded at the magnitude
+    // |b| + 1, and the two kernels differ by at most about 65 * 2^-24 (|b| + 1) on a row; a row whose
+    // score lies that close to s has |b| <= |s| + 1, and rows further above s pass anyway.  A lower
+    // start only admits more candidates, the selection stays exact.
     float thr_slack;
-    const float *bias_absmax;
     // Task launches (TASK = true, one query group): workgroup column y is a (query, list) pair of a
     // cluster-pruned search.  Query y / task_nprobe is compared with the rows of one cluster, the
     // contiguous range [offsets[c], offsets[c + 1]) of a store sorted by cluster, c =
@@ -108,27 +108,16 @@ __host__ __device__ constexpr size_t scan_lds_bytes(int qg, int cap) {
 // Score bias of every row for one search: lambda * utility where the row is valid, -inf
 // where the mask excludes it, where the row has been invalidated (live[i] == 0) and for the
 // padding rows [n, n_pad).  util, mask and live may be NULL.
-// If absmax is not NULL it receives the largest |bias| over the valid rows (fp32 bits, which order
-// like the values for non-negative floats; the caller zeroes it first).
 __global__ __launch_bounds__(256) void make_bias(const float *__restrict__ util,
                                                  const uint8_t *__restrict__ mask,
                                                  const uint8_t *__restrict__ live, int64_t n,
-                                                 int64_t n_pad, float lambda, float *__restrict__ bias,
-                                                 uint32_t *__restrict__ absmax) {
+                                                 int64_t n_pad, float lambda, float *__restrict__ bias) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t step = (int64_t)gridDim.x * 256;
-    float big = 0.0f;
     for (; i < n_pad; i += step) {
         float b = -INFINITY;
-        if (i < n && (!mask || mask[i] != 0) && (!live || live[i] != 0)) {
-            b = util ? lambda * util[i] : 0.0f;
-            big = fmaxf(big, fabsf(b));
-        }
+        if (i < n && (!mask || mask[i] != 0) && (!live || live[i] != 0)) b = util ? lambda * util[i] : 0.0f;
         bias[i] = b;
-    }
-    if (absmax) {
-        big = wave_max(big);
-        if ((threadIdx.x & 63) == 0 && big > 0.0f) atomicMax(absmax, __float_as_uint(big));
     }
 }
 
@@ -221,8 +210,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
         if (t0 <= kKeyFloor) return kKeyFloor;
         if (a.thr_slack > 0.0f) {
             const float s0 = key_score(t0);
-            const float mag = fabsf(s0) + (a.bias_absmax ? *a.bias_absmax : 0.0f);
-            const float s1 = s0 - (a.thr_slack + mag * 0x1p-17f);
+            const float s1 = s0 - (a.thr_slack + (fabsf(s0) + 2.0f) * 0x1p-17f);
             return ((uint64_t)ord_of_score(s1) << 32) - 1ull;
         }
         return ((t0 >> 32) << 32) - 1ull;

@@ -40,7 +40,9 @@ constexpr int kGemmMinQueries = 65;         // batches from here on use the MFMA
 constexpr int kGemmListSeg = ic::kMergeKeys;  // candidate lists are merged in segments of this many keys
 constexpr uint32_t kGemmOverCap = 65536;      // tiles of one tiled scan that may be left to its second launch
 constexpr int kGemmListMax = 8 * kGemmListSeg;
-constexpr size_t kL2Share = 4u << 20;       // query-block bytes of a group of XCDs (measured: 4 MB beats 2 MB and 8 MB by about 3 %)
+constexpr size_t kL2Share = 2u << 20;       // query-block bytes of a group of XCDs: half of an XCD's 4 MB L2, the other half
+                                            // holds the row tiles its 32 workgroups are on (with the whole L2 given to queries
+                                            // the fp8 scan of 4096 queries re-read the store 9 times and ran 6 % slower)
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
@@ -120,12 +122,6 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
 __global__ void init_consts(uint32_t *c) {
     if (threadIdx.x < 16) c[threadIdx.x] = 0u;
 }
-
-// consts + 32: the largest |bias| of the search being prepared, as fp32 bits (make_bias raises it)
-__global__ void reset_bias_absmax(uint32_t *slot) {
-    if (threadIdx.x == 0) *slot = 0u;
-}
-constexpr int kConstsAbsmaxOffset = 32;
 
 using ScanFn = void (*)(dim3, hipStream_t, const ic::ScanArgs &);
 
@@ -226,8 +222,7 @@ struct Workspace {
     uint64_t *regions = nullptr;    // candidate keys per (query, slice)
     int32_t *counts = nullptr;
     uint64_t *list_a = nullptr, *list_b = nullptr;  // ping-pong between merge levels
-    uint8_t *consts = nullptr;      // 64 bytes: 16 zero bytes (the bias of a search without one), then the
-                                    // largest |bias| of the current search as fp32 bits at byte 32
+    uint8_t *consts = nullptr;      // 64 zero bytes (the bias of a search that has none)
     float *bias = nullptr;          // [cap_pad] per-row additive term of the current search
     uint64_t *pilot_keys = nullptr; // [q_chunk][kPilotSlices]
     uint64_t *thr_init = nullptr;   // [q_chunk]
@@ -693,17 +688,13 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
     // (it marks the padding rows of the last tile); the streaming scan only if it is not all zero.
     const bool any_gemm = gemm_for(std::min<int64_t>(Q, W.q_chunk));
     const bool use_bias = (lambda != 0.0f) || mask_dev != nullptr || any_gemm || index->any_invalid;
-    // The tiled scan hands thresholds to the streaming scan when a block is redone; the slack that
-    // covers their different rounding grows with the largest |bias|, which make_bias leaves here.
-    uint32_t *absmax = (any_gemm && lambda != 0.0f) ? (uint32_t *)(W.consts + kConstsAbsmaxOffset) : nullptr;
     if (use_bias && n > 0) {
         const int64_t n_pad = round_up(n, ic::kGemmTile);
         const int grid = (int)std::min<int64_t>((n_pad + 255) / 256, 4096);
-        if (absmax) hipLaunchKernelGGL(reset_bias_absmax, dim3(1), dim3(64), 0, st, absmax);
         hipLaunchKernelGGL(ic::make_bias, dim3(grid), dim3(256), 0, st,
                            (lambda != 0.0f) ? (const float *)index->util : (const float *)nullptr, mask_dev,
                            index->any_invalid ? (const uint8_t *)index->valid : (const uint8_t *)nullptr, n, n_pad,
-                           lambda, W.bias, absmax);
+                           lambda, W.bias);
     }
 
     for (int64_t q0 = 0; q0 < Q; q0 += W.q_chunk) {
@@ -908,7 +899,6 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             // between two fp32 summation orders of a dot product of unit vectors)
             a.redo = W.redo;
             a.thr_slack = 1e-4f;
-            a.bias_absmax = (const float *)absmax;
             scan_table[0][et][qg_idx][cpw - 1](dim3(S, nqb), st, a);
 
             ic::MergeArgs m{};
@@ -1307,7 +1297,7 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         const int64_t n_pad = round_up(n, ic::kGemmTile);
         hipLaunchKernelGGL(ic::make_bias, dim3((int)std::min<int64_t>((n_pad + 255) / 256, 4096)), dim3(256), 0, st,
                            (const float *)s->util, (const uint8_t *)nullptr, (const uint8_t *)nullptr, n, n_pad, lambda,
-                           s->ws.bias, (uint32_t *)nullptr);
+                           s->ws.bias);
     }
     // slices per list: about 12 tiles of 16 rows each, at most 16 slices
     const int64_t avg_tiles = std::max<int64_t>(1, n / std::max<int64_t>(1, ivf->K) / 16);
