@@ -99,7 +99,7 @@ constexpr int kTransBytes = 16 * kTransRow;
 
 // Dynamic LDS of scan_stream for a block of QG*16 queries with region capacity cap.
 __host__ __device__ constexpr size_t scan_lds_bytes(int qg, int cap) {
-    return (size_t)kScanWaves * qg * 64 * 16   // partial score tiles
+    return (size_t)kScanWaves * qg * 64 * 16 * (qg < 4 ? 2 : 1)   // partial score tiles (two sets when they are small)
            + (size_t)qg * 16 * cap * 8         // candidate regions
            + (size_t)qg * 16 * (8 + 4)         // threshold keys, region sizes
            + (qg < 4 ? (size_t)kScanWaves * kTransBytes : 0);  // transposition buffers (QG = 4: inside the partial tiles)
@@ -166,8 +166,12 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds_raw = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
     typedef f32x4 PartTile[kScanWaves][QG][64];
-    PartTile &part = *reinterpret_cast<PartTile *>(lds_raw);
-    uint64_t *regs = reinterpret_cast<uint64_t *>(lds_raw + sizeof(PartTile));  // [QB][cap]
+    // With one or two query groups the partial tiles are small and there are two sets of them, used
+    // by alternate tiles: a wavefront then cannot overwrite a set before every wavefront has passed
+    // the next tile's barrier, i.e. has read it, and one barrier per tile is enough.
+    constexpr bool kTwoSets = QG < 4;
+    PartTile *parts = reinterpret_cast<PartTile *>(lds_raw);
+    uint64_t *regs = reinterpret_cast<uint64_t *>(lds_raw + sizeof(PartTile) * (kTwoSets ? 2 : 1));  // [QB][cap]
     uint64_t *thr_key = regs + QB * (PILOT ? 0 : a.cap);                          // [QB]; a pilot has no regions
     uint32_t *cnt = reinterpret_cast<uint32_t *>(thr_key + QB);                   // [QB]
 
@@ -180,7 +184,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     // With QG = 4 the buffer is the wavefront's own 4 KB of the partial tiles: it is used before
     // the wavefront writes its partial sums, and nobody reads those until the barrier after.
     constexpr bool LINES = (CPW % 2 == 0);
-    uint8_t *trans = (QG == 4) ? reinterpret_cast<uint8_t *>(&part[w][0][0])
+    uint8_t *trans = (QG == 4) ? reinterpret_cast<uint8_t *>(&parts[0][w][0][0])
                                : reinterpret_cast<uint8_t *>(cnt + QB) + w * kTransBytes;
     static_assert(QG < 4 || sizeof(f32x4) * QG * 64 >= (size_t)kTransBytes, "partial tiles hold the buffer");
     const int r16 = lane & 15;  // row within tile (A operand) / query within group (B, D)
@@ -328,10 +332,13 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     for (int b = 0; b + 1 < kStages; ++b) load_stage(t + b * S, st[b]);
     const int64_t my_tiles = (s < ntiles) ? (ntiles - s + S - 1) / S : 0;
 
+    int set = 0;   // which set of partial tiles this tile uses
     for (int64_t it = 0; it < my_tiles; it += kStages) {
 #pragma unroll
         for (int b = 0; b < kStages; ++b) {
             {
+                PartTile &part = parts[kTwoSets ? set : 0];
+                set ^= 1;
                 load_stage(t + (kStages - 1) * S, st[(b + kStages - 1) % kStages]);
                 const Stage &cur = st[b];
 
@@ -405,7 +412,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                     sum += part[2][w][lane];
                     sum += part[3][w][lane];
                 }
-                __syncthreads();  // the partial tiles may be overwritten from here on
+                if (!kTwoSets) __syncthreads();  // the partial tiles may be overwritten from here on
 
                 if (w < QG) {
                     // first of this lane's 4 rows; a pilot's are sampled rows i0, i0 + ntiles, ...
