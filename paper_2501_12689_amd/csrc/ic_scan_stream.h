@@ -5,8 +5,9 @@
 // store from HBM once.
 //
 // Shape of the computation
-//   * A workgroup (4 wavefronts) owns slice s of the cache: the 16-row tiles
-//     s, s+S, s+2S, ...  and one block of QG*16 queries.
+//   * A workgroup (4 wavefronts) owns slice s of the cache, a contiguous range of
+//     16-row tiles (a pilot: the tiles s, s+S, s+2S, ... of its sample), and one
+//     block of QG*16 queries.
 //   * The embedding dimension is split over the 4 wavefronts: wavefront w owns
 //     CPW consecutive 64-byte chunks of every row.  Its share of the query block
 //     stays in registers for the whole kernel (QG*CPW 16-byte fragments).  The
@@ -327,10 +328,25 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     // Tiles past the end of the slice (when its tile count is not a multiple of kStages) are
     // processed like any other: their loads are clamped and all their rows fall past
     // last_row, so they contribute no candidate.
-    int64_t t = s;
+    // Which tiles a slice takes.  A full scan gives slice s the contiguous range of tiles
+    // [s * per, (s + 1) * per): every workgroup then reads one sequential stream, and the streams are
+    // spread over the whole store.  (Tiles s, s + S, s + 2S, ... make all workgroups walk the store side
+    // by side, inside the same 16 * S rows at any time; the memory system serves that 2 % slower for
+    // 1.5 KB rows and 9 % slower for 1 KB rows.)  The selection does not depend on how the tiles are
+    // dealt.  A pilot keeps the interleaved order: its tiles are samples spread over the store anyway.
+    constexpr bool kBlocked = !PILOT;
+    const int64_t per = (ntiles + S - 1) / S;
+    const int64_t mine0 = (int64_t)s * per;   // kBlocked: the slice's first tile
+    const int64_t my_tiles = kBlocked ? (mine0 < ntiles ? (ntiles - mine0 < per ? ntiles - mine0 : per) : 0)
+                                      : ((s < ntiles) ? (ntiles - s + S - 1) / S : 0);
+    auto tile_at = [&](int64_t j) -> int64_t {   // the j-th tile this slice visits; past its end: a tile no row is in
+        if (j >= my_tiles) return ntiles + s;
+        return kBlocked ? mine0 + j : s + j * S;
+    };
+    int64_t j = 0;
+    int64_t t = tile_at(0);
 #pragma unroll
-    for (int b = 0; b + 1 < kStages; ++b) load_stage(t + b * S, st[b]);
-    const int64_t my_tiles = (s < ntiles) ? (ntiles - s + S - 1) / S : 0;
+    for (int b = 0; b + 1 < kStages; ++b) load_stage(tile_at(b), st[b]);
 
     int set = 0;   // which set of partial tiles this tile uses
     for (int64_t it = 0; it < my_tiles; it += kStages) {
@@ -339,7 +355,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
             {
                 PartTile &part = parts[kTwoSets ? set : 0];
                 set ^= 1;
-                load_stage(t + (kStages - 1) * S, st[(b + kStages - 1) % kStages]);
+                load_stage(tile_at(j + kStages - 1), st[(b + kStages - 1) % kStages]);
                 const Stage &cur = st[b];
 
                 // operand fragments: lane (r16, c4) holds bytes [16*c4, 16*c4 + 16) of chunk c of row r16
@@ -473,7 +489,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
                             if (((pend >> v) & 1u) && !(key[v] > thr_k)) pend &= ~(1u << v);
                     }
                 }
-                t += S;
+                t = tile_at(++j);
             }
         }
     }
