@@ -16,7 +16,8 @@
 namespace ic {
 
 constexpr int kMergeKeys = 2048;
-constexpr int kMergeMaxSegs = 64;  // segments one workgroup can take
+constexpr int kMergeMaxSegs = 64;  // segments one workgroup takes when they may be full
+constexpr int kMergeWideSegs = 1024;  // most segments one workgroup can take (sparse segments: one level for all slices)
 
 struct MergeArgs {
     const uint64_t *src;        // keys of query q start at src + q * q_stride
@@ -29,7 +30,7 @@ struct MergeArgs {
     const int32_t *seg_counts;
     const int32_t *total_counts;
     int nseg;                   // segments per query
-    int segs_per_wg;            // <= kMergeMaxSegs
+    int segs_per_wg;            // <= kMergeWideSegs
     int k;
     uint64_t *dst;              // non-final: lists [Q][gridDim.y][k]
     float *out_scores;          // final: [Q][k], or NULL
@@ -110,8 +111,9 @@ __device__ __forceinline__ void sort_buffer(uint64_t *buf, int tid) {
 
 __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     __shared__ uint64_t buf[kMergeKeys];
-    __shared__ int seg_cnt[kMergeMaxSegs];
-    __shared__ int seg_off[kMergeMaxSegs + 1];
+    __shared__ int seg_cnt[kMergeWideSegs];
+    __shared__ int seg_off[kMergeWideSegs + 1];
+    __shared__ int wave_tot[4];
     __shared__ int kept;
     __shared__ int self_pos;
     const int tid = threadIdx.x;
@@ -120,26 +122,43 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     if (a.only_flagged && a.only_flagged[q >> 6] == 0) return;
     const int seg0 = g * a.segs_per_wg;
 
-    if (tid < a.segs_per_wg) {
-        const int seg = seg0 + tid;
+    // keys in use per segment and their exclusive prefix sums: thread t owns the kPer consecutive
+    // segments from kPer * t on; wavefronts combine by shuffles, the four wavefronts through LDS
+    constexpr int kPer = kMergeWideSegs / 256;
+    int mine[kPer], run = 0;
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+        const int sl = kPer * tid + e, seg = seg0 + sl;
         int c = 0;
-        if (seg < a.nseg) {
+        if (sl < a.segs_per_wg && seg < a.nseg) {
             if (a.seg_counts) c = a.seg_counts[(int64_t)q * a.nseg + seg];
             else if (a.total_counts) c = a.total_counts[q] - seg * a.seg_cap;
             else c = a.seg_cap;
             c = c < 0 ? 0 : (c > a.seg_cap ? a.seg_cap : c);
         }
-        seg_cnt[tid] = c;
+        mine[e] = c;
+        run += c;
     }
+    int incl = run;   // inclusive sum over the lanes of this wavefront
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        const int o = __shfl_up(incl, m, kWave);
+        if ((tid & 63) >= m) incl += o;
+    }
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
     __syncthreads();
-    if (tid == 0) {
-        int acc = 0;
-        for (int s = 0; s < a.segs_per_wg; ++s) {
-            seg_off[s] = acc;
-            acc += seg_cnt[s];
+    int before = incl - run;
+    for (int w = 0; w < (tid >> 6); ++w) before += wave_tot[w];
+#pragma unroll
+    for (int e = 0; e < kPer; ++e) {
+        const int sl = kPer * tid + e;
+        if (sl < a.segs_per_wg) {
+            seg_cnt[sl] = mine[e];
+            seg_off[sl] = before;
         }
-        seg_off[a.segs_per_wg] = acc;
+        before += mine[e];
     }
+    if (tid == 255) seg_off[a.segs_per_wg] = before;   // the last thread's running sum is the total
     __syncthreads();
     const int total = seg_off[a.segs_per_wg];
     const uint64_t *src = a.src + (int64_t)q * a.q_stride;
@@ -158,14 +177,21 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
     do {
         const int room = kMergeKeys - have;
         const int take = total - consumed < room ? total - consumed : room;
-        if (take == total) {  // everything at once: all segments in parallel, a few threads each
-            const int tps = 256 / a.segs_per_wg;  // threads per segment (segs_per_wg <= 64)
+        if (take == total && a.segs_per_wg <= 256) {  // everything at once: all segments in parallel, a few threads each
+            const int tps = 256 / a.segs_per_wg;  // threads per segment
             const int s = tid / tps;
             if (s < a.segs_per_wg) {
                 const int c = seg_cnt[s];
                 const uint64_t *sp = src + (int64_t)(seg0 + s) * a.seg_stride;
                 uint64_t *dp = buf + seg_off[s];
                 for (int idx = tid % tps; idx < c; idx += tps) dp[idx] = fetch(sp, idx);
+            }
+        } else if (take == total) {  // more segments than threads (sparse ones): a thread takes several
+            for (int s = tid; s < a.segs_per_wg; s += 256) {
+                const int c = seg_cnt[s];
+                const uint64_t *sp = src + (int64_t)(seg0 + s) * a.seg_stride;
+                uint64_t *dp = buf + seg_off[s];
+                for (int idx = 0; idx < c; ++idx) dp[idx] = fetch(sp, idx);
             }
         } else {  // keys [consumed, consumed + take) of the sequence: find each key's segment
             for (int e = tid; e < take; e += 256) {

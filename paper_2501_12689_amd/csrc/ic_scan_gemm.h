@@ -854,15 +854,12 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     }
 }
 
-// Zero the slice maxima before a pilot launch of scan_gemm.
-__global__ void gemm_pilot_reset(uint64_t *keys, int64_t count) {
+// One launch before a tiled search: zero the slice maxima of the pilot, and the per-query counters,
+// the redo flags and the list of overflowed tiles of the selection launch (count >= nq >= nblk).
+__global__ void gemm_reset(uint64_t *keys, int64_t count, int32_t *gcount, int nq, int32_t *redo, int nblk,
+                           uint32_t *over_n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) keys[i] = 0ull;
-}
-
-// Zero the per-query counters and the redo flags before a scan_gemm launch.
-__global__ void gemm_reset(int32_t *gcount, int nq, int32_t *redo, int nblk, uint32_t *over_n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nq) gcount[i] = 0;
     if (i < nblk) redo[i] = 0;
     if (i == 0) *over_n = 0u;

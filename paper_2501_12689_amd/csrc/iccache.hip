@@ -788,6 +788,7 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
         // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
         // k rows, so the full scan may start from it.
         const int gemm_grid = std::max(8, index->compute_units / 8 * 8);
+        bool sparse_regions = false;   // the streaming pilot leaves so few candidates that one merge level will do
         ic::GemmArgs g{};
         if (gemm) {
             g.store = index->rows;
@@ -826,8 +827,8 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             p.pilot_out = W.pilot_keys;
             p.pilot_stride = kPilotSlices;
             const int64_t nkeys = (int64_t)qc * kPilotSlices;
-            hipLaunchKernelGGL(ic::gemm_pilot_reset, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, st,
-                               W.pilot_keys, nkeys);
+            hipLaunchKernelGGL(ic::gemm_reset, dim3((unsigned)((nkeys + 255) / 256)), dim3(256), 0, st, W.pilot_keys, nkeys,
+                               W.gcount, qc, W.redo, (qc + 63) / 64, W.over);
             if (et == 0) launch_gemm<0, true>(gemm_grid, st, p);
             else launch_gemm<1, true>(gemm_grid, st, p);
             ic::MergeArgs m{};
@@ -854,6 +855,7 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             p.S = kPilotSlices;
             const int64_t by_regions = std::max<int64_t>(4, 8 * (int64_t)S / k);
             p.tile_mul = (int)std::min<int64_t>(std::min<int64_t>(128, ntiles / kPilotSlices), by_regions);
+            sparse_regions = (int64_t)p.tile_mul * k <= ic::kMergeKeys / 2;   // about tile_mul * k rows pass per query
             scan_table[1][et][qg_idx][cpw - 1](dim3(kPilotSlices, nqb), st, p);
             ic::MergeArgs m{};
             m.src = W.pilot_keys;
@@ -874,8 +876,6 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
         if (gemm) {
             const int gcap = index->gemm_list_cap_override ? index->gemm_list_cap_override : gemm_list_cap(k);
             const int nblk64 = (qc + 63) / 64;
-            hipLaunchKernelGGL(ic::gemm_reset, dim3((qc + 255) / 256), dim3(256), 0, st, W.gcount, qc,
-                               W.redo, nblk64, W.over);
             index->last_nblk64 = nblk64;
             g.thr_init = W.thr_init;
             g.glist = W.glist;
@@ -929,6 +929,9 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
         // it may (fewer, smaller lists for the next level; a rare full group is merged in rounds);
         // without one they may be full, and more workgroups with one round each are faster
         m.segs_per_wg = a.thr_init ? ic::kMergeMaxSegs : std::min(ic::kMergeMaxSegs, ic::kMergeKeys / cap);
+        // few candidates in all (a pilot that sampled densely, on a small store): one workgroup per query
+        // takes every slice, one launch instead of two (more than it can sort at once is merged in rounds)
+        if (sparse_regions && S <= ic::kMergeWideSegs) m.segs_per_wg = S;
         run_merge(index, W, m, qc, k, out_s, out_i, gemm ? W.redo : nullptr, fo);
     }
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
