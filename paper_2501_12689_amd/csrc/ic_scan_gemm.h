@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             else off_r[u] = (uint32_t)(r * a.row_bytes + cg * 16);
         }
     };
-    auto issue = [&](int slot) {  // request the cursor's step into an LDS slot
+    auto issue = [&](int slot, auto half_c) {  // request the cursor's step into an LDS slot
         uint8_t *dst = lds + slot * kSlot + w * (16 * kGemmHalfBytes);  // wave-uniform
         const uint8_t *ra = c_rows + c_hs * kGemmHalfBytes;
         const uint8_t *qa = c_q + c_hs * kGemmHalfBytes;
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         for (int u = 0; u < 2; ++u)
             __builtin_amdgcn_global_load_lds((gptr_t)(ra + off_r[u]), (lptr_t)(dst + u * 128 * kGemmHalfBytes), 16, 0, 0);
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < (decltype(half_c)::value ? 1 : 2); ++u)   // kHalf: the second half of the block is never read
             __builtin_amdgcn_global_load_lds((gptr_t)(qa + off_q[u]),
                                              (lptr_t)(dst + (kGemmTile + u * 128) * kGemmHalfBytes), 16, 0, 0);
     };
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
 #pragma unroll
     for (int sl = 0; sl < kGemmSlots; ++sl) {
         if (sl + 1 < kGemmSlots || !late) {
-            issue(sl);
+            issue(sl, std::false_type{});
             advance();
         }
     }
@@ -323,12 +323,19 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     asm volatile("" ::: "memory");
 
     int hslot = 0;  // ring slot of the step being computed
+    // At a step's barrier this wavefront's loads for the next step must have landed; those of the two
+    // steps after it (4 loads each; 3 when the second half of the query block is not copied) may be
+    // in flight.
+    auto wait_next_step = [&](auto half_c) {
+        if (decltype(half_c)::value) asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+    };
     // kDead: the batch is a single query block with at most 128 real queries and this wavefront's
     // 128 queries are all padding.  It keeps its part in the copies and the barriers and skips the
     // operand reads and the MFMAs, so such a batch costs half the matrix work and the scan is bound
     // by reading the store.  (In a batch of several blocks only the last block can have such
     // wavefronts; they are not worth a second copy of the loop there.)
-    auto run_tiles = [&](auto late_c, auto dead_c) {
+    auto run_tiles = [&](auto late_c, auto dead_c, auto half_c) {
     constexpr bool kLate = decltype(late_c)::value;
     constexpr bool kDead = decltype(dead_c)::value;
     for (; tw.job < work; walk_next(tw)) {
@@ -434,7 +441,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         // step ahead of their use.
         auto half = [&](auto last_c, auto first_c) {
             constexpr bool kLast = decltype(last_c)::value;
-            if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1));  // the slot freed by the previous barrier
+            if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1), half_c);  // the slot freed by the previous barrier
             if (!kDead) {
                 read_frags(hslot, 1, fa[1], fb[1]);
                 mfma8(fa[0], fb[0], first_c);
@@ -448,7 +455,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             }
             __builtin_amdgcn_sched_barrier(0);
             if (kLate) advance();
-            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            wait_next_step(half_c);
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
@@ -469,7 +476,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (!kLate) issue(hslot);
+            if (!kLate) issue(hslot, half_c);
             const int nslot = (hslot + 1) & (kGemmSlots - 1);
             if (!kDead) {
                 if (!kLast) read_frags(nslot, 0, fa[0], fb[0]);
@@ -514,7 +521,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         auto half8 = [&](auto last_c, auto par_c) {
             constexpr bool kLast = decltype(last_c)::value;
             constexpr int kPar = decltype(par_c)::value;
-            if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1));  // the slot freed by the previous barrier
+            if (kLate) issue((hslot + kGemmSlots - 1) & (kGemmSlots - 1), half_c);  // the slot freed by the previous barrier
             if (!kDead) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
@@ -532,7 +539,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             }
             __builtin_amdgcn_sched_barrier(0);
             if (kLate) advance();
-            asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+            wait_next_step(half_c);
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
@@ -552,7 +559,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (!kLate) issue(hslot);
+            if (!kLate) issue(hslot, half_c);
             const int nslot = (hslot + 1) & (kGemmSlots - 1);
             if (!kDead) {
                 if (!kLast) read_frags8(nslot, ga[kPar ^ 1], gb[kPar ^ 1]);
@@ -839,9 +846,10 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     }
     };
     const bool dead = half_block && wn == 1;  // wave-uniform; these are wavefronts 4-7, the late ones
-    if (dead) run_tiles(std::true_type{}, std::true_type{});
-    else if (late) run_tiles(std::true_type{}, std::false_type{});
-    else run_tiles(std::false_type{}, std::false_type{});
+    if (dead) run_tiles(std::true_type{}, std::true_type{}, std::true_type{});
+    else if (half_block) run_tiles(std::false_type{}, std::false_type{}, std::true_type{});
+    else if (late) run_tiles(std::true_type{}, std::false_type{}, std::false_type{});
+    else run_tiles(std::false_type{}, std::false_type{}, std::false_type{});
 
     // the last tile's parked candidates; the direct loads of the unused extra stage must have landed
     // before the workgroup gives up its LDS

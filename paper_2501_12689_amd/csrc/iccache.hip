@@ -790,6 +790,7 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
         const int gemm_grid = std::max(8, index->compute_units / 8 * 8);
         bool sparse_regions = false;   // the streaming pilot leaves so few candidates that one merge level will do
         ic::GemmArgs g{};
+        int64_t gemm_stride = 1;       // row stride of the tiled scan's pilot
         if (gemm) {
             g.store = index->rows;
             g.n = n;
@@ -822,6 +823,7 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             // (256 queries x stride * k rows per query x 256 / n rows): the per-tile hit list holds 96
             const int64_t by_hits = g.ntiles * 3 / (32 * (int64_t)k);
             p.row_stride = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, by_hits), g.ntiles / std::max(k, 64)));
+            gemm_stride = p.row_stride;
             p.n_sampled = (n + p.row_stride - 1) / p.row_stride;
             p.ntiles = (p.n_sampled + ic::kGemmTile - 1) / ic::kGemmTile;
             p.pilot_out = W.pilot_keys;
@@ -908,7 +910,10 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             m.seg_stride = m.seg_cap;
             m.total_counts = W.gcount;
             m.nseg = (gcap + m.seg_cap - 1) / m.seg_cap;
-            m.segs_per_wg = 1;
+            // about stride * k keys per query passed the pilot's threshold: when that is well inside one
+            // sort, one workgroup per query takes the whole list (one launch; a longer list is merged in
+            // rounds), otherwise the segments are sorted side by side and merged by a second level
+            m.segs_per_wg = (gemm_stride * k <= kGemmListSeg / 2) ? m.nseg : 1;
             run_merge(index, W, m, qc, k, out_s, out_i, nullptr, fo);
         } else {
             if (!timer.start()) return IC_ERR_DEVICE;
@@ -932,6 +937,8 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
         // few candidates in all (a pilot that sampled densely, on a small store): one workgroup per query
         // takes every slice, one launch instead of two (more than it can sort at once is merged in rounds)
         if (sparse_regions && S <= ic::kMergeWideSegs) m.segs_per_wg = S;
+        // after the tiled scan only flagged blocks have regions at all (nearly always none): one launch
+        if (gemm && S <= ic::kMergeWideSegs) m.segs_per_wg = S;
         run_merge(index, W, m, qc, k, out_s, out_i, gemm ? W.redo : nullptr, fo);
     }
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
