@@ -67,7 +67,11 @@ typedef enum {
  * Bytes of device memory an index needs: the embedding store (rows padded to a
  * multiple of 128 B), per-row scale, utility and validity arrays, the prepared query
  * block, and the top-k workspace for searches of up to max_queries queries per
- * call with k <= max_k.  Returns 0 if an argument is out of range.
+ * call with k <= max_k.  With max_queries >= 65 the index also keeps a second copy of
+ * the store, ordered for the large-batch scan (as large as the store itself, kept up to
+ * date by ic_index_append and ic_index_compact): an index that will only ever see
+ * batches of up to 64 queries should say so and gets by with half the memory.
+ * Returns 0 if an argument is out of range.
  */
 size_t ic_workspace_bytes(int32_t d, ic_dtype store, int64_t capacity_rows,
                           int64_t max_queries, int32_t max_k);

@@ -23,6 +23,16 @@
 //     step p (0, 1); rows and queries use the same mapping, so each MFMA pairs equal coordinates
 //     (the order of the coordinates inside a dot product is free).  bf16: one
 //     v_mfma_f32_32x32x16_bf16 per granule pair; fp8: two v_mfma_f32_32x32x16_fp8_fp8 (8 bytes each).
+//   * Where the operands come from.  Selection launches (and their second launch) read both operands
+//     from step-major copies ("panels"): tile t of 256 rows is stored as its pipeline steps one
+//     after the other, a step being 16 KB = 64 B of each of the 256 rows with the granules already in
+//     their swizzled positions, i.e. exactly the image the step has in LDS.  A direct load then moves
+//     1 KB of contiguous memory (eight full 128-byte lines) instead of half a line of each of 16
+//     rows, which halves the requests the L2 has to answer (it served 64-byte requests at 140 G/s
+//     when the rows were read from the row-major store, and a copy-only pipeline measured 950 against
+//     630 cycles per step).  The panel of the store is written by to_panel() when rows are appended
+//     or moved, the panel of the query block once per search.  Pilot and row-maximum launches
+//     read the row-major store (a pilot's rows are a strided sample).
 //   * Workgroups are persistent and XCD-aware: workgroup id modulo 8 is the XCD it runs on; an XCD
 //     owns a group of query blocks small enough to stay in its L2 and a class of row tiles, and
 //     walks query blocks fastest so that a row tile is used by consecutive tiles.  The load
@@ -63,6 +73,8 @@ constexpr int kGemmSlots = 4;         // LDS ring: pipeline steps resident or in
 constexpr int kGemmThreads = 512;     // 8 wavefronts, two per SIMD: one issues MFMAs while the other issues loads
 
 struct GemmArgs {
+    const uint8_t *panel;    // selection launches: step-major copy of the store, [ceil(n/256)] tiles of 256 * row_bytes bytes
+    const uint8_t *qpanel;   // selection launches: step-major copy of the prepared queries, [nqb] tiles
     const uint8_t *store;    // [n] rows, row_bytes apart
     int64_t n;
     int row_bytes;           // multiple of 128
@@ -120,6 +132,9 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     // additions per lane and tile less, at a time when the matrix pipe is idle).  The bias of a tile is
     // fetched during the tile before it.  fp8 scores need the two scales first and keep the addition.
     constexpr bool kBiasInit = ET == 0 && !ROWMAX;
+    // selection launches read both operands from the step-major copies (a tile covers the same byte
+    // range in either layout, so a tile's base address is computed the same way)
+    constexpr bool kPanel = !PILOT && !ROWMAX;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_dyn[];
     uint8_t *lds = static_cast<uint8_t *>(__builtin_assume_aligned(lds_dyn, 16));
     constexpr int kSlot = 2 * kGemmTile * kGemmHalfBytes;  // 32 KB: 256 rows then 256 queries, 64 B each
@@ -171,14 +186,14 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             t.qb = (int)e.y;
             t.row0 = (int64_t)e.x * kGemmTile;
         }
-        t.q_base = a.qbuf + (size_t)t.qb * kGemmTile * a.row_bytes;
+        t.q_base = (kPanel ? a.qpanel : a.qbuf) + (size_t)t.qb * kGemmTile * a.row_bytes;
         if (PILOT) {
             t.row0 = rclass + gr * rl;   // the tile's index: its row r is row r * ntiles + row0 of the sample
             t.rows_base = a.store + t.row0 * a.row_stride * a.row_bytes;
             t.last = (int)((a.n_sampled - 1 - t.row0) / a.ntiles);   // 0 .. 255 since ntiles = ceil(n_sampled / 256)
         } else {
             if (!AGAIN) t.row0 = (rclass + gr * rl) * kGemmTile;
-            t.rows_base = a.store + t.row0 * a.row_bytes;
+            t.rows_base = (kPanel ? a.panel : a.store) + t.row0 * a.row_bytes;
             const int64_t last = a.n - 1 - t.row0;
             t.last = (int)(last < kGemmTile - 1 ? last : kGemmTile - 1);
         }
@@ -209,7 +224,9 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     // ---- copy plan.  One direct load moves 16 rows x 64 B per wavefront: lane l lands at the
     // wavefront's LDS base + 16*l, i.e. row l/4, position l%4, and therefore fetches granule
     // (l%4) ^ ((row/4)%4).  Per pipeline step a wavefront issues 4 loads: row groups w and w+8 (of 16
-    // rows each) of the cached rows and the same groups of the queries.
+    // rows each) of the cached rows and the same groups of the queries.  From a panel the same
+    // load reads 1 KB of contiguous memory: lane l fetches byte 16*l of the group's kilobyte (rows
+    // past the end of the store are zeros there, so nothing is clamped).
     typedef const void __attribute__((address_space(1))) *gptr_t;
     typedef void __attribute__((address_space(3))) *lptr_t;
     const int crow = lane >> 2;
@@ -238,15 +255,31 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             else off_r[u] = (uint32_t)(r * a.row_bytes + cg * 16);
         }
     };
+    const uint32_t lane16 = (uint32_t)lane * 16u;
     auto issue = [&](int slot, auto half_c) {  // request the cursor's step into an LDS slot
         uint8_t *dst = lds + slot * kSlot + w * (16 * kGemmHalfBytes);  // wave-uniform
+        constexpr int kQueryLoads = decltype(half_c)::value ? 1 : 2;   // kHalf: the second half of the block is never read
+        if (kPanel) {
+            // step c_hs of a tile is the 16 KB from c_hs * 16 KB on; row group g is its g-th kilobyte
+            const uint8_t *ra = c_rows + (size_t)c_hs * (kGemmTile * kGemmHalfBytes) + w * (16 * kGemmHalfBytes);
+            const uint8_t *qa = c_q + (size_t)c_hs * (kGemmTile * kGemmHalfBytes) + w * (16 * kGemmHalfBytes);
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                __builtin_amdgcn_global_load_lds((gptr_t)(ra + u * 128 * kGemmHalfBytes + lane16),
+                                                 (lptr_t)(dst + u * 128 * kGemmHalfBytes), 16, 0, 0);
+#pragma unroll
+            for (int u = 0; u < kQueryLoads; ++u)
+                __builtin_amdgcn_global_load_lds((gptr_t)(qa + u * 128 * kGemmHalfBytes + lane16),
+                                                 (lptr_t)(dst + (kGemmTile + u * 128) * kGemmHalfBytes), 16, 0, 0);
+            return;
+        }
         const uint8_t *ra = c_rows + c_hs * kGemmHalfBytes;
         const uint8_t *qa = c_q + c_hs * kGemmHalfBytes;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
             __builtin_amdgcn_global_load_lds((gptr_t)(ra + off_r[u]), (lptr_t)(dst + u * 128 * kGemmHalfBytes), 16, 0, 0);
 #pragma unroll
-        for (int u = 0; u < (decltype(half_c)::value ? 1 : 2); ++u)   // kHalf: the second half of the block is never read
+        for (int u = 0; u < kQueryLoads; ++u)
             __builtin_amdgcn_global_load_lds((gptr_t)(qa + off_q[u]),
                                              (lptr_t)(dst + (kGemmTile + u * 128) * kGemmHalfBytes), 16, 0, 0);
     };
@@ -859,6 +892,28 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     for (uint32_t e = tid; e < parked; e += kGemmThreads) {
         const uint32_t q = park_q[e];
         append_global(q, park_key[e], atomicAdd(a.gcount + q, 1));
+    }
+}
+
+// Step-major copy of rows [first, last) of a row-major array (row_bytes apart, a multiple of 64):
+// tile t = 256 rows is stored as row_bytes / 64 steps of 16 KB, step s holding bytes [64 s, 64 s + 64)
+// of the tile's rows, 64 B per row, with granule g (16 bytes) of row r at position g ^ ((r / 4) % 4):
+// the image scan_gemm keeps of the step in LDS.  Rows [last, fill_to) are written as zeros (the rest
+// of the last tile: fill_to = last rounded up to a multiple of 256).  One thread per granule.
+__global__ __launch_bounds__(256) void to_panel(const uint8_t *__restrict__ rows, int row_bytes, int64_t first,
+                                                int64_t last, int64_t fill_to, uint8_t *__restrict__ panel) {
+    const int gpr = row_bytes >> 4;   // granules per row
+    const int64_t total = (fill_to - first) * gpr;
+    const int64_t tile_bytes = (int64_t)kGemmTile * row_bytes;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t i = first + idx / gpr;
+        const int gi = (int)(idx % gpr);
+        i32x4 v = {0, 0, 0, 0};
+        if (i < last) v = *reinterpret_cast<const i32x4 *>(rows + i * row_bytes + gi * 16);
+        const int r = (int)(i & (kGemmTile - 1));
+        const int s = gi >> 2, g = gi & 3;
+        uint8_t *dst = panel + (i >> 8) * tile_bytes + ((int64_t)s * kGemmTile + r) * kGemmHalfBytes + ((g ^ ((r >> 2) & 3)) << 4);
+        *reinterpret_cast<i32x4 *>(dst) = v;
     }
 }
 

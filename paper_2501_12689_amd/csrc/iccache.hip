@@ -70,12 +70,17 @@ struct Layout {
     int64_t cap_pad = 0;
     size_t off_rows = 0, off_scale = 0, off_util = 0, off_qbuf = 0, off_qscale = 0, off_regions = 0,
            off_counts = 0, off_list_a = 0, off_list_b = 0, off_consts = 0, off_bias = 0, off_pilot = 0, off_thr = 0, off_glist = 0, off_gcount = 0,
-           off_redo = 0, off_over = 0, off_valid = 0, off_blocks = 0, off_domain = 0, total = 0;
+           off_redo = 0, off_over = 0, off_valid = 0, off_blocks = 0, off_domain = 0, off_panel = 0, off_qpanel = 0,
+           total = 0;
+    bool panel = false;  // the store has a step-major copy for the tiled scan
     int64_t list_slots = 0;
     int q_rows = 0;  // rows of the prepared query block
 };
 
-bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int32_t max_k, Layout &L) {
+// with_panel = false: an index that is only ever scanned by the streaming kernels (the sorted copy behind
+// cluster pruning) goes without the step-major copy of its rows
+bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int32_t max_k, Layout &L,
+                 bool with_panel = true) {
     if (store != IC_STORE_BF16 && store != IC_STORE_FP8_E4M3) return false;
     if (d < 1 || capacity < 1 || max_q < 1 || max_k < 1 || max_k > IC_MAX_K) return false;
     if (capacity > (int64_t)1 << 31) return false;
@@ -114,6 +119,11 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_valid = take((size_t)L.cap_pad);                                          // persistent validity, 1 B/row
     L.off_blocks = take((size_t)(L.cap_pad / ic::kScanBlock + 2) * 8);              // compaction: block offsets
     L.off_domain = take((size_t)L.cap_pad * 4);                                      // sharing domain, 4 B/row
+    // the tiled scan reads both operands from step-major copies (see ic_scan_gemm.h): the store's, as large as
+    // the store itself, and the query block's
+    L.panel = gemm && with_panel;
+    L.off_panel = take(L.panel ? (size_t)L.cap_pad * (size_t)L.row_bytes : 0);
+    L.off_qpanel = take(L.panel ? (size_t)L.q_rows * (size_t)L.row_bytes : 0);
     L.total = off;
     return true;
 }
@@ -218,6 +228,7 @@ void launch_gemm_again(int grid, hipStream_t st, const ic::GemmArgs &a) {
 // the library's static device array instead.
 struct Workspace {
     uint8_t *qbuf = nullptr;        // prepared query block, [q_rows] rows in the store's format
+    uint8_t *qpanel = nullptr;      // its step-major copy for the tiled scan, or NULL
     float *qscale = nullptr;        // [q_rows]
     uint64_t *regions = nullptr;    // candidate keys per (query, slice)
     int32_t *counts = nullptr;
@@ -249,6 +260,7 @@ struct ic_index {
     int compute_units;
     int device;        // the GPU that was current at creation
     uint8_t *rows;
+    uint8_t *panel;        // step-major copy of rows for the tiled scan ([cap_pad / 256] tiles), or NULL
     float *scale;
     float *util;
     uint8_t *valid;        // [cap_pad] 1 = row is live, 0 = invalidated (evicted) and waiting for compaction
@@ -285,13 +297,13 @@ size_t ic_workspace_bytes(int32_t d, ic_dtype store, int64_t capacity_rows, int6
     return L.total;
 }
 
-ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t capacity_rows,
-                          int64_t max_queries, int32_t max_k, void *arena_dev, size_t arena_bytes,
-                          void *stream) {
+static ic_status create_index(ic_index **out, int32_t d, ic_dtype store, int64_t capacity_rows,
+                              int64_t max_queries, int32_t max_k, void *arena_dev, size_t arena_bytes,
+                              void *stream, bool with_panel) {
     if (!out || !arena_dev) return IC_ERR_INVALID_ARG;
     if (((uintptr_t)arena_dev % kAlign) != 0) return IC_ERR_INVALID_ARG;
     Layout L;
-    if (!make_layout(d, store, capacity_rows, max_queries, max_k, L)) return IC_ERR_INVALID_ARG;
+    if (!make_layout(d, store, capacity_rows, max_queries, max_k, L, with_panel)) return IC_ERR_INVALID_ARG;
     if (arena_bytes < L.total) return IC_ERR_CAPACITY;
     ic_index *ix = new (std::nothrow) ic_index();
     if (!ix) return IC_ERR_OOM;
@@ -313,6 +325,7 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     (void)hipGetLastError();
     uint8_t *base = (uint8_t *)arena_dev;
     ix->rows = base + L.off_rows;
+    ix->panel = L.panel ? base + L.off_panel : nullptr;
     ix->scale = (store == IC_STORE_FP8_E4M3) ? (float *)(base + L.off_scale) : nullptr;
     ix->util = (float *)(base + L.off_util);
     ix->valid = base + L.off_valid;
@@ -321,6 +334,7 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->domain = (int32_t *)(base + L.off_domain);
     Workspace &W = ix->ws;
     W.qbuf = base + L.off_qbuf;
+    W.qpanel = L.panel ? base + L.off_qpanel : nullptr;
     W.qscale = (float *)(base + L.off_qscale);
     W.regions = (uint64_t *)(base + L.off_regions);
     W.counts = (int32_t *)(base + L.off_counts);
@@ -344,6 +358,12 @@ ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t cap
     ix->consts_ready = false;
     *out = ix;
     return IC_OK;
+}
+
+ic_status ic_index_create(ic_index **out, int32_t d, ic_dtype store, int64_t capacity_rows,
+                          int64_t max_queries, int32_t max_k, void *arena_dev, size_t arena_bytes,
+                          void *stream) {
+    return create_index(out, d, store, capacity_rows, max_queries, max_k, arena_dev, arena_bytes, stream, true);
 }
 
 ic_status ic_index_destroy(ic_index *index) {
@@ -418,6 +438,18 @@ ic_status ic_index_tiled_scan_counts(ic_index *index, int64_t *tiles_again, int6
     return IC_OK;
 }
 
+// Bring the step-major copy of the store up to date for rows [first, last): they are copied, and the
+// rest of the last tile they touch is zeroed (rows past the end of the store must not hold stale
+// bytes: the tiled scan multiplies whole tiles).
+static void panel_rows(ic_index *index, int64_t first, int64_t last) {
+    if (last <= first) return;
+    const int64_t fill_to = round_up(last, ic::kGemmTile);
+    const int64_t granules = (fill_to - first) * (index->L.row_bytes / 16);
+    const int grid = (int)std::min<int64_t>((granules + 255) / 256, 65536);
+    hipLaunchKernelGGL(ic::to_panel, dim3(grid), dim3(256), 0, index->stream, (const uint8_t *)index->rows,
+                       index->L.row_bytes, first, last, fill_to, index->panel);
+}
+
 ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *util_dev, int64_t n,
                           int64_t *first_id) {
     if (!index || n < 0 || (n > 0 && !emb_dev)) return IC_ERR_INVALID_ARG;
@@ -439,6 +471,7 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
                        index->valid + at, n, (uint8_t)1);
     hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n * 4 + 255) / 256)), dim3(256), 0, index->stream,
                        (uint8_t *)(index->domain + at), n * 4, (uint8_t)0);  // new rows are shared with everyone
+    if (index->panel) panel_rows(index, at, at + n);
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     index->n += n;
     return IC_OK;
@@ -523,6 +556,7 @@ ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_si
     index->n = total;
     index->any_invalid = false;
     if (new_size) *new_size = total;
+    if (index->panel) panel_rows(index, 0, total);   // every surviving row may have moved
     return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
 }
 
@@ -674,7 +708,7 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
     // (measured on 100k-250k rows: 1.5 to 2 times faster than the streaming scan from 256 queries on,
     // about even at 128)
     auto gemm_for = [&](int64_t queries) {
-        return W.glist != nullptr && queries >= kGemmMinQueries &&
+        return W.glist != nullptr && index->panel != nullptr && W.qpanel != nullptr && queries >= kGemmMinQueries &&
                (ntiles >= kGemmMinTiles || (ntiles >= kGemmSmallTiles && queries > 128) ||
                 (ntiles >= kGemmTinyTiles && queries > 128 && k <= 16));
     };
@@ -736,6 +770,12 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
                                    (const float *)nullptr, (float *)nullptr);
         }
 
+        if (gemm) {   // the tiled scan reads the query block from its step-major copy
+            const int64_t granules = (int64_t)q_pad * (L.row_bytes / 16);
+            hipLaunchKernelGGL(ic::to_panel, dim3((unsigned)std::min<int64_t>((granules + 255) / 256, 65536)), dim3(256), 0, st,
+                               (const uint8_t *)W.qbuf, L.row_bytes, (int64_t)0, (int64_t)q_pad, (int64_t)q_pad, W.qpanel);
+        }
+
         if (n == 0) {  // nothing to scan: the merge of zero segments writes the padding rows
             ic::MergeArgs m{};
             m.src = W.regions;
@@ -793,6 +833,8 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
         int64_t gemm_stride = 1;       // row stride of the tiled scan's pilot
         if (gemm) {
             g.store = index->rows;
+            g.panel = index->panel;
+            g.qpanel = W.qpanel;
             g.n = n;
             g.row_bytes = L.row_bytes;
             g.row_scale = index->scale;
@@ -1065,7 +1107,8 @@ struct IvfLayout {
 bool make_ivf_layout(const ic_index *base, int32_t K, int32_t max_probe, IvfLayout &V) {
     if (!base || K < 1 || K > (1 << 20) || max_probe < 1 || max_probe > IC_MAX_K) return false;
     V.cent_bytes = ic_workspace_bytes(base->d, base->store, K, kIvfCentQueries, max_probe);
-    V.sorted_bytes = ic_workspace_bytes(base->d, base->store, base->capacity, base->max_q, base->max_k);
+    Layout LS;   // the sorted copy is only scanned list by list (streaming kernel): no step-major copy of its rows
+    V.sorted_bytes = make_layout(base->d, base->store, base->capacity, base->max_q, base->max_k, LS, false) ? LS.total : 0;
     if (!V.cent_bytes || !V.sorted_bytes) return false;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -1147,8 +1190,8 @@ ic_status ic_ivf_create(ic_ivf **out, ic_index *base, int32_t K, int32_t max_pro
     ic_status st = ic_index_create(&v->cent, base->d, base->store, K, kIvfCentQueries, max_probe, p + V.off_cent,
                                    V.cent_bytes, base->stream);
     if (st == IC_OK)
-        st = ic_index_create(&v->sorted, base->d, base->store, base->capacity, base->max_q, base->max_k,
-                             p + V.off_sorted, V.sorted_bytes, base->stream);
+        st = create_index(&v->sorted, base->d, base->store, base->capacity, base->max_q, base->max_k,
+                          p + V.off_sorted, V.sorted_bytes, base->stream, false);
     if (st != IC_OK) {
         if (v->cent) ic_index_destroy(v->cent);
         delete v;

@@ -281,3 +281,50 @@ def test_large_batch_queries_that_are_stored_rows(pkg, oracle, list_cap):
         parity.check_batch("bf16", s, i, E.numpy(), U.numpy(), M.numpy(), Qm.numpy(), k, cfg.lam, f"stored rows k={k}",
                            queries=range(0, cfg.Q, 17))
     ix.close()
+
+
+@pytest.mark.parametrize("store", ["bf16", "fp8"])
+def test_tiled_scan_after_ragged_appends_and_compaction(pkg, oracle, store):
+    """The tiled scan reads a step-major copy of the store that every append and every compaction has
+    to keep in step with the rows: appends of odd sizes that start and end inside tiles of 256 rows,
+    a ragged last tile, rows squeezed out by a compaction, and appends after it."""
+    _say(f"step-major copy kept up to date, {store}")
+    N, d, Q, k = 140000, 160, 200, 24
+    cfg = workloads.Config("P", N=N, d=d, clusters=24, Q=Q, k=k, store=store, zipf=1.1, lam=0.1, util="uniform",
+                           seed=8600)
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, _ = wl.rows(0, N)
+    Qm = wl.queries()
+    sid = pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3
+    ix = pkg.Index(d, N + 5000, sid, Q, k, DEV)
+    at = 0
+    for n in (1, 254, 2, 255, 257, 1000, 37, 70001, 3, 511, N):   # the last one takes what is left
+        n = min(n, N - at)
+        ix.append(E[at:at + n].to(DEV), U[at:at + n].to(DEV))
+        at += n
+    assert at == N and len(ix) == N
+    qd = Qm.to(DEV)
+    s, i = ix.search(qd, k, cfg.lam)
+    torch.cuda.synchronize()
+    sample = list(range(0, Q, 17)) + [Q - 1]
+    parity.check_batch(store, s.cpu().numpy(), i.cpu().numpy(), E.numpy(), U.numpy(), None, Qm.numpy(), k, cfg.lam,
+                       "ragged appends", queries=sample)
+    # evict every third row, squeeze, search, append, search
+    gone = np.arange(0, N, 3, dtype=np.int64)
+    ix.invalidate(torch.from_numpy(gone).to(DEV))
+    ix.compact()
+    keep = np.setdiff1d(np.arange(N), gone)
+    s2, i2 = ix.search(qd, k, cfg.lam)
+    torch.cuda.synchronize()
+    parity.check_batch(store, s2.cpu().numpy(), i2.cpu().numpy(), E.numpy()[keep], U.numpy()[keep], None, Qm.numpy(), k,
+                       cfg.lam, "after compaction", queries=sample)
+    more = workloads.Workload(cfg.scaled(seed=8601), "cpu").rows(0, 4097)
+    ix.append(more[0][:1].to(DEV), more[1][:1].to(DEV))
+    ix.append(more[0][1:].to(DEV), more[1][1:].to(DEV))
+    s3, i3 = ix.search(qd, k, cfg.lam)
+    torch.cuda.synchronize()
+    E3 = np.concatenate([E.numpy()[keep], more[0].numpy()])
+    U3 = np.concatenate([U.numpy()[keep], more[1].numpy()])
+    parity.check_batch(store, s3.cpu().numpy(), i3.cpu().numpy(), E3, U3, None, Qm.numpy(), k, cfg.lam,
+                       "appends after compaction", queries=sample)
+    ix.close()
