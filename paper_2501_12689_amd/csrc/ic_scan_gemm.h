@@ -18,11 +18,13 @@
 //     then cover all sixteen 16-byte slots of the 256-byte bank span exactly once.  A direct load
 //     writes lane l of a wavefront to (wave's LDS base + 16*l), i.e. 16 rows x 4 granules per
 //     instruction, so the swizzle is applied on the global side: the lane fetches the granule that
-//     belongs at its position.
+//     belongs at its position (the step-major copies described below hold the granules in that
+//     order already).
 //   * Operand mapping: lane (r = lane%32, h = lane/32) reads granule 2*p + h of row r for MFMA
 //     step p (0, 1); rows and queries use the same mapping, so each MFMA pairs equal coordinates
 //     (the order of the coordinates inside a dot product is free).  bf16: one
-//     v_mfma_f32_32x32x16_bf16 per granule pair; fp8: two v_mfma_f32_32x32x16_fp8_fp8 (8 bytes each).
+//     v_mfma_f32_32x32x16_bf16 per granule pair; fp8: one v_mfma_f32_32x32x64_f8f6f4 per step, whose
+//     32-byte operand is both of the lane's granules.
 //   * Where the operands come from.  Selection launches (and their second launch) read both operands
 //     from step-major copies ("panels"): tile t of 256 rows is stored as its pipeline steps one
 //     after the other, a step being 16 KB = 64 B of each of the 256 rows with the granules already in
