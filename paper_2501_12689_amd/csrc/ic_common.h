@@ -39,6 +39,21 @@ __device__ __forceinline__ uint64_t make_key(float s, uint32_t id) {
 __device__ __forceinline__ float key_score(uint64_t key) { return score_of_ord((uint32_t)(key >> 32)); }
 __device__ __forceinline__ uint32_t key_id(uint64_t key) { return 0xFFFFFFFFu - (uint32_t)key; }
 
+// ---------------------------------------------------------------------------
+// Step-major copy ("panel") of an array of rows, the layout the tiled scan reads: tile t = 256 rows
+// is stored as row_bytes / 64 steps of 16 KB, step s holding bytes [64 s, 64 s + 64) of the tile's
+// rows, 64 B per row, with granule g (16 bytes) of row r at position g ^ ((r / 4) % 4), which is the
+// image the scan keeps of the step in LDS.  Byte offset of 32-bit word `word` of row `row`:
+// ---------------------------------------------------------------------------
+constexpr int kPanelRows = 256;
+constexpr int kPanelStepBytes = 64;
+__host__ __device__ __forceinline__ int64_t panel_word_offset(int64_t row, int word, int row_bytes) {
+    const int r = (int)(row & (kPanelRows - 1));
+    const int s = word >> 4, g = (word >> 2) & 3;
+    return (row >> 8) * ((int64_t)kPanelRows * row_bytes) + ((int64_t)s * kPanelRows + r) * kPanelStepBytes +
+           ((g ^ ((r >> 2) & 3)) << 4) + ((word & 3) << 2);
+}
+
 // Butterfly reductions: after the loop every lane holds the same bits, because
 // each step combines the two partners' values with a commutative operation.
 __device__ __forceinline__ double wave_sum(double v) {

@@ -34,7 +34,9 @@ __device__ __forceinline__ uint32_t e4m3_bits(float t) {
 // One wavefront per row.  X is [n_src, d] fp32; rows [n_src, n_total) of the
 // destination are written as zeros (padding of the query block).  Row i goes to
 // dst + i * row_bytes; columns [d, row_bytes / elem) are zero.  fp8 also writes
-// scale_dst[i].  util_src may be NULL (utility 0); util_dst may be NULL.
+// scale_dst[i].  util_src may be NULL (utility 0); util_dst may be NULL.  If panel is not NULL
+// every row is also written into the step-major copy the tiled scan reads, as its row
+// panel_first + i (layout: panel_word_offset in ic_common.h).
 //
 // Arithmetic: the norm is accumulated in fp64, x / norm is formed in fp64 and
 // rounded once to fp32, and that fp32 value is what gets quantised.  fp8:
@@ -46,7 +48,8 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
                                                      uint8_t *__restrict__ dst,
                                                      float *__restrict__ scale_dst,
                                                      const float *__restrict__ util_src,
-                                                     float *__restrict__ util_dst) {
+                                                     float *__restrict__ util_dst,
+                                                     uint8_t *__restrict__ panel, int64_t panel_first) {
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
@@ -56,7 +59,10 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
     for (int64_t i = wave; i < n_total; i += nwaves) {
         uint32_t *out = reinterpret_cast<uint32_t *>(dst + i * (int64_t)row_bytes);
         if (i >= n_src) {
-            for (int w = lane; w < groups; w += 64) out[w] = 0u;
+            for (int w = lane; w < groups; w += 64) {
+                out[w] = 0u;
+                if (panel) *reinterpret_cast<uint32_t *>(panel + panel_word_offset(panel_first + i, w, row_bytes)) = 0u;
+            }
             if (ET == 1 && lane == 0) scale_dst[i] = 1.0f;
             continue;
         }
@@ -93,6 +99,7 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
                 }
             }
             out[w] = word;
+            if (panel) *reinterpret_cast<uint32_t *>(panel + panel_word_offset(panel_first + i, w, row_bytes)) = word;
         }
         if (util_dst && lane == 0) util_dst[i] = util_src ? util_src[i] : 0.0f;
     }

@@ -68,9 +68,10 @@ namespace ic {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int kGemmTile = 256;        // rows and queries per output tile
+constexpr int kGemmTile = 256;        // rows and queries per output tile (= kPanelRows: a tile of the step-major copies)
 constexpr int kGemmStageBytes = 128;  // rows are padded to a multiple of this
-constexpr int kGemmHalfBytes = 64;    // bytes of every row per pipeline step
+constexpr int kGemmHalfBytes = 64;    // bytes of every row per pipeline step (= kPanelStepBytes)
+static_assert(kGemmTile == kPanelRows && kGemmHalfBytes == kPanelStepBytes, "the step-major copies are laid out for this kernel");
 constexpr int kGemmSlots = 4;         // LDS ring: pipeline steps resident or in flight
 constexpr int kGemmThreads = 512;     // 8 wavefronts, two per SIMD: one issues MFMAs while the other issues loads
 
@@ -897,25 +898,19 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
     }
 }
 
-// Step-major copy of rows [first, last) of a row-major array (row_bytes apart, a multiple of 64):
-// tile t = 256 rows is stored as row_bytes / 64 steps of 16 KB, step s holding bytes [64 s, 64 s + 64)
-// of the tile's rows, 64 B per row, with granule g (16 bytes) of row r at position g ^ ((r / 4) % 4):
-// the image scan_gemm keeps of the step in LDS.  Rows [last, fill_to) are written as zeros (the rest
-// of the last tile: fill_to = last rounded up to a multiple of 256).  One thread per granule.
+// Step-major copy (layout: panel_word_offset in ic_common.h) of rows [first, last) of a row-major
+// array, row_bytes apart.  Rows [last, fill_to) are written as zeros (the rest of the last tile:
+// fill_to = last rounded up to a multiple of 256).  One thread per 16-byte granule.
 __global__ __launch_bounds__(256) void to_panel(const uint8_t *__restrict__ rows, int row_bytes, int64_t first,
                                                 int64_t last, int64_t fill_to, uint8_t *__restrict__ panel) {
     const int gpr = row_bytes >> 4;   // granules per row
     const int64_t total = (fill_to - first) * gpr;
-    const int64_t tile_bytes = (int64_t)kGemmTile * row_bytes;
     for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
         const int64_t i = first + idx / gpr;
         const int gi = (int)(idx % gpr);
         i32x4 v = {0, 0, 0, 0};
         if (i < last) v = *reinterpret_cast<const i32x4 *>(rows + i * row_bytes + gi * 16);
-        const int r = (int)(i & (kGemmTile - 1));
-        const int s = gi >> 2, g = gi & 3;
-        uint8_t *dst = panel + (i >> 8) * tile_bytes + ((int64_t)s * kGemmTile + r) * kGemmHalfBytes + ((g ^ ((r >> 2) & 3)) << 4);
-        *reinterpret_cast<i32x4 *>(dst) = v;
+        *reinterpret_cast<i32x4 *>(panel + panel_word_offset(i, gi * 4, row_bytes)) = v;
     }
 }
 

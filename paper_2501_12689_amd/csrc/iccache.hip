@@ -442,9 +442,9 @@ ic_status ic_index_tiled_scan_counts(ic_index *index, int64_t *tiles_again, int6
 // rest of the last tile they touch is zeroed (rows past the end of the store must not hold stale
 // bytes: the tiled scan multiplies whole tiles).
 static void panel_rows(ic_index *index, int64_t first, int64_t last) {
-    if (last <= first) return;
     const int64_t fill_to = round_up(last, ic::kGemmTile);
     const int64_t granules = (fill_to - first) * (index->L.row_bytes / 16);
+    if (granules <= 0) return;
     const int grid = (int)std::min<int64_t>((granules + 255) / 256, 65536);
     hipLaunchKernelGGL(ic::to_panel, dim3(grid), dim3(256), 0, index->stream, (const uint8_t *)index->rows,
                        index->L.row_bytes, first, last, fill_to, index->panel);
@@ -462,16 +462,17 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
     float *util_dst = index->util + at;
     if (index->store == IC_STORE_BF16) {
         hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, index->stream, emb_dev, n, n,
-                           index->d, index->L.row_bytes, dst, (float *)nullptr, util_dev, util_dst);
+                           index->d, index->L.row_bytes, dst, (float *)nullptr, util_dev, util_dst, index->panel, at);
     } else {
         hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, index->stream, emb_dev, n, n,
-                           index->d, index->L.row_bytes, dst, index->scale + at, util_dev, util_dst);
+                           index->d, index->L.row_bytes, dst, index->scale + at, util_dev, util_dst, index->panel, at);
     }
     hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream,
                        index->valid + at, n, (uint8_t)1);
     hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n * 4 + 255) / 256)), dim3(256), 0, index->stream,
                        (uint8_t *)(index->domain + at), n * 4, (uint8_t)0);  // new rows are shared with everyone
-    if (index->panel) panel_rows(index, at, at + n);
+    // quantize_rows wrote the new rows into the step-major copy as well; the rest of their last tile is zeroed
+    if (index->panel && (at + n) % ic::kGemmTile != 0) panel_rows(index, at + n, at + n);
     if (hipGetLastError() != hipSuccess) return IC_ERR_DEVICE;
     index->n += n;
     return IC_OK;
@@ -763,14 +764,14 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             if (et == 0)
                 hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
                                    (int64_t)q_pad, index->d, L.row_bytes, W.qbuf, (float *)nullptr,
-                                   (const float *)nullptr, (float *)nullptr);
+                                   (const float *)nullptr, (float *)nullptr, gemm ? W.qpanel : (uint8_t *)nullptr, (int64_t)0);
             else
                 hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
                                    (int64_t)q_pad, index->d, L.row_bytes, W.qbuf, W.qscale,
-                                   (const float *)nullptr, (float *)nullptr);
+                                   (const float *)nullptr, (float *)nullptr, gemm ? W.qpanel : (uint8_t *)nullptr, (int64_t)0);
         }
 
-        if (gemm) {   // the tiled scan reads the query block from its step-major copy
+        if (gemm && req.q_rows) {   // stored rows as queries: their step-major copy (quantize_rows writes both at once)
             const int64_t granules = (int64_t)q_pad * (L.row_bytes / 16);
             hipLaunchKernelGGL(ic::to_panel, dim3((unsigned)std::min<int64_t>((granules + 255) / 256, 65536)), dim3(256), 0, st,
                                (const uint8_t *)W.qbuf, L.row_bytes, (int64_t)0, (int64_t)q_pad, (int64_t)q_pad, W.qpanel);
@@ -1368,10 +1369,12 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         const int grid = (qc + 3) / 4;
         if (et == 0)
             hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
-                               s->d, L.row_bytes, s->ws.qbuf, (float *)nullptr, (const float *)nullptr, (float *)nullptr);
+                               s->d, L.row_bytes, s->ws.qbuf, (float *)nullptr, (const float *)nullptr, (float *)nullptr,
+                               (uint8_t *)nullptr, (int64_t)0);
         else
             hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
-                               s->d, L.row_bytes, s->ws.qbuf, s->ws.qscale, (const float *)nullptr, (float *)nullptr);
+                               s->d, L.row_bytes, s->ws.qbuf, s->ws.qscale, (const float *)nullptr, (float *)nullptr,
+                               (uint8_t *)nullptr, (int64_t)0);
         float *out_s = out_scores_dev + q0 * (int64_t)k;
         int64_t *out_i = out_ids_dev + q0 * (int64_t)k;
         const FinalOpts fo{-INFINITY, nullptr, -1};
