@@ -250,6 +250,22 @@ def main() -> int:
             "tiles_again_blocks_redone": list(ix.tiled_scan_counts()),
         }
         del qd, out_s, out_i
+        # batches between the two regimes (one and two query blocks of the tiled scan)
+        for Qm in (128, 512):
+            qd = wl.queries(Qm, batch=Qm)
+            out_s = torch.empty(Qm, cfg.k, dtype=torch.float32, device=dev)
+            out_i = torch.empty(Qm, cfg.k, dtype=torch.int64, device=dev)
+            ms, scan, wall, spread = time_search(ix, torch, qd, cfg.k, cfg.lam, None, out_s, out_i, lwarm, lsteps)
+            flop = 2.0 * Qm * cfg.N * cfg.d
+            per_q[str(Qm)] = {
+                "queries_per_s": Qm / (ms * 1e-3), "ms_per_step": ms, "steps": lsteps, "scan_kernel_ms": scan,
+                "scan_GBps": store_bytes / (scan * 1e-3) / 1e9,
+                "hbm_frac": store_bytes / (scan * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "scan_TFLOPs": flop / (scan * 1e-3) / 1e12,
+                "mfma_frac": flop / (scan * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                "step_ms": spread, "tiles_again_blocks_redone": list(ix.tiled_scan_counts()),
+            }
+            del qd, out_s, out_i
     say("Q=4096 on the headline store done")
     # ---- cluster pruning on the same store: K = sqrt(N) clusters, two K-Means iterations
     ivf_leg = None

@@ -113,21 +113,12 @@ struct GemmArgs {
 constexpr int kGemmPark = 512;        // candidates a workgroup can park per tile (one flusher thread each)
 constexpr int kGemmHits = 96;         // blocks of 16 scores a workgroup can list per tile
 
-struct HitEntry {   // one lane's block of 16 that may hold a candidate
-    f32x4 sc[4];    // bf16: the 16 scores; fp8: the 16 dot products, still to be scaled
+struct HitEntry {   // 16 scores of one lane's block that reached its query's threshold
+    f32x4 sc[4];
     uint64_t thr;   // the query's pilot key
     uint32_t q;
     uint32_t row;   // row of score 0
-    float qs;       // fp8: the query's scale
-    uint32_t pad_;
 };
-
-// fp8 score of a dot product of codes: one rounding for the product of the two scales, one for the
-// fused multiply-add.  Every kernel mode forms it this way, so that a pilot's threshold is a score the
-// selection reaches again bit for bit.
-__device__ __forceinline__ float fp8_score(float dot, float row_scale, float q_scale, float bias) {
-    return __builtin_fmaf(dot, row_scale * q_scale, bias);
-}
 
 constexpr size_t gemm_lds_bytes() {
     return (size_t)kGemmSlots * 2 * kGemmTile * kGemmHalfBytes + 2 * kGemmTile * 4 + (size_t)kGemmPark * 12 + 16 +
@@ -714,7 +705,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        float x = (ET == 1) ? fp8_score(acc[i][j][v], rs[v >> 2][v & 3], qs[j], bs[v >> 2][v & 3])
+                        float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
                                             : acc[i][j][v];   // bf16: the bias is in it from the start
                         if (DOM && ds[v >> 2][v & 3] != 0 && ds[v >> 2][v & 3] != qd[j]) x = -INFINITY;
                         best[j] = fmaxf(best[j], x);
@@ -804,7 +795,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                     const uint64_t thr_k = t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const float x = (ET == 1) ? fp8_score(acc[i][j][v], rs[v >> 2][v & 3], qs[j], bs[v >> 2][v & 3])
+                        const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
                                                   : acc[i][j][v];   // bf16: the bias is in it from the start
                         const uint32_t row = (uint32_t)(row0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3));
                         const uint64_t key = make_key(x, row);
@@ -825,41 +816,27 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 if (!kBiasInit) bs[u] = *reinterpret_cast<const f32x4 *>(bias_t + rr);
                 if (ET == 1) rs[u] = *reinterpret_cast<const f32x4 *>(scale_t + rr);
             }
-            // fp8: the score is dot * (row scale * query scale) + bias, three operations per score.  A block is
-            // tested with a bound that costs half of that: m = max over the block of dot * row scale, then
-            // m * query scale + (largest bias of the block) against the threshold, with a slack far above the
-            // rounding of either form (2^-20 of the magnitudes involved, the roundings are 2^-23).  No score of
-            // the block can exceed that bound, so a block that fails it holds no candidate; a block that
-            // passes is listed with its dot products and scored exactly in pass 2.
-            float bmax = -INFINITY;
-            if (ET == 1) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) bmax = fmaxf(bmax, fmaxf(fmaxf(bs[u][0], bs[u][1]), fmaxf(bs[u][2], bs[u][3])));
-            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                f32x4 sc[4];
                 float best = -INFINITY;
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    best = fmaxf(best, (ET == 1) ? acc[i][j][v] * rs[v >> 2][v & 3] : acc[i][j][v]);   // bf16: the score itself
-                bool listed = best >= thr_s[j];
-                if (ET == 1) {
-                    const float mq = best * qs[j];
-                    const float bound = mq + bmax + 0x1p-20f * (fabsf(mq) + fabsf(bmax) + fabsf(thr_s[j]));
-                    listed = bound >= thr_s[j] || thr_s[j] == -INFINITY;   // false for a padding query (NaN)
+                for (int v = 0; v < 16; ++v) {
+                    const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
+                                              : acc[i][j][v];   // bf16: the bias is in it from the start
+                    sc[v >> 2][v & 3] = x;
+                    best = fmaxf(best, x);
                 }
-                if (listed) {
+                if (best >= thr_s[j]) {
                     const uint32_t slot = atomicAdd(hit_n, 1u);
                     const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
                     if (slot < (uint32_t)kGemmHits) {
                         HitEntry &e = hits[slot];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            e.sc[u] = f32x4{acc[i][j][4 * u], acc[i][j][4 * u + 1], acc[i][j][4 * u + 2], acc[i][j][4 * u + 3]};
+                        for (int u = 0; u < 4; ++u) e.sc[u] = sc[u];
                         e.q = (uint32_t)q;
                         e.row = (uint32_t)(row0 + wm * 64 + i * 32 + 4 * h);  // row of score 0; score v: + 8*(v/4) + v%4
                         e.thr = thr_raw[j];
-                        if (ET == 1) e.qs = qs[j];
                     }   // list full: the whole tile is left to a second launch, see below
                 }
             }
@@ -886,14 +863,10 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             const int v = tid & 15;
             for (uint32_t e = tid >> 4; e < nh; e += kGemmThreads / 16) {
                 const HitEntry &he = hits[e];
+                const float x = he.sc[v >> 2][v & 3];
                 const uint64_t t0 = he.thr;
                 const uint64_t thr_k = t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
                 const uint32_t row = he.row + 8 * (v >> 2) + (v & 3);
-                float x = he.sc[v >> 2][v & 3];
-                if (ET == 1) {   // the tile's row scales and biases are still in LDS
-                    const int rr = (int)(row - (uint32_t)row0);
-                    x = fp8_score(x, scale_t[rr], he.qs, bias_t[rr]);
-                }
                 const uint64_t key = make_key(x, row);
                 if (key > thr_k && x > -INFINITY) {
                     const uint32_t slot = atomicAdd(park_n, 1u);
