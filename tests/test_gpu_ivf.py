@@ -205,6 +205,43 @@ def test_pruned_search_from_given_centroids_and_assignment(pkg, oracle, store, n
     ivf.close(); ix.close()
 
 
+def test_many_centroids_and_a_large_batch_take_the_tiled_scan(pkg, oracle):
+    """With 16,400 centroids and 200 queries the probe step (nearest centroids of every query) is a
+    batch large enough for the MFMA-tiled scan over the centroid index, whose step-major copy is
+    rewritten every time the centroids are loaded: twice here, the second load being the one that counts."""
+    _say("ivf search, 16400 centroids, 200 queries")
+    K, N, d, k, nprobe = 16400, 40000, 64, 4, 2
+    cfg = workloads.Config("V", N=N, d=d, clusters=K, Q=200, k=k, store="bf16", sigma=0.25, seed=9650)
+    wl = workloads.Workload(cfg, "cpu")
+    E = wl.rows(0, N)[0].numpy()
+    C = wl.centres.numpy()
+    ix = pkg.Index(d, N, pkg.STORE_BF16, 256, 16, DEV)
+    ix.append(torch.from_numpy(E).to(DEV), None)
+    assign = oracle.ivf_assign(E, C)
+    ivf = pkg.Ivf(ix, K, 4)
+    ivf.set_centroids(torch.from_numpy(np.ascontiguousarray(C[::-1])).to(DEV))   # a first set, overwritten below
+    ivf.set_centroids(torch.from_numpy(C).to(DEV))
+    ivf.set_assignment(torch.from_numpy(assign).to(DEV))
+    Qm = wl.queries(cfg.Q).numpy()
+    s, i = ivf.search(torch.from_numpy(Qm).to(DEV), k, nprobe, 0.0)
+    torch.cuda.synchronize()
+    gs, gi = s.cpu().numpy(), i.cpu().numpy()
+    cs = oracle.scores(C, Qm)
+    order = np.argsort(-cs, axis=1, kind="stable")
+    checked = 0
+    for q in range(0, cfg.Q, 3):
+        top = order[q, :nprobe]
+        gap = cs[q, order[q, nprobe - 1]] - cs[q, order[q, nprobe]]
+        if gap > 5e-3:
+            members = np.isin(assign, top).astype(np.uint8)
+            parity.check_batch("bf16", gs[q:q + 1], gi[q:q + 1], E, None, members, Qm[q:q + 1], k, 0.0, f"ivf q={q}")
+            checked += 1
+        else:
+            assert np.all(np.isin(assign[gi[q][gi[q] >= 0]], order[q, :nprobe + 1]))
+    assert checked >= 30, checked
+    ivf.close(); ix.close()
+
+
 def test_training_against_the_reference_kmeans(pkg, oracle):
     _say("ivf train")
     cfg, wl, ix, E, U = _setup(pkg, "bf16", N=30000, d=64, C=24, util="none")
