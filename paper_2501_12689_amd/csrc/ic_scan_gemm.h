@@ -452,19 +452,12 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    if (ET == 0) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, xa[i]), __builtin_bit_cast(bf16x8, xb[j]),
-                            kFirst ? bvec[i] : acc[i][j], 0, 0, 0);
-                    } else {
-                        const i64x2 x = __builtin_bit_cast(i64x2, xa[i]);
-                        const i64x2 y = __builtin_bit_cast(i64x2, xb[j]);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.x, y.x, acc[i][j], 0, 0, 0);
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(x.y, y.y, acc[i][j], 0, 0, 0);
-                    }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, xa[i]), __builtin_bit_cast(bf16x8, xb[j]),
+                        kFirst ? bvec[i] : acc[i][j], 0, 0, 0);
                 }
         };
-        constexpr int kPer = (ET == 0) ? 1 : 2;  // MFMA instructions per accumulator tile and step
+        constexpr int kPer = 1;  // MFMA instructions per accumulator tile and 32-byte half step (bf16)
 
         // One pipeline step = 64 B of every row = two MFMA steps of 8 accumulator tiles.
         //   first half:  MFMAs on the operands read earlier; the second half's operands are read
