@@ -865,7 +865,22 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             // and dense enough that a tile of 256 x 256 scores has about 24 or fewer above the thresholds
             // (256 queries x stride * k rows per query x 256 / n rows): the per-tile hit list holds 96
             const int64_t by_hits = g.ntiles * 3 / (32 * (int64_t)k);
-            p.row_stride = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, by_hits), g.ntiles / std::max(k, 64)));
+            const int64_t most = std::min<int64_t>(want, g.ntiles / std::max(k, 64));
+            p.row_stride = std::max<int64_t>(1, std::min<int64_t>(by_hits, most));
+            // a pilot of a few rounds of the grid: a slightly sparser sample (up to half again as many hits per
+            // tile) that saves a whole round is the cheaper one
+            auto rounds = [&](int64_t stride) {
+                const int64_t tiles = ((n + stride - 1) / stride + ic::kGemmTile - 1) / ic::kGemmTile * nqb_gemm;
+                return (tiles + gemm_grid - 1) / gemm_grid;
+            };
+            if (rounds(p.row_stride) <= 3) {
+                for (int64_t s2 = p.row_stride + 1; s2 <= std::min<int64_t>(most, p.row_stride * 3 / 2); ++s2) {
+                    if (rounds(s2) < rounds(p.row_stride)) {
+                        p.row_stride = s2;
+                        break;
+                    }
+                }
+            }
             gemm_stride = p.row_stride;
             p.n_sampled = (n + p.row_stride - 1) / p.row_stride;
             p.ntiles = (p.n_sampled + ic::kGemmTile - 1) / ic::kGemmTile;
