@@ -147,6 +147,20 @@ def cluster_pruning_leg(pkg, torch, np, ix, wl, cfg, Q, k, probes):
     return leg
 
 
+def host_cpu() -> str:
+    """Model name and logical CPU count of the host the CPU reference is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.lower().startswith("model name"):
+                    model = ln.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return f"{model}, {os.cpu_count()} logical CPUs visible"
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -496,6 +510,7 @@ def main() -> int:
         full_equiv = qs / (dt * cfg.N / n_sample)
         cpu = {
             "value": full_equiv, "unit": "queries/s", "cores": ic_oracle.num_threads(), "kind": "oracle",
+            "host": host_cpu(),
             "sample": f"{qs} queries x first {n_sample} rows in {dt:.2f} s, scaled linearly "
                       f"to N={cfg.N}",
         }
