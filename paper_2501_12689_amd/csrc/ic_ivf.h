@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void ivf_offsets(const int64_t *__restrict__ c
         tile[threadIdx.x] = v;
         __syncthreads();
         for (int off = 1; off < 256; off <<= 1) {
-            const int64_t add = threadIdx.x >= off ? tile[threadIdx.x - off] : 0;
+            const int64_t add = (int)threadIdx.x >= off ? tile[threadIdx.x - off] : 0;
             __syncthreads();
             tile[threadIdx.x] += add;
             __syncthreads();
