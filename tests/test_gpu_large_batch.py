@@ -78,6 +78,59 @@ def test_large_batch_parity(pkg, oracle, case):
     print("   stats", st, flush=True)
 
 
+def _drawn_large(count, seed):
+    """Seeded draw of shapes the fixed list does not name: any d the store accepts, store sizes across
+    the three thresholds from which a batch takes the tiled scan, batches in one, two or several
+    blocks of 256 queries and split into chunks by a smaller ``max_queries``, any k, rows appended in
+    pieces, a capacity that is or is not a whole number of tiles."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for n in range(count):
+        store = "fp8" if rng.random() < 0.4 else "bf16"
+        dmax = 2048 if store == "fp8" else 1024
+        d = int(rng.choice([rng.integers(1, 65), rng.integers(65, 400), rng.integers(400, dmax + 1)]))
+        N = int(rng.choice([rng.integers(16384, 65536), rng.integers(65536, 262144), rng.integers(262144, 420000)]))
+        N = min(N, int(1.6e8 // d))
+        Q = int(rng.choice([rng.integers(65, 129), rng.integers(129, 257), rng.integers(257, 1200)]))
+        k = int(rng.choice([1, rng.integers(2, 17), rng.integers(17, 129)]))
+        lam = float(rng.choice([0.0, 0.1, 0.7]))
+        util = "none" if lam == 0.0 else str(rng.choice(["uniform", "beta25"]))
+        pv = float(rng.choice([1.0, 0.9, 0.3]))
+        max_q = int(rng.choice([Q, Q + 7, max(65, Q // 2)]))
+        out.append((store, N, d, int(rng.integers(1, 40)), Q, k, lam, util, pv, float(rng.choice([0.0, 1.1])),
+                    max_q, int(rng.choice([1, 2, 5])), int(rng.choice([0, 1, 300]))))
+    return out
+
+
+DRAWN_LARGE = _drawn_large(20, 20250113)
+
+
+@pytest.mark.parametrize("case", DRAWN_LARGE, ids=lambda c: "-".join(str(x) for x in c))
+def test_tiled_scan_on_drawn_shapes(pkg, oracle, case):
+    store, N, d, C, Q, k, lam, util, pv, zipf, max_q, pieces, spare = case
+    _say(f"tiled scan, drawn shape {case}")
+    n = DRAWN_LARGE.index(case)
+    cfg = workloads.Config("H", N=N, d=d, clusters=C, Q=Q, k=k, store=store, zipf=zipf, lam=lam, util=util,
+                           p_valid=pv, seed=8300 + n)
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, M = wl.rows(0, N)
+    Qm = wl.queries()
+    rng = np.random.default_rng(8300 + n)
+    sid = pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3
+    ix = pkg.Index(d, N + spare, sid, max_q, 128, DEV)
+    cuts = sorted(set([0, N] + [int(x) for x in rng.integers(0, N + 1, size=pieces - 1)]))
+    Ed, Ud = E.to(DEV), (None if U is None else U.to(DEV))
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        assert ix.append(Ed[lo:hi].contiguous(), None if Ud is None else Ud[lo:hi].contiguous()) == lo
+    s, i = ix.search(Qm.to(DEV), k, lam, None if M is None else M.to(DEV))
+    torch.cuda.synchronize()
+    ix.close()
+    np_ = lambda t: None if t is None else t.numpy()
+    sample = sorted(set([0, Q - 1] + [int(x) for x in rng.integers(0, Q, size=8)]))
+    parity.check_batch(store, s.cpu().numpy(), i.cpu().numpy(), np_(E), np_(U), np_(M), Qm.numpy(), k, lam,
+                       f"{case}", queries=sample)
+
+
 def test_large_batch_list_overflow_is_redone_exactly(pkg, oracle):
     """Candidate lists shrunk to 8 keys: every block overflows and is redone by the streaming scan."""
     _say("tiled scan, forced list overflow")
