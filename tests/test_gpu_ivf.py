@@ -205,6 +205,70 @@ def test_pruned_search_from_given_centroids_and_assignment(pkg, oracle, store, n
     ivf.close(); ix.close()
 
 
+def _drawn_pruned(count, seed):
+    """Seeded draw of pruned searches the fixed cases do not name: any row length, 2 to 600 clusters
+    (uniform or Zipf sizes, so lists from empty to most of the store), 1 to all clusters probed,
+    batches beyond one block of 64 queries, evicted rows."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for n in range(count):
+        store = "fp8" if rng.random() < 0.4 else "bf16"
+        d = int(rng.choice([rng.integers(8, 65), rng.integers(65, 300), rng.integers(300, 900)]))
+        N = int(rng.choice([rng.integers(300, 3000), rng.integers(3000, 60000), rng.integers(60000, 150000)]))
+        N = min(N, int(6e7 // d))
+        K = min(int(rng.choice([rng.integers(2, 10), rng.integers(10, 100), rng.integers(100, 600)])), max(2, N // 4))
+        max_probe = int(min(K, rng.choice([1, 2, 8, 32])))
+        out.append((store, N, d, K, int(rng.integers(1, max_probe + 1)), max_probe,
+                    int(rng.choice([1, rng.integers(2, 65), rng.integers(65, 150)])),
+                    int(rng.choice([1, rng.integers(2, 17), rng.integers(17, 64)])),
+                    float(rng.choice([0.0, 0.2])), float(rng.choice([0.0, 0.1])), float(rng.choice([0.0, 1.1]))))
+    return out
+
+
+DRAWN_PRUNED = _drawn_pruned(16, 20250114)
+
+
+@pytest.mark.parametrize("case", DRAWN_PRUNED, ids=lambda c: "-".join(str(x) for x in c))
+def test_pruned_search_on_drawn_shapes(pkg, oracle, case):
+    store, N, d, K, nprobe, max_probe, Q, k, lam, evicted, zipf = case
+    _say(f"ivf search, drawn shape {case}")
+    n = DRAWN_PRUNED.index(case)
+    rng = np.random.default_rng(9700 + n)
+    cfg = workloads.Config("V", N=N, d=d, clusters=K, Q=Q, k=k, store=store, zipf=zipf, lam=lam, util="uniform",
+                           seed=9700 + n)
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, _ = wl.rows(0, N)
+    E, U = E.numpy(), U.numpy()
+    C = wl.centres.numpy()
+    sid = pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3
+    ix = pkg.Index(d, N, sid, max(64, Q), 64, DEV)
+    ix.append(torch.from_numpy(E).to(DEV), torch.from_numpy(U).to(DEV))
+    live = np.ones(N, bool)
+    if evicted > 0:
+        gone = rng.choice(N, int(N * evicted), replace=False).astype(np.int64)
+        ix.invalidate(torch.from_numpy(gone).to(DEV))
+        live[gone] = False
+    assign = oracle.ivf_assign(E, C)
+    ivf = pkg.Ivf(ix, K, max_probe)
+    ivf.set_centroids(torch.from_numpy(C).to(DEV))
+    ivf.set_assignment(torch.from_numpy(assign).to(DEV))
+    Qm = wl.queries(Q).numpy()
+    s, i = ivf.search(torch.from_numpy(Qm).to(DEV), k, nprobe, lam)
+    torch.cuda.synchronize()
+    gs, gi = s.cpu().numpy(), i.cpu().numpy()
+    ivf.close(); ix.close()
+    cs = oracle.scores(C, Qm)
+    order = np.argsort(-cs, axis=1, kind="stable")
+    for q in sorted(set([0, Q - 1] + [int(x) for x in rng.integers(0, Q, size=6)])):
+        gap = np.inf if nprobe >= K else cs[q, order[q, nprobe - 1]] - cs[q, order[q, nprobe]]
+        if gap > (5e-3 if store == "bf16" else 3e-2):     # the probe set is unambiguous (see the test above)
+            members = (np.isin(assign, order[q, :nprobe]) & live).astype(np.uint8)
+            parity.check_batch(store, gs[q:q + 1], gi[q:q + 1], E, U, members, Qm[q:q + 1], k, lam, f"{case} q={q}")
+        else:
+            got = gi[q][gi[q] >= 0]
+            assert np.all(np.isin(assign[got], order[q, :nprobe + 1])) and np.all(live[got])
+
+
 def test_many_centroids_and_a_large_batch_take_the_tiled_scan(pkg, oracle):
     """With 16,400 centroids and 200 queries the probe step (nearest centroids of every query) is a
     batch large enough for the MFMA-tiled scan over the centroid index, whose step-major copy is
