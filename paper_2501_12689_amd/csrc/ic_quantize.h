@@ -31,6 +31,19 @@ __device__ __forceinline__ uint32_t e4m3_bits(float t) {
     return sign | ((uint32_t)(E + 7) << 3) | ((uint32_t)r - 8u);
 }
 
+// fp32(x / div), the fp64 quotient rounded once more to fp32, without dividing wherever that provably
+// changes nothing.  inv = 1 / div (correctly rounded), so q = x * inv lies within 2^-52 (relative) of
+// the true quotient and the correctly rounded fp64 quotient within 2^-53 of it: both lie between
+// q (1 - 2^-50) and q (1 + 2^-50).  Rounding to fp32 is monotonic, so when the two ends round to the same
+// fp32 value that value is fp32(fp64(x / div)).  Otherwise (a quotient within 2^-49 of a rounding
+// boundary of fp32: about 3 elements in 10^8) the division is carried out.
+__device__ __forceinline__ float quotient_f32(double x, double div, double inv) {
+    const double q = x * inv;
+    const float lo = (float)(q * (1.0 - 0x1p-50)), hi = (float)(q * (1.0 + 0x1p-50));
+    if (lo == hi) return lo;
+    return (float)(x / div);
+}
+
 // One wavefront per row.  X is [n_src, d] fp32; rows [n_src, n_total) of the
 // destination are written as zeros (padding of the query block).  Row i goes to
 // dst + i * row_bytes; columns [d, row_bytes / elem) are zero.  fp8 also writes
@@ -42,6 +55,14 @@ __device__ __forceinline__ uint32_t e4m3_bits(float t) {
 // rounded once to fp32, and that fp32 value is what gets quantised.  fp8:
 // scale = fp32(max|unit| / 448) (1 for a zero row), code = e4m3(fp32(unit / scale))
 // with the quotient in fp64.
+//
+// A lane owns columns 256 t + 4 lane + {0, 1, 2, 3}, t = 0 ... 7 (d <= 2048), and keeps them in
+// registers: the row is read once, 16 bytes per lane and a contiguous kilobyte per wavefront and
+// instruction, all loads issued before the first is used.  The squares are added in that order per
+// lane (columns past d count as zeros), then across lanes by wave_sum, whatever the alignment of X, so
+// a row's norm does not depend on how it was handed over.
+constexpr int kQuantSteps = 8;   // 256 columns each
+
 template <int ET>  // 0 = bf16, 1 = fp8 e4m3
 __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X, int64_t n_src,
                                                      int64_t n_total, int d, int row_bytes,
@@ -53,8 +74,11 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
-    constexpr int G = (ET == 0) ? 2 : 4;      // elements per 32-bit store
     const int groups = row_bytes / 4;         // 32-bit words per destination row
+    const int row_elems = (ET == 0) ? row_bytes / 2 : row_bytes;   // columns of a destination row (a multiple of 64)
+    const int nt = (row_elems + 255) / 256;   // steps that hold a column of the row
+    // 16-byte loads need d % 4 == 0 and an aligned X (then every row starts aligned)
+    const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0);
 
     for (int64_t i = wave; i < n_total; i += nwaves) {
         uint32_t *out = reinterpret_cast<uint32_t *>(dst + i * (int64_t)row_bytes);
@@ -67,39 +91,74 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
             continue;
         }
         const float *x = X + i * (int64_t)d;
-        double ss = 0.0;
-        for (int j = lane; j < d; j += 64) {
-            double v = (double)x[j];
-            ss += v * v;
+        f32x4 v[kQuantSteps];
+#pragma unroll
+        for (int t = 0; t < kQuantSteps; ++t) {
+            v[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int j = 256 * t + 4 * lane;
+            if (t < nt && j < d) {
+                if (vec) {
+                    v[t] = *reinterpret_cast<const f32x4 *>(x + j);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (j + c < d) v[t][c] = x[j + c];
+                }
+            }
         }
+        double ss = 0.0;
+#pragma unroll
+        for (int t = 0; t < kQuantSteps; ++t)
+            if (t < nt) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const double e = (double)v[t][c];
+                    ss += e * e;
+                }
+            }
         const double nrm = sqrt(wave_sum(ss));
         const bool live = nrm > 0.0;
+        const double inv_nrm = live ? 1.0 / nrm : 0.0;
 
+        // unit values (columns past d, and every column of a zero row, are zeros)
+        float amax = 0.0f;
+#pragma unroll
+        for (int t = 0; t < kQuantSteps; ++t)
+            if (t < nt) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    v[t][c] = live ? quotient_f32((double)v[t][c], nrm, inv_nrm) : 0.0f;
+                    amax = fmaxf(amax, fabsf(v[t][c]));
+                }
+            }
         float sc = 1.0f;
         if (ET == 1) {
-            float amax = 0.0f;
-            if (live)
-                for (int j = lane; j < d; j += 64) amax = fmaxf(amax, fabsf((float)((double)x[j] / nrm)));
             amax = wave_max(amax);
             if (amax > 0.0f) sc = (float)((double)amax / 448.0);
             if (lane == 0) scale_dst[i] = sc;
         }
-        for (int w = lane; w < groups; w += 64) {
-            uint32_t word = 0u;
+        const double inv_sc = 1.0 / (double)sc;
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const int j = w * G + g;
-                float unit = 0.0f;
-                if (j < d && live) unit = (float)((double)x[j] / nrm);
+        for (int t = 0; t < kQuantSteps; ++t) {
+            if (t < nt && 256 * t + 4 * lane < row_elems) {
                 if (ET == 0) {
-                    word |= bf16_bits(unit) << (16 * g);
+                    // two 32-bit words of two bf16 each: words 128 t + 2 lane and the next, in one granule
+                    const int w = 128 * t + 2 * lane;
+                    uint2 word;
+                    word.x = bf16_bits(v[t][0]) | (bf16_bits(v[t][1]) << 16);
+                    word.y = bf16_bits(v[t][2]) | (bf16_bits(v[t][3]) << 16);
+                    *reinterpret_cast<uint2 *>(out + w) = word;
+                    if (panel) *reinterpret_cast<uint2 *>(panel + panel_word_offset(panel_first + i, w, row_bytes)) = word;
                 } else {
-                    const float t = (float)((double)unit / (double)sc);
-                    word |= e4m3_bits(t) << (8 * g);
+                    const int w = 64 * t + lane;
+                    uint32_t word = 0u;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        word |= e4m3_bits(quotient_f32((double)v[t][c], (double)sc, inv_sc)) << (8 * c);
+                    out[w] = word;
+                    if (panel) *reinterpret_cast<uint32_t *>(panel + panel_word_offset(panel_first + i, w, row_bytes)) = word;
                 }
             }
-            out[w] = word;
-            if (panel) *reinterpret_cast<uint32_t *>(panel + panel_word_offset(panel_first + i, w, row_bytes)) = word;
         }
         if (util_dst && lane == 0) util_dst[i] = util_src ? util_src[i] : 0.0f;
     }
