@@ -36,12 +36,12 @@ __device__ __forceinline__ uint32_t e4m3_bits(float t) {
 // the true quotient and the correctly rounded fp64 quotient within 2^-53 of it: both lie between
 // q (1 - 2^-50) and q (1 + 2^-50).  Rounding to fp32 is monotonic, so when the two ends round to the same
 // fp32 value that value is fp32(fp64(x / div)).  Otherwise (a quotient within 2^-49 of a rounding
-// boundary of fp32: about 3 elements in 10^8) the division is carried out.
-__device__ __forceinline__ float quotient_f32(double x, double div, double inv) {
+// boundary of fp32: about 3 elements in 10^8) `doubt` is set and the caller divides.
+__device__ __forceinline__ float quotient_f32(double x, double inv, bool &doubt) {
     const double q = x * inv;
     const float lo = (float)(q * (1.0 - 0x1p-50)), hi = (float)(q * (1.0 + 0x1p-50));
-    if (lo == hi) return lo;
-    return (float)(x / div);
+    doubt |= lo != hi;
+    return lo;
 }
 
 // One wavefront per row.  X is [n_src, d] fp32; rows [n_src, n_total) of the
@@ -56,14 +56,16 @@ __device__ __forceinline__ float quotient_f32(double x, double div, double inv) 
 // scale = fp32(max|unit| / 448) (1 for a zero row), code = e4m3(fp32(unit / scale))
 // with the quotient in fp64.
 //
-// A lane owns columns 256 t + 4 lane + {0, 1, 2, 3}, t = 0 ... 7 (d <= 2048), and keeps them in
-// registers: the row is read once, 16 bytes per lane and a contiguous kilobyte per wavefront and
-// instruction, all loads issued before the first is used.  The squares are added in that order per
-// lane (columns past d count as zeros), then across lanes by wave_sum, whatever the alignment of X, so
-// a row's norm does not depend on how it was handed over.
-constexpr int kQuantSteps = 8;   // 256 columns each
+// A lane owns columns 256 t + 4 lane + {0, 1, 2, 3}, t < NT (NT = steps of 256 columns that a
+// destination row has, at most 8), and keeps them in registers: the row is read once, 16 bytes per lane
+// and a contiguous kilobyte per wavefront and instruction, all loads issued before the first is used.
+// The squares are added in that order per lane (columns past d count as zeros), then across lanes by
+// wave_sum, whatever the alignment of X, so a row's norm does not depend on how it was handed over.
+// The quotients are formed by quotient_f32; a row in which any lane is in doubt about any column (rare)
+// is done again with the divisions themselves, from the row as reloaded.
+constexpr int kQuantSteps = 8;   // 256 columns each: d <= 2048
 
-template <int ET>  // 0 = bf16, 1 = fp8 e4m3
+template <int ET, int NT>  // ET: 0 = bf16, 1 = fp8 e4m3
 __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X, int64_t n_src,
                                                      int64_t n_total, int d, int row_bytes,
                                                      uint8_t *__restrict__ dst,
@@ -76,7 +78,6 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     const int groups = row_bytes / 4;         // 32-bit words per destination row
     const int row_elems = (ET == 0) ? row_bytes / 2 : row_bytes;   // columns of a destination row (a multiple of 64)
-    const int nt = (row_elems + 255) / 256;   // steps that hold a column of the row
     // 16-byte loads need d % 4 == 0 and an aligned X (then every row starts aligned)
     const bool vec = (d % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15u) == 0);
 
@@ -91,57 +92,64 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
             continue;
         }
         const float *x = X + i * (int64_t)d;
-        f32x4 v[kQuantSteps];
+        auto load_row = [&](f32x4 (&v)[NT]) {
 #pragma unroll
-        for (int t = 0; t < kQuantSteps; ++t) {
-            v[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const int j = 256 * t + 4 * lane;
-            if (t < nt && j < d) {
-                if (vec) {
-                    v[t] = *reinterpret_cast<const f32x4 *>(x + j);
-                } else {
+            for (int t = 0; t < NT; ++t) {
+                v[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                const int j = 256 * t + 4 * lane;
+                if (j < d) {
+                    if (vec) {
+                        v[t] = *reinterpret_cast<const f32x4 *>(x + j);
+                    } else {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (j + c < d) v[t][c] = x[j + c];
+                        for (int c = 0; c < 4; ++c)
+                            if (j + c < d) v[t][c] = x[j + c];
+                    }
                 }
             }
-        }
+        };
+        f32x4 v[NT];
+        load_row(v);
         double ss = 0.0;
 #pragma unroll
-        for (int t = 0; t < kQuantSteps; ++t)
-            if (t < nt) {
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const double e = (double)v[t][c];
-                    ss += e * e;
-                }
+            for (int c = 0; c < 4; ++c) {
+                const double e = (double)v[t][c];
+                ss += e * e;
             }
         const double nrm = sqrt(wave_sum(ss));
         const bool live = nrm > 0.0;
         const double inv_nrm = live ? 1.0 / nrm : 0.0;
 
         // unit values (columns past d, and every column of a zero row, are zeros)
-        float amax = 0.0f;
+        bool doubt = false;
 #pragma unroll
-        for (int t = 0; t < kQuantSteps; ++t)
-            if (t < nt) {
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    v[t][c] = live ? quotient_f32((double)v[t][c], nrm, inv_nrm) : 0.0f;
-                    amax = fmaxf(amax, fabsf(v[t][c]));
-                }
-            }
+            for (int c = 0; c < 4; ++c) v[t][c] = quotient_f32((double)v[t][c], inv_nrm, doubt);
+        if (__builtin_amdgcn_ballot_w64(doubt) != 0ull) {
+            load_row(v);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[t][c] = live ? (float)((double)v[t][c] / nrm) : 0.0f;
+        }
         float sc = 1.0f;
         if (ET == 1) {
+            float amax = 0.0f;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) amax = fmaxf(amax, fabsf(v[t][c]));
             amax = wave_max(amax);
             if (amax > 0.0f) sc = (float)((double)amax / 448.0);
             if (lane == 0) scale_dst[i] = sc;
         }
-        const double inv_sc = 1.0 / (double)sc;
+        if (ET == 0) {
 #pragma unroll
-        for (int t = 0; t < kQuantSteps; ++t) {
-            if (t < nt && 256 * t + 4 * lane < row_elems) {
-                if (ET == 0) {
+            for (int t = 0; t < NT; ++t) {
+                if (256 * t + 4 * lane < row_elems) {
                     // two 32-bit words of two bf16 each: words 128 t + 2 lane and the next, in one granule
                     const int w = 128 * t + 2 * lane;
                     uint2 word;
@@ -149,12 +157,29 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
                     word.y = bf16_bits(v[t][2]) | (bf16_bits(v[t][3]) << 16);
                     *reinterpret_cast<uint2 *>(out + w) = word;
                     if (panel) *reinterpret_cast<uint2 *>(panel + panel_word_offset(panel_first + i, w, row_bytes)) = word;
-                } else {
+                }
+            }
+        } else {
+            const double scd = (double)sc, inv_sc = 1.0 / scd;
+            f32x4 tq[NT];
+            bool doubt2 = false;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) tq[t][c] = quotient_f32((double)v[t][c], inv_sc, doubt2);
+            if (__builtin_amdgcn_ballot_w64(doubt2) != 0ull) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) tq[t][c] = (float)((double)v[t][c] / scd);
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                if (256 * t + 4 * lane < row_elems) {
                     const int w = 64 * t + lane;
                     uint32_t word = 0u;
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        word |= e4m3_bits(quotient_f32((double)v[t][c], (double)sc, inv_sc)) << (8 * c);
+                    for (int c = 0; c < 4; ++c) word |= e4m3_bits(tq[t][c]) << (8 * c);
                     out[w] = word;
                     if (panel) *reinterpret_cast<uint32_t *>(panel + panel_word_offset(panel_first + i, w, row_bytes)) = word;
                 }
@@ -162,6 +187,40 @@ __global__ __launch_bounds__(256) void quantize_rows(const float *__restrict__ X
         }
         if (util_dst && lane == 0) util_dst[i] = util_src ? util_src[i] : 0.0f;
     }
+}
+
+// Host side: the instance for a destination row of row_bytes bytes (NT = steps of 256 columns).
+template <int ET, int NT>
+inline void launch_quantize_rows_nt(unsigned grid, hipStream_t st, const float *X, int64_t n_src, int64_t n_total, int d,
+                                    int row_bytes, uint8_t *dst, float *scale_dst, const float *util_src, float *util_dst,
+                                    uint8_t *panel, int64_t panel_first) {
+    hipLaunchKernelGGL((quantize_rows<ET, NT>), dim3(grid), dim3(256), 0, st, X, n_src, n_total, d, row_bytes, dst, scale_dst,
+                       util_src, util_dst, panel, panel_first);
+}
+
+inline void launch_quantize_rows(int et, unsigned grid, hipStream_t st, const float *X, int64_t n_src, int64_t n_total, int d,
+                                 int row_bytes, uint8_t *dst, float *scale_dst, const float *util_src, float *util_dst,
+                                 uint8_t *panel, int64_t panel_first) {
+    const int row_elems = et == 0 ? row_bytes / 2 : row_bytes;
+    const int nt = (row_elems + 255) / 256;   // 1 .. 4 for bf16 (d <= 1024), 1 .. 8 for fp8 (d <= 2048)
+#define IC_QUANT_CASE(ET, NT)                                                                                          \
+    case NT:                                                                                                           \
+        launch_quantize_rows_nt<ET, NT>(grid, st, X, n_src, n_total, d, row_bytes, dst, scale_dst, util_src, util_dst, \
+                                        panel, panel_first);                                                           \
+        break;
+    if (et == 0) {
+        switch (nt) {
+            IC_QUANT_CASE(0, 1) IC_QUANT_CASE(0, 2) IC_QUANT_CASE(0, 3) IC_QUANT_CASE(0, 4)
+            default: break;   // longer rows are refused when the index is created
+        }
+    } else {
+        switch (nt) {
+            IC_QUANT_CASE(1, 1) IC_QUANT_CASE(1, 2) IC_QUANT_CASE(1, 3) IC_QUANT_CASE(1, 4)
+            IC_QUANT_CASE(1, 5) IC_QUANT_CASE(1, 6) IC_QUANT_CASE(1, 7) IC_QUANT_CASE(1, 8)
+            default: break;
+        }
+    }
+#undef IC_QUANT_CASE
 }
 
 }  // namespace ic

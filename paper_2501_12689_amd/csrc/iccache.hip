@@ -460,13 +460,9 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
     const int grid = (int)std::min<int64_t>((n + 3) / 4, 65536);
     uint8_t *dst = index->rows + at * (int64_t)index->L.row_bytes;
     float *util_dst = index->util + at;
-    if (index->store == IC_STORE_BF16) {
-        hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, index->stream, emb_dev, n, n,
-                           index->d, index->L.row_bytes, dst, (float *)nullptr, util_dev, util_dst, index->panel, at);
-    } else {
-        hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, index->stream, emb_dev, n, n,
-                           index->d, index->L.row_bytes, dst, index->scale + at, util_dev, util_dst, index->panel, at);
-    }
+    ic::launch_quantize_rows(index->store == IC_STORE_BF16 ? 0 : 1, (unsigned)grid, index->stream, emb_dev, n, n, index->d,
+                             index->L.row_bytes, dst, index->store == IC_STORE_BF16 ? nullptr : index->scale + at, util_dev,
+                             util_dst, index->panel, at);
     hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, index->stream,
                        index->valid + at, n, (uint8_t)1);
     hipLaunchKernelGGL(ic::fill_bytes, dim3((unsigned)((n * 4 + 255) / 256)), dim3(256), 0, index->stream,
@@ -761,14 +757,8 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
         } else {
             const int grid = (q_pad + 3) / 4;
             const float *src = q_dev + q0 * (int64_t)index->d;
-            if (et == 0)
-                hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
-                                   (int64_t)q_pad, index->d, L.row_bytes, W.qbuf, (float *)nullptr,
-                                   (const float *)nullptr, (float *)nullptr, gemm ? W.qpanel : (uint8_t *)nullptr, (int64_t)0);
-            else
-                hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, src, (int64_t)qc,
-                                   (int64_t)q_pad, index->d, L.row_bytes, W.qbuf, W.qscale,
-                                   (const float *)nullptr, (float *)nullptr, gemm ? W.qpanel : (uint8_t *)nullptr, (int64_t)0);
+            ic::launch_quantize_rows(et, (unsigned)grid, st, src, (int64_t)qc, (int64_t)q_pad, index->d, L.row_bytes, W.qbuf,
+                                     et == 0 ? nullptr : W.qscale, nullptr, nullptr, gemm ? W.qpanel : nullptr, 0);
         }
 
         if (gemm && req.q_rows) {   // stored rows as queries: their step-major copy (quantize_rows writes both at once)
@@ -1382,14 +1372,8 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         if (rc != IC_OK) return rc;
         // the queries in the store's format, then one scan task per (query, list)
         const int grid = (qc + 3) / 4;
-        if (et == 0)
-            hipLaunchKernelGGL((ic::quantize_rows<0>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
-                               s->d, L.row_bytes, s->ws.qbuf, (float *)nullptr, (const float *)nullptr, (float *)nullptr,
-                               (uint8_t *)nullptr, (int64_t)0);
-        else
-            hipLaunchKernelGGL((ic::quantize_rows<1>), dim3(grid), dim3(256), 0, st, r.q_dev, (int64_t)qc, (int64_t)qc,
-                               s->d, L.row_bytes, s->ws.qbuf, s->ws.qscale, (const float *)nullptr, (float *)nullptr,
-                               (uint8_t *)nullptr, (int64_t)0);
+        ic::launch_quantize_rows(et, (unsigned)grid, st, r.q_dev, (int64_t)qc, (int64_t)qc, s->d, L.row_bytes, s->ws.qbuf,
+                                 et == 0 ? nullptr : s->ws.qscale, nullptr, nullptr, nullptr, 0);
         float *out_s = out_scores_dev + q0 * (int64_t)k;
         int64_t *out_i = out_ids_dev + q0 * (int64_t)k;
         const FinalOpts fo{-INFINITY, nullptr, -1};
