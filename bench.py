@@ -340,7 +340,8 @@ def main() -> int:
             e1.synchronize()
             cms = e0.elapsed_time(e1)
             row4 = ix4.store_view()[0].shape[1]
-            moved = (c4.N + len(ix4)) * (row4 + 4)      # every row read once, every survivor written once
+            # every row read once, every survivor written once, and once more into the step-major copy
+            moved = c4.N * (row4 + 4) + len(ix4) * (2 * row4 + 4)
             ms2, scan2, _, _ = time_search(ix4, torch, qd, c4.k, c4.lam, None, out_s, out_i, lwarm, lsteps)
             maintenance = {
                 "evicted_rows": int(gone.numel()), "rows_left": len(ix4), "compact_ms": cms,

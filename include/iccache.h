@@ -215,8 +215,10 @@ ic_status ic_self_search(const ic_index *index, int64_t first_row, int64_t count
  *                        number of rows left.  Ids change: this is the one call after which
  *                        "ids are append order" refers to the surviving rows only, and masks
  *                        given to later searches are indexed by the new ids.  Unlike the other
- *                        calls it waits for the stream (the new size is needed on the host).
- *                        Cost: the store is read and written twice, O(size).
+ *                        calls it waits for the stream (row counts are needed on the host, to
+ *                        plan the moves and as the new size).  Cost: every row is read once and
+ *                        every surviving row written once (twice in the first few chunks, and
+ *                        once more into the second copy of an index that has one), O(size).
  * Errors: INVALID_ARG, DEVICE.
  */
 ic_status ic_index_set_utility(ic_index *index, const int64_t *ids_dev, const float *util_dev, int64_t n);

@@ -116,6 +116,13 @@ __global__ __launch_bounds__(256) void write_id_map(const uint8_t *__restrict__ 
     }
 }
 
+// every stride-th block offset, for the host's plan of the moves (one small copy)
+__global__ void pick_offsets(const int64_t *__restrict__ block_offsets, int64_t stride, int count,
+                             int64_t *__restrict__ out) {
+    const int i = threadIdx.x;
+    if (i < count) out[i] = block_offsets[(int64_t)i * stride];
+}
+
 // ---- compaction, step 2: move the surviving rows of one chunk [lo, hi) of the store (lo a
 // multiple of kScanBlock; hi too, or hi = size).  Chunks are processed in order, one pair of
 // launches each.  Once at least a chunk's worth of rows has been dropped before the chunk, its
@@ -126,13 +133,16 @@ __global__ __launch_bounds__(256) void write_id_map(const uint8_t *__restrict__ 
 __device__ __forceinline__ bool chunk_moves_directly(int64_t lo, int64_t hi, int64_t first_new) {
     return lo - first_new >= hi - lo;
 }
+// If the index keeps a step-major copy (panel != NULL) a moved row is written to its new place there as
+// well (by gather_rows when the chunk moves directly, by store_rows otherwise): the copy is a different
+// buffer, so it has no overlap to mind, and nothing has to be read twice to rebuild it.
 __global__ __launch_bounds__(256) void gather_rows(const uint8_t *rows, int row_bytes,
                                                    const int64_t *__restrict__ id_map,
                                                    const int64_t *__restrict__ block_offsets, int64_t lo,
-                                                   int64_t hi, uint8_t *bounce) {
+                                                   int64_t hi, uint8_t *bounce, uint8_t *panel) {
     const int64_t first_new = block_offsets[lo / kScanBlock];
-    uint8_t *out = chunk_moves_directly(lo, hi, first_new) ? const_cast<uint8_t *>(rows) + first_new * (int64_t)row_bytes
-                                                           : bounce;
+    const bool direct = chunk_moves_directly(lo, hi, first_new);
+    uint8_t *out = direct ? const_cast<uint8_t *>(rows) + first_new * (int64_t)row_bytes : bounce;
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * 4;
@@ -141,21 +151,33 @@ __global__ __launch_bounds__(256) void gather_rows(const uint8_t *rows, int row_
         if (to < 0) continue;
         const i32x4 *src = reinterpret_cast<const i32x4 *>(rows + r * (int64_t)row_bytes);
         i32x4 *dst = reinterpret_cast<i32x4 *>(out + (to - first_new) * (int64_t)row_bytes);
-        for (int c = lane; c < row_bytes / 16; c += 64) dst[c] = src[c];
+        for (int c = lane; c < row_bytes / 16; c += 64) {
+            const i32x4 g = src[c];
+            dst[c] = g;
+            if (direct && panel) *reinterpret_cast<i32x4 *>(panel + panel_word_offset(to, c * 4, row_bytes)) = g;
+        }
     }
 }
 
 __global__ __launch_bounds__(256) void store_rows(uint8_t *__restrict__ rows, int row_bytes,
                                                   const int64_t *__restrict__ block_offsets, int64_t lo,
                                                   int64_t hi, int64_t hi_block,
-                                                  const uint8_t *__restrict__ bounce) {
+                                                  const uint8_t *__restrict__ bounce, uint8_t *__restrict__ panel) {
     const int64_t first_new = block_offsets[lo / kScanBlock];
     if (chunk_moves_directly(lo, hi, first_new)) return;
     const int64_t count = block_offsets[hi_block] - first_new;
-    const int64_t vecs = count * (int64_t)(row_bytes / 16);
+    const int per_row = row_bytes / 16;
+    const int64_t vecs = count * (int64_t)per_row;
     const i32x4 *src = reinterpret_cast<const i32x4 *>(bounce);
     i32x4 *dst = reinterpret_cast<i32x4 *>(rows + first_new * (int64_t)row_bytes);
-    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < vecs; v += (int64_t)gridDim.x * 256) dst[v] = src[v];
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < vecs; v += (int64_t)gridDim.x * 256) {
+        const i32x4 g = src[v];
+        dst[v] = g;
+        if (panel) {
+            const int64_t row = first_new + v / per_row;
+            *reinterpret_cast<i32x4 *>(panel + panel_word_offset(row, (int)(v % per_row) * 4, row_bytes)) = g;
+        }
+    }
 }
 
 // per-row fp32 side arrays (utility, fp8 scale): scatter into a scratch array, then copy back

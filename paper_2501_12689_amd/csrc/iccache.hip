@@ -527,12 +527,37 @@ ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_si
     const int64_t chunk = std::max<int64_t>(ic::kScanBlock,
                                             (int64_t)(bounce_bytes / (size_t)L.row_bytes) / ic::kScanBlock * ic::kScanBlock);
     const int grid = std::max(8, index->compute_units) * 4;
-    for (int64_t lo = 0; lo < n; lo += chunk) {
-        const int64_t hi = std::min(n, lo + chunk);
-        hipLaunchKernelGGL(ic::gather_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, id_map_dev, offs,
-                           lo, hi, bounce);
-        hipLaunchKernelGGL(ic::store_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, offs, lo, hi,
-                           (hi + ic::kScanBlock - 1) / ic::kScanBlock, bounce);
+    // A few block offsets come to the host (this call synchronises anyway): every `stride`-th, at most 64 of
+    // them, which is a copy small enough to take the driver's quick path.  With the number of rows dropped
+    // before a chunk known, a chunk that moves directly can be as long as that number, so the chunks grow as
+    // the gap widens and a few dozen launches do what fixed chunks need hundreds for.  Between two sampled
+    // offsets the chunks have the fixed size and the kernels decide for themselves, as they always can.
+    int64_t stride = chunk / ic::kScanBlock;                 // in blocks; sampled positions are chunk boundaries
+    while ((nblocks + stride - 1) / stride > 64) stride *= 2;
+    const int picked = (int)((nblocks + stride - 1) / stride);
+    int64_t *picked_dev = reinterpret_cast<int64_t *>(index->ws.bias);   // scratch of the searches, not in use here yet
+    int64_t picked_h[64];
+    hipLaunchKernelGGL(ic::pick_offsets, dim3(1), dim3(64), 0, st, offs, stride, picked, picked_dev);
+    if (hipMemcpyAsync(picked_h, picked_dev, (size_t)picked * sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return IC_ERR_DEVICE;
+    const int64_t span = stride * ic::kScanBlock;            // rows between two sampled offsets
+    for (int64_t lo = 0; lo < n;) {
+        int64_t hi = std::min(n, lo + chunk);
+        bool direct = false;
+        if (lo % span == 0) {
+            const int64_t dropped = lo - picked_h[lo / span];
+            if (dropped >= span) {   // gather_rows sees lo - first_new >= hi - lo and writes the rows in place
+                hi = std::min(n, lo + dropped / span * span);
+                direct = true;
+            }
+        }
+        hipLaunchKernelGGL(ic::gather_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, id_map_dev, offs, lo, hi,
+                           bounce, index->panel);
+        if (!direct)
+            hipLaunchKernelGGL(ic::store_rows, dim3(grid), dim3(256), 0, st, index->rows, L.row_bytes, offs, lo, hi,
+                               (hi + ic::kScanBlock - 1) / ic::kScanBlock, bounce, index->panel);
+        lo = hi;
     }
     // side arrays through the per-search bias scratch
     const unsigned g1 = (unsigned)((n + 255) / 256);
@@ -553,7 +578,7 @@ ic_status ic_index_compact(ic_index *index, int64_t *id_map_dev, int64_t *new_si
     index->n = total;
     index->any_invalid = false;
     if (new_size) *new_size = total;
-    if (index->panel) panel_rows(index, 0, total);   // every surviving row may have moved
+    if (index->panel) panel_rows(index, total, total);   // the moved rows wrote their copies; the rest of the last tile is zeroed
     return hipGetLastError() == hipSuccess ? IC_OK : IC_ERR_DEVICE;
 }
 
