@@ -1383,9 +1383,13 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
                            (const float *)s->util, (const uint8_t *)nullptr, (const uint8_t *)nullptr, n, n_pad, lambda,
                            s->ws.bias);
     }
-    // slices per list: about 12 tiles of 16 rows each, at most 16 slices
+    // slices per list: about 12 tiles of 16 rows each, at most 16 slices; with few (query, list) tasks more,
+    // up to 64 and down to 2 tiles of an average list, so that about 4096 workgroups are launched: lists are
+    // uneven (a head cluster's can be 20 times the average), and the longest one sets the time of the launch
     const int64_t avg_tiles = std::max<int64_t>(1, n / std::max<int64_t>(1, ivf->K) / 16);
-    const int S = (int)std::min<int64_t>(16, std::max<int64_t>(1, avg_tiles / 12));
+    const int64_t tasks = std::min<int64_t>(Q, std::min<int64_t>(L.q_chunk, ivf->base->L.q_chunk)) * nprobe;
+    const int64_t by_tasks = std::min<int64_t>(std::min<int64_t>(64, 4096 / std::max<int64_t>(1, tasks)), avg_tiles / 2);
+    const int S = (int)std::max<int64_t>(std::min<int64_t>(16, std::max<int64_t>(1, avg_tiles / 12)), by_tasks);
     const int64_t qmax = std::min<int64_t>(std::min<int64_t>(L.q_chunk, ivf->base->L.q_chunk),
                                            std::max<int64_t>(1, kRegionSlots / ((int64_t)nprobe * S)));
     for (int64_t q0 = 0; q0 < Q; q0 += qmax) {
