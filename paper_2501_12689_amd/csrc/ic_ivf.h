@@ -8,8 +8,107 @@
 // update step (mean direction of every cluster).
 #pragma once
 #include "ic_common.h"
+#include "ic_merge.h"
 
 namespace ic {
+
+// ---- online part: the (query, list) pairs of a batch, grouped by list --------------------------------
+//
+// A list that several queries of a batch probe is read once for up to 16 of them: the pairs are sorted by
+// list, and every run of equal lists is cut into tasks of at most 16 pairs.  One workgroup; at most
+// kTaskPairs pairs.  probe[p] is the list of pair p (pair = query * nprobe + rank; a value outside
+// [0, K) means no list).  task_list[t] = the list of task t, task_pair[16 t + j] = the pair in slot j of
+// task t, -1 where there is none; both hold `pairs` tasks, the most there can be.  The order of the tasks
+// and of the pairs inside a task is fixed by the sort (descending list id, descending pair), so a search
+// does the same thing every time it is run.  The kernel also zeroes region_counts[0, n_counts), the
+// per-(pair, slice) counts that the scan tasks then fill in for the pairs they serve.
+constexpr int kTaskPairs = kMergeKeys;   // pairs of one pass: what one workgroup sorts at once
+constexpr int kTaskSlots = 16;           // query slots of a task (= the queries of a scan workgroup)
+
+// R = sorted keys per thread: 256 R >= pairs.
+template <int R>
+__global__ __launch_bounds__(256) void ivf_group_tasks(const int64_t *__restrict__ probe, int pairs, int32_t K,
+                                                       int64_t *__restrict__ task_list, int32_t *__restrict__ task_pair,
+                                                       int32_t *__restrict__ region_counts, int n_counts) {
+    __shared__ uint64_t key[kMergeKeys];
+    __shared__ int32_t part[2][256];
+    const int tid = threadIdx.x;
+    // (the barriers of the sort below order these stores before the ones that fill the tasks in)
+    for (int i = tid; i < pairs; i += 256) task_list[i] = -1;
+    for (int i = tid; i < pairs * kTaskSlots; i += 256) task_pair[i] = -1;
+    for (int i = tid; i < n_counts; i += 256) region_counts[i] = 0;
+    // key = (list + 1, pair); 0 for a pair without a list and for the padding: those sort to the end
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int p = R * tid + r;
+        uint64_t k64 = 0ull;
+        if (p < pairs) {
+            const int64_t c = probe[p];
+            if (c >= 0 && c < K) k64 = ((uint64_t)(c + 1) << 32) | (uint64_t)(uint32_t)p;
+        }
+        key[p] = k64;
+    }
+    __syncthreads();
+    sort_buffer<R>(key, tid);
+    // element e = R tid + r of the sorted keys.  head: first pair of its list.  Every thread finds, for its
+    // elements, the start of the run they are in (a prefix maximum over the heads' positions) ...
+    uint64_t mine[R];
+    int head_at[R];   // position of the last head at or before the element, -1 if none in this thread yet
+#pragma unroll
+    for (int r = 0; r < R; ++r) mine[r] = key[R * tid + r];
+    const uint64_t before = tid > 0 ? key[R * tid - 1] : 0ull;
+    int last_head = -1;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint64_t prev = r > 0 ? mine[r - 1] : before;
+        const bool head = mine[r] != 0ull && (R * tid + r == 0 || (prev >> 32) != (mine[r] >> 32));
+        if (head) last_head = R * tid + r;
+        head_at[r] = last_head;
+    }
+    // exclusive prefix maximum of last_head over the threads
+    int src = 0;
+    part[0][tid] = last_head;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const int v = part[src][tid];
+        const int o = tid >= off ? part[src][tid - off] : -1;
+        part[src ^ 1][tid] = v > o ? v : o;
+        src ^= 1;
+        __syncthreads();
+    }
+    const int head_before = tid > 0 ? part[src][tid - 1] : -1;
+    __syncthreads();
+    // ... then which of them open a task (every 16th pair of a run), and how many tasks were opened before
+    int opens = 0;
+    bool open[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int start = head_at[r] >= 0 ? head_at[r] : head_before;
+        open[r] = mine[r] != 0ull && ((R * tid + r - start) % kTaskSlots) == 0;
+        head_at[r] = start;
+        opens += open[r] ? 1 : 0;
+    }
+    src = 0;
+    part[0][tid] = opens;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const int v = part[src][tid];
+        const int o = tid >= off ? part[src][tid - off] : 0;
+        part[src ^ 1][tid] = v + o;
+        src ^= 1;
+        __syncthreads();
+    }
+    int task = (tid > 0 ? part[src][tid - 1] : 0) - 1;   // index of the task open before this thread's first element
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (mine[r] == 0ull) continue;
+        if (open[r]) {
+            ++task;
+            task_list[task] = (int64_t)(mine[r] >> 32) - 1;
+        }
+        task_pair[task * kTaskSlots + (R * tid + r - head_at[r]) % kTaskSlots] = (int32_t)(uint32_t)mine[r];
+    }
+}
 
 // assign[i] = cluster of row i from its key (score of the best centroid, its id); 0 = no key: -1
 __global__ void ivf_take_assignment(const uint64_t *__restrict__ keys, int64_t n, int32_t *__restrict__ assign) {

@@ -77,12 +77,16 @@ struct ScanArgs {
     // score lies that close to s has |b| <= |s| + 1, and rows further above s pass anyway.  A lower
     // start only admits more candidates, the selection stays exact.
     float thr_slack;
-    // Task launches (TASK = true, one query group): workgroup column y is a (query, list) pair of a
-    // cluster-pruned search.  Query y / task_nprobe is compared with the rows of one cluster, the
-    // contiguous range [offsets[c], offsets[c + 1]) of a store sorted by cluster, c =
-    // task_cluster[y] (-1: no list).  regions / counts are indexed by y instead of the query.
+    // Task launches (TASK = true, one query group): workgroup column y is one list of a cluster-pruned
+    // search together with up to 16 (query, list) pairs that probe it, so that the list is read once
+    // for all of them.  The list is the contiguous range [offsets[c], offsets[c + 1]) of a store sorted
+    // by cluster, c = task_cluster[y] (-1: no task).  Query slot j of the workgroup serves pair
+    // task_pair[16 y + j] (-1: empty slot), i.e. query pair / task_nprobe; regions / counts are indexed
+    // by the pair instead of the query, and the counts of pairs no task serves are left as the caller
+    // set them (zero).
     const int64_t *task_cluster;
     const int64_t *task_offsets;
+    const int32_t *task_pair;
     int task_nprobe;
     // Sharing domains (DOM = true): row i is visible to query q if row_dom[i] == 0 (public) or
     // row_dom[i] == q_dom[q].  row_dom is [round_up(n,16)] int32, q_dom [Q] int32.
@@ -198,10 +202,7 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
         const int64_t c = a.task_cluster[qb];
         row_lo = c >= 0 ? a.task_offsets[c] : 0;
         row_hi = c >= 0 ? a.task_offsets[c + 1] : 0;
-        if (row_lo >= row_hi) {  // no list, or an empty one: nothing to hand to the merge
-            if (tid == 0) a.counts[(int64_t)qb * a.S + s] = 0;
-            return;
-        }
+        if (row_lo >= row_hi) return;  // no task, or an empty list: the pairs' counts stay zero
     }
     const int nchunks = a.row_bytes >> 6;
     const int chunk0 = w * CPW;
@@ -238,12 +239,15 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     const int l8 = lane >> 3;   // line mode: row within a half tile, and the lane's 16 bytes of the line
     const int p8 = lane & 7;
 
+    // task launches: the pair and the query of this lane's slot
+    const int task_p = TASK ? a.task_pair[(int64_t)qb * 16 + r16] : -1;
+    const int task_q = task_p >= 0 ? task_p / a.task_nprobe : 0;
     // query fragments owned by this wavefront, resident for the whole kernel
     i32x4 qf[QG][CPW];
 #pragma unroll
     for (int g = 0; g < QG; ++g) {
-        // task launches: all 16 query slots hold the task's one query (slot 0 is the one that counts)
-        const uint8_t *qrow = a.qbuf + (int64_t)(TASK ? qb / a.task_nprobe : qb * QB + g * 16 + r16) * a.row_bytes + c4 * 16;
+        // task launches: slot r16 holds the query of the pair it serves (an empty slot: query 0, never live)
+        const uint8_t *qrow = a.qbuf + (int64_t)(TASK ? task_q : qb * QB + g * 16 + r16) * a.row_bytes + c4 * 16;
 #pragma unroll
         for (int c = 0; c < CPW; ++c) {
             qf[g][c] = *reinterpret_cast<const i32x4 *>(qrow + coff[c]);
@@ -253,8 +257,8 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
 
     // selection state of the query this lane serves in the epilogue (wave g == w)
     const int jl = (w < QG ? w : 0) * 16 + r16;  // query within block
-    const int jq = TASK ? qb / a.task_nprobe : qb * QB + jl;  // query within this launch
-    const bool q_live = (w < QG) && (jq < a.Q) && (!TASK || r16 == 0);
+    const int jq = TASK ? task_q : qb * QB + jl;  // query within this launch
+    const bool q_live = (w < QG) && (jq < a.Q) && (!TASK || task_p >= 0);
     float q_scale = 1.0f;
     if (ET == 1 && q_live) q_scale = a.q_scale[jq];
     int q_dom = 0;
@@ -503,9 +507,10 @@ __global__ __launch_bounds__(256) void scan_stream(const ScanArgs a) {
     }
     // hand the regions to the merge kernel
     if (w < QG) {
-        for (int j = 0; j < (TASK ? 1 : 16); ++j) {  // task launches: only slot 0 holds a result
+        for (int j = 0; j < 16; ++j) {
             const int ql = w * 16 + j;
-            const int qq = TASK ? qb : qb * QB + ql;     // row of regions / counts
+            const int qq = TASK ? a.task_pair[(int64_t)qb * 16 + j] : qb * QB + ql;     // row of regions / counts
+            if (TASK && qq < 0) continue;   // empty slot
             if (!TASK && qq >= a.Q) break;
             uint32_t c = __hip_atomic_load(&cnt[ql], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
             if (c > (uint32_t)a.cap) c = (uint32_t)a.cap;

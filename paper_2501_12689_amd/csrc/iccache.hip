@@ -1121,6 +1121,8 @@ struct ic_ivf {
     float *tmp_scores;
     int64_t *probe_ids;  // [query chunk, max_probe]
     float *probe_scores;
+    int64_t *task_list;  // [kTaskPairs] list of every scan task of a pass
+    int32_t *task_pair;  // [kTaskPairs, kTaskSlots] (query, list) pairs a task serves
     bool lists_ready;
 };
 
@@ -1131,7 +1133,7 @@ constexpr int kIvfShares = 16;             // workgroups that share the rows of 
 struct IvfLayout {
     size_t off_cent = 0, off_sorted = 0, off_assign = 0, off_perm = 0, off_counts = 0, off_offsets = 0,
            off_cursor = 0, off_sums = 0, off_acc64 = 0, off_tmp_ids = 0, off_tmp_scores = 0, off_probe_ids = 0,
-           off_probe_scores = 0, total = 0;
+           off_probe_scores = 0, off_task_list = 0, off_task_pair = 0, total = 0;
     size_t cent_bytes = 0, sorted_bytes = 0;
 };
 
@@ -1161,6 +1163,8 @@ bool make_ivf_layout(const ic_index *base, int32_t K, int32_t max_probe, IvfLayo
     V.off_tmp_scores = take(cap * 4);
     V.off_probe_ids = take((size_t)base->L.q_chunk * (size_t)max_probe * 8);
     V.off_probe_scores = take((size_t)base->L.q_chunk * (size_t)max_probe * 4);
+    V.off_task_list = take((size_t)ic::kTaskPairs * 8);
+    V.off_task_pair = take((size_t)ic::kTaskPairs * ic::kTaskSlots * 4);
     V.total = off;
     return true;
 }
@@ -1239,6 +1243,8 @@ ic_status ic_ivf_create(ic_ivf **out, ic_index *base, int32_t K, int32_t max_pro
     v->tmp_scores = (float *)(p + V.off_tmp_scores);
     v->probe_ids = (int64_t *)(p + V.off_probe_ids);
     v->probe_scores = (float *)(p + V.off_probe_scores);
+    v->task_list = (int64_t *)(p + V.off_task_list);
+    v->task_pair = (int32_t *)(p + V.off_task_pair);
     v->lists_ready = false;
     *out = v;
     return IC_OK;
@@ -1390,8 +1396,11 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
     const int64_t tasks = std::min<int64_t>(Q, std::min<int64_t>(L.q_chunk, ivf->base->L.q_chunk)) * nprobe;
     const int64_t by_tasks = std::min<int64_t>(std::min<int64_t>(64, 4096 / std::max<int64_t>(1, tasks)), avg_tiles / 2);
     const int S = (int)std::max<int64_t>(std::min<int64_t>(16, std::max<int64_t>(1, avg_tiles / 12)), by_tasks);
-    const int64_t qmax = std::min<int64_t>(std::min<int64_t>(L.q_chunk, ivf->base->L.q_chunk),
-                                           std::max<int64_t>(1, kRegionSlots / ((int64_t)nprobe * S)));
+    // a pass takes as many queries as the candidate regions hold (one per pair and slice) and as one
+    // workgroup can group by list (kTaskPairs pairs)
+    const int64_t qmax = std::min<int64_t>(std::min<int64_t>(std::min<int64_t>(L.q_chunk, ivf->base->L.q_chunk),
+                                                             std::max<int64_t>(1, kRegionSlots / ((int64_t)nprobe * S))),
+                                           std::max<int64_t>(1, ic::kTaskPairs / nprobe));
     for (int64_t q0 = 0; q0 < Q; q0 += qmax) {
         const int qc = (int)std::min<int64_t>(qmax, Q - q0);
         // the nprobe nearest centroids of every query
@@ -1435,10 +1444,17 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         a.regions = s->ws.regions;
         a.counts = s->ws.counts;
         a.tile_mul = 1;
-        a.task_cluster = ivf->probe_ids;
+        // the pairs grouped by list: a list that several queries probe is read once for up to 16 of them
+        const int pairs = qc * nprobe;
+        auto group = pairs <= 256 ? ic::ivf_group_tasks<1> : pairs <= 512 ? ic::ivf_group_tasks<2>
+                   : pairs <= 1024 ? ic::ivf_group_tasks<4> : ic::ivf_group_tasks<8>;   // the sort is sized to the pairs
+        hipLaunchKernelGGL(group, dim3(1), dim3(256), 0, st, (const int64_t *)ivf->probe_ids, pairs, ivf->K, ivf->task_list,
+                           ivf->task_pair, s->ws.counts, pairs * S);
+        a.task_cluster = ivf->task_list;
         a.task_offsets = ivf->offsets;
+        a.task_pair = ivf->task_pair;
         a.task_nprobe = nprobe;
-        kTaskTable[et][cpw - 1](dim3(S, qc * nprobe), st, a);
+        kTaskTable[et][cpw - 1](dim3(S, pairs), st, a);
         m.q_stride = (int64_t)nprobe * S * cap;
         m.nseg = nprobe * S;
         m.id_map = ivf->perm;

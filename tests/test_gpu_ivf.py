@@ -269,6 +269,43 @@ def test_pruned_search_on_drawn_shapes(pkg, oracle, case):
             assert np.all(np.isin(assign[got], order[q, :nprobe + 1])) and np.all(live[got])
 
 
+@pytest.mark.parametrize("store", ["bf16", "fp8"])
+def test_pruned_search_does_not_depend_on_the_batch(pkg, oracle, store):
+    """Queries of a batch that probe the same list share one read of it, up to 16 to a scan task.  With
+    6 clusters and 100 queries every list is probed by far more than 16 queries, so lists are served by
+    several full tasks and a ragged one; every query must get exactly what it gets when searched alone
+    or in small batches (each score is the same sum whatever slot the query sits in), and what the
+    reference finds in the probed lists."""
+    _say(f"ivf search, shared lists, {store}")
+    cfg, wl, ix, E, U = _setup(pkg, store, N=30000, d=160, C=6, seed=9660)
+    K, nprobe, k, lam = 6, 2, 12, 0.2
+    C = wl.centres.numpy()
+    assign = oracle.ivf_assign(E, C)
+    ivf = pkg.Ivf(ix, K, 4)
+    ivf.set_centroids(torch.from_numpy(C).to(DEV))
+    ivf.set_assignment(torch.from_numpy(assign).to(DEV))
+    Qm = wl.queries(100).numpy()
+    qd = torch.from_numpy(Qm).to(DEV)
+    s, i = ivf.search(qd, k, nprobe, lam)
+    torch.cuda.synchronize()
+    gs, gi = s.cpu().numpy(), i.cpu().numpy()
+    for step in (1, 7):
+        for q0 in list(range(0, 100, step))[:: (9 if step == 1 else 3)]:
+            s1, i1 = ivf.search(qd[q0:q0 + step].contiguous(), k, nprobe, lam)
+            torch.cuda.synchronize()
+            assert np.array_equal(i1.cpu().numpy(), gi[q0:q0 + step]) and np.array_equal(s1.cpu().numpy(), gs[q0:q0 + step]), (step, q0)
+    cs = oracle.scores(C, Qm)
+    order = np.argsort(-cs, axis=1, kind="stable")
+    checked = 0
+    for q in range(0, 100, 5):
+        if cs[q, order[q, nprobe - 1]] - cs[q, order[q, nprobe]] > (5e-3 if store == "bf16" else 3e-2):
+            members = np.isin(assign, order[q, :nprobe]).astype(np.uint8)
+            parity.check_batch(store, gs[q:q + 1], gi[q:q + 1], E, U, members, Qm[q:q + 1], k, lam, f"shared lists q={q}")
+            checked += 1
+    assert checked >= 10, checked
+    ivf.close(); ix.close()
+
+
 def test_many_centroids_and_a_large_batch_take_the_tiled_scan(pkg, oracle):
     """With 16,400 centroids and 200 queries the probe step (nearest centroids of every query) is a
     batch large enough for the MFMA-tiled scan over the centroid index, whose step-major copy is
