@@ -1408,7 +1408,7 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
         r.q_dev = q_dev + q0 * (int64_t)s->d;
         ic_status rc = search_impl(c, c->ws, qc, nprobe, 0.0f, nullptr, ivf->probe_scores, ivf->probe_ids, r);
         if (rc != IC_OK) return rc;
-        // the queries in the store's format, then one scan task per (query, list)
+        // the queries in the store's format, then scan tasks: one per list and up to 16 queries that probe it
         const int grid = (qc + 3) / 4;
         ic::launch_quantize_rows(et, (unsigned)grid, st, r.q_dev, (int64_t)qc, (int64_t)qc, s->d, L.row_bytes, s->ws.qbuf,
                                  et == 0 ? nullptr : s->ws.qscale, nullptr, nullptr, nullptr, 0);
