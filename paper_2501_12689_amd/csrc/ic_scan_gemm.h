@@ -627,42 +627,47 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
         if (ROWMAX) {
             // Row maxima: for each of the tile's rows the best of this block's queries.  A row's
             // positive scale does not change which query is best, so only the queries' scales enter.
-            // A lane holds 4 queries of 32 rows; it keeps the best key per row, the 32 lanes that
-            // share those rows combine theirs with a butterfly, and lane r32 of the group adds the
-            // key of the group's r32-th row to that row's key in global memory (64-bit atomic
-            // maximum; the other query blocks and the other half of this block do the same).
-            uint64_t best[2][16];
+            // A lane holds 4 queries of 32 rows.  It first picks, per row, the best of its 4 queries on
+            // the fp32 scores (equal scores: the lower query) and only then forms the row's 64-bit key.
+            // The 32 lanes that share those rows combine their keys with a butterfly that halves the
+            // values a lane carries at every step (a lane keeps the rows whose index has its own lane
+            // bit and hands the others to its partner: 16 + 8 + 4 + 2 + 1 exchanges instead of 5 x 32),
+            // which leaves lane r32 of the group with the finished key of the group's r32-th row; it
+            // adds that key to the row's key in global memory (64-bit atomic maximum; the other query
+            // blocks and the other half of this block do the same).
+            int qn[4];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) best[i][v] = 0ull;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
-                if (q < a.Q) {
-#pragma unroll
-                    for (int i = 0; i < 2; ++i)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const float x = (ET == 1) ? acc[i][j][v] * qs[j] : acc[i][j][v];
-                            const uint64_t key = make_key(x, (uint32_t)q);
-                            best[i][v] = key > best[i][v] ? key : best[i][v];
-                        }
-                }
-            }
-            uint64_t mine = 0ull;
+            for (int j = 0; j < 4; ++j) qn[j] = qb * kGemmTile + wn * 128 + j * 32 + r32;
+            uint64_t val[32];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    uint64_t k64 = best[i][v];
+                    float bs = -INFINITY;
+                    int bq = -1;
 #pragma unroll
-                    for (int m = 1; m < 32; m <<= 1) {
-                        const uint64_t o = __shfl_xor(k64, m, kWave);
-                        k64 = o > k64 ? o : k64;
+                    for (int j = 3; j >= 0; --j) {   // downwards: on equal scores the lower query stays
+                        const float x = (ET == 1) ? acc[i][j][v] * qs[j] : acc[i][j][v];
+                        if (qn[j] < a.Q && (bq < 0 || x >= bs)) {
+                            bs = x;
+                            bq = qn[j];
+                        }
                     }
-                    if (r32 == i * 16 + v) mine = k64;
+                    val[i * 16 + v] = bq >= 0 ? make_key(bs, (uint32_t)bq) : 0ull;
                 }
+#pragma unroll
+            for (int bit = 4; bit >= 0; --bit) {
+                const int half = 1 << bit;                     // values a lane still carries after this step
+                const bool upper = ((r32 >> bit) & 1) != 0;    // this lane keeps the upper half of what it carries
+#pragma unroll
+                for (int t = 0; t < half; ++t) {
+                    const uint64_t keep = upper ? val[half + t] : val[t];
+                    const uint64_t send = upper ? val[t] : val[half + t];
+                    const uint64_t got = __shfl_xor(send, half, kWave);   // the partner keeps the other half
+                    val[t] = keep > got ? keep : got;
+                }
+            }
+            const uint64_t mine = val[0];   // row index r32 = i * 16 + v of this group's rows
             {
                 const int i = r32 >> 4, v = r32 & 15;
                 const int r = wm * 64 + i * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
