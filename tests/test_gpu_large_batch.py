@@ -131,6 +131,33 @@ def test_tiled_scan_on_drawn_shapes(pkg, oracle, case):
                        f"{case}", queries=sample)
 
 
+@pytest.mark.parametrize("store,N,Q,k", [("bf16", 20000, 300, 16), ("fp8", 70000, 200, 24), ("bf16", 270000, 130, 64)])
+def test_tiled_scan_with_hardly_any_valid_row(pkg, oracle, store, N, Q, k):
+    """Masks that leave 0, 1, k - 1, k, k + 1 and 300 valid rows: fewer valid rows than k means no pilot
+    threshold exists (every block of every tile is listed and the tiles are done again score by score),
+    the result is what there is, padded with (-inf, -1)."""
+    _say(f"tiled scan, nearly everything masked, {store} N={N} Q={Q} k={k}")
+    cfg = workloads.Config("M", N=N, d=96, clusters=8, Q=Q, k=k, store=store, zipf=1.1, lam=0.2, util="uniform", seed=8400)
+    wl = workloads.Workload(cfg, "cpu")
+    E, U, _ = wl.rows(0, N)
+    Qm = wl.queries()
+    ix = pkg.Index(96, N, pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3, Q, 128, DEV)
+    ix.append(E.to(DEV), U.to(DEV))
+    rng = np.random.default_rng(N)
+    for n_valid in (0, 1, k - 1, k, k + 1, 300):
+        M = np.zeros(N, np.uint8)
+        M[rng.choice(N, n_valid, replace=False)] = 1
+        s, i = ix.search(Qm.to(DEV), k, 0.2, torch.from_numpy(M).to(DEV))
+        torch.cuda.synchronize()
+        s, i = s.cpu().numpy(), i.cpu().numpy()
+        assert ((i >= 0).sum(1) == min(k, n_valid)).all(), n_valid
+        assert np.all(np.isneginf(s[i < 0])), n_valid
+        if n_valid:
+            parity.check_batch(store, s, i, E.numpy(), U.numpy(), M, Qm.numpy(), k, 0.2, f"{n_valid} valid rows",
+                               queries=[0, Q // 2, Q - 1])
+    ix.close()
+
+
 def test_large_batch_list_overflow_is_redone_exactly(pkg, oracle):
     """Candidate lists shrunk to 8 keys: every block overflows and is redone by the streaming scan."""
     _say("tiled scan, forced list overflow")
