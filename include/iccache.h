@@ -111,7 +111,9 @@ ic_status ic_index_append(ic_index *index, const float *emb_dev, const float *ut
  * Top-k selection for Q queries (GetSimilarExamples, Algorithm 1).
  *   q_dev           [Q, d] fp32 row-major; rows need not be unit length
  *   k               1 .. max_k given at creation
- *   lambda          weight of the stored utility (0 = pure cosine)
+ *   lambda          weight of the stored utility (0 = pure cosine); any sign and size as long
+ *                   as lambda * utility stays above -1e30 (a score at or below that is
+ *                   treated as no score, like a masked row's)
  *   mask_dev        [size] uint8, nonzero = valid, shared by all queries; NULL =
  *                   all rows valid.  size is the index size at the time of call.
  *   out_scores_dev  [Q, k] fp32; out_ids_dev [Q, k] int64.  Rows are sorted by

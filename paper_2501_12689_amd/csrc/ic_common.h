@@ -37,6 +37,11 @@ __device__ __forceinline__ uint64_t make_key(float s, uint32_t id) {
     return ((uint64_t)ord_of_score(s) << 32) | (uint64_t)(0xFFFFFFFFu - id);
 }
 __device__ __forceinline__ float key_score(uint64_t key) { return score_of_ord((uint32_t)(key >> 32)); }
+// Starting threshold of a query whose pilot found fewer than k rows with a score: a score below every
+// real one (cosines lie in [-1, 1] and lambda * utility is taken to stay above -1e30) and above -inf, the
+// score of masked, evicted and invisible rows.  Every row with a score passes it, no row without one does,
+// so a mask that leaves a handful of rows leaves the scans' candidate lists nearly empty instead of full.
+constexpr float kNoThresholdScore = -1e30f;
 __device__ __forceinline__ uint32_t key_id(uint64_t key) { return 0xFFFFFFFFu - (uint32_t)key; }
 
 // ---------------------------------------------------------------------------

@@ -35,7 +35,7 @@ struct MergeArgs {
     uint64_t *dst;              // non-final: lists [Q][gridDim.y][k]
     float *out_scores;          // final: [Q][k], or NULL
     int64_t *out_ids;           // final: [Q][k], or NULL
-    uint64_t *kth_out;          // final: [Q] key of the k-th best (0 if there are fewer), or NULL
+    uint64_t *kth_out;          // final: [Q] key of the k-th best (a key of kNoThresholdScore if there are fewer), or NULL
     const int32_t *only_flagged;  // if not NULL, queries whose block of 64 has flag 0 are left alone
     float min_score;            // final: entries whose score is below it are dropped (-inf: none)
     int32_t *out_counts;        // final: [Q] entries kept, or NULL
@@ -239,7 +239,10 @@ __global__ __launch_bounds__(256) void merge_lists(const MergeArgs a) {
             if (!none) atomicAdd(&kept, 1);
         }
     }
-    if (!a.dst && a.kth_out && tid == 0) a.kth_out[q] = buf[a.k - 1];
+    if (!a.dst && a.kth_out && tid == 0) {
+        const uint64_t kth = buf[a.k - 1];
+        a.kth_out[q] = kth > kKeyFloor ? kth : make_key(kNoThresholdScore, 0u);
+    }
     if (!a.dst && a.out_scores && a.out_counts) {
         __syncthreads();
         if (tid == 0) a.out_counts[q] = kept;

@@ -86,7 +86,7 @@ struct GemmArgs {
     const uint8_t *qbuf;     // prepared queries, [nqb*256] rows
     const float *q_scale;    // fp8: per prepared query
     int Q;                   // real queries
-    const uint64_t *thr_init;  // [Q] key of a score that >= k rows reach (0: none)
+    const uint64_t *thr_init;  // [Q] key of a score that >= k rows reach (or of kNoThresholdScore: every row with a score passes)
     uint64_t *glist;         // [Q][gcap] candidate keys
     int gcap;
     int32_t *gcount;         // [Q] candidates appended (may exceed gcap: the list overflowed)

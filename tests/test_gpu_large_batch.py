@@ -133,9 +133,10 @@ def test_tiled_scan_on_drawn_shapes(pkg, oracle, case):
 
 @pytest.mark.parametrize("store,N,Q,k", [("bf16", 20000, 300, 16), ("fp8", 70000, 200, 24), ("bf16", 270000, 130, 64)])
 def test_tiled_scan_with_hardly_any_valid_row(pkg, oracle, store, N, Q, k):
-    """Masks that leave 0, 1, k - 1, k, k + 1 and 300 valid rows: fewer valid rows than k means no pilot
-    threshold exists (every block of every tile is listed and the tiles are done again score by score),
-    the result is what there is, padded with (-inf, -1)."""
+    """Masks that leave 0, 1, k - 1, k, k + 1 and 300 valid rows: with fewer valid rows than k the pilot
+    has no k-th score to hand over and the scan starts from a floor below every real score, which masked
+    rows (score -inf) do not pass: the result is what there is, padded with (-inf, -1), and only tiles that
+    hold a valid row can fill their hit list and be done a second time (without the floor every tile was)."""
     _say(f"tiled scan, nearly everything masked, {store} N={N} Q={Q} k={k}")
     cfg = workloads.Config("M", N=N, d=96, clusters=8, Q=Q, k=k, store=store, zipf=1.1, lam=0.2, util="uniform", seed=8400)
     wl = workloads.Workload(cfg, "cpu")
@@ -152,6 +153,8 @@ def test_tiled_scan_with_hardly_any_valid_row(pkg, oracle, store, N, Q, k):
         s, i = s.cpu().numpy(), i.cpu().numpy()
         assert ((i >= 0).sum(1) == min(k, n_valid)).all(), n_valid
         assert np.all(np.isneginf(s[i < 0])), n_valid
+        again, redone = ix.tiled_scan_counts()
+        assert redone == 0 and (n_valid > k + 1 or again <= n_valid * ((Q + 255) // 256)), (n_valid, again, redone)
         if n_valid:
             parity.check_batch(store, s, i, E.numpy(), U.numpy(), M, Qm.numpy(), k, 0.2, f"{n_valid} valid rows",
                                queries=[0, Q // 2, Q - 1])
