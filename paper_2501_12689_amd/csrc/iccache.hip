@@ -35,6 +35,7 @@ constexpr int kComputeUnitsDefault = 256;   // MI355X
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr size_t kMaxTimedEvents = 1 << 16;  // event pairs kept while timing is on
 constexpr int64_t kRegionSlots = 64 * (int64_t)kSliceBudgetMax;  // bound on queries x slices
+constexpr int kRedoSlices = 64;             // slices of the streaming pass that redoes query blocks of the tiled scan
 constexpr int kGemmMinQueries = 65;         // batches from here on use the MFMA-tiled scan (one tile is 256 queries wide, but from
                                             // 65 queries on it already beats two passes of the streaming scan: 4.1 vs 4.7 ms at d=768)
 constexpr int kGemmListSeg = ic::kMergeKeys;  // candidate lists are merged in segments of this many keys
@@ -74,6 +75,7 @@ struct Layout {
            total = 0;
     bool panel = false;  // the store has a step-major copy for the tiled scan
     int64_t list_slots = 0;
+    int64_t region_slots = 0;  // queries x slices that the candidate regions hold
     int q_rows = 0;  // rows of the prepared query block
 };
 
@@ -92,6 +94,10 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.q_chunk = (int)std::min<int64_t>(round_up(max_q, 64), kQueryChunkMax);
     L.q_rows = (int)round_up(L.q_chunk, ic::kGemmTile);
     const bool gemm = L.q_chunk >= kGemmMinQueries;
+    // A block of 64 queries that the tiled scan hands back is redone by one streaming pass over the store;
+    // that pass gets kRedoSlices workgroups for the block whatever the size of the batch, so the regions of
+    // an index that serves large batches hold that many slices for every query of a pass.
+    L.region_slots = gemm ? std::max<int64_t>(kRegionSlots, (int64_t)L.q_chunk * kRedoSlices) : kRegionSlots;
     L.list_slots = std::max<int64_t>(kRegionSlots / 8 + L.q_chunk, gemm ? (int64_t)L.q_chunk * (kGemmListMax / kGemmListSeg) : 0);
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -104,8 +110,8 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     L.off_util = take((size_t)L.cap_pad * 4);
     L.off_qbuf = take((size_t)L.q_rows * (size_t)L.row_bytes);
     L.off_qscale = take((size_t)L.q_rows * 4);
-    L.off_regions = take((size_t)kRegionSlots * (size_t)region_cap(max_k) * 8);
-    L.off_counts = take((size_t)kRegionSlots * 4);
+    L.off_regions = take((size_t)L.region_slots * (size_t)region_cap(max_k) * 8);
+    L.off_counts = take((size_t)L.region_slots * 4);
     L.off_list_a = take((size_t)L.list_slots * (size_t)max_k * 8);
     L.off_list_b = take((size_t)L.list_slots * (size_t)max_k * 8);
     L.off_consts = take(64);
@@ -350,7 +356,7 @@ static ic_status create_index(ic_index **out, int32_t d, ic_dtype store, int64_t
     W.redo = gemm ? (int32_t *)(base + L.off_redo) : nullptr;
     W.over = gemm ? (uint32_t *)(base + L.off_over) : nullptr;
     W.q_chunk = L.q_chunk;
-    W.region_slots = kRegionSlots;
+    W.region_slots = L.region_slots;
     W.consts_ready = &ix->consts_ready;
     ix->gemm_list_cap_override = 0;
     ix->timing = false;
@@ -839,7 +845,11 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
             budget = std::min(kSliceBudgetMax, index->compute_units * per_cu);
         }
         budget = (int)std::min<int64_t>(budget, W.region_slots / qb_rows);   // what the candidate regions hold
-        const int S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
+        int S = (int)std::min<int64_t>(std::max<int64_t>(1, budget / nqb), ntiles);
+        // after the tiled scan the streaming kernel only redoes flagged blocks (nearly always none, and the
+        // other workgroups return at once): a block gets kRedoSlices workgroups, not its share of one resident grid
+        if (gemm && index->slice_budget == 0)
+            S = (int)std::min<int64_t>(std::max<int64_t>(S, std::min<int64_t>(kRedoSlices, W.region_slots / ((int64_t)nqb * qb_rows))), ntiles);
         // Threshold pilot: a pass over a strided sample of the rows that keeps the best score
         // per (query, slice); the k-th largest of a query's slice maxima is reached by at least
         // k rows, so the full scan may start from it.
