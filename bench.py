@@ -40,8 +40,8 @@ MFMA_FP8_PEAK_TFLOPS = 5000.0
 # (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter reads for a plain
 # 1 GiB copy: 1,048,576 / 524,300 and 1.0).  Valid for the kernels as committed with the rocprofv3
 # summaries of these runs; set to None when a kernel changes until its counters are taken again.
-SCAN_TRAFFIC_BYTES_Q64 = (7_502_375 * (1_048_576 / 524_300) + 3_524) * 1024      # scan_stream, N = 10M, d = 768, Q = 64
-GEMM_TRAFFIC_BYTES_C4 = (23_502_636 * (1_048_576 / 524_300) + 223_716) * 1024    # scan_gemm, N = 4M, d = 1024, Q = 4096
+SCAN_TRAFFIC_BYTES_Q64 = (7_502_488 * (1_048_576 / 524_300) + 3_526) * 1024      # scan_stream, N = 10M, d = 768, Q = 64
+GEMM_TRAFFIC_BYTES_C4 = (23_786_629 * (1_048_576 / 524_300) + 225_161) * 1024    # scan_gemm, N = 4M, d = 1024, Q = 4096
 LARGE_Q = 4096
 
 

@@ -42,7 +42,8 @@
 //   * Scores: bf16 accumulators start at their row's bias (lambda * utility, -inf for rows that may
 //     not be selected), passed as the addend of the tile's first MFMAs, so the finished accumulator
 //     is the score; fp8 multiplies by the row's and the query's scale and adds the bias afterwards.
-//   * Selection: thresholds come from the pilot (a score that at least k rows reach, per query).
+//   * Selection: thresholds come from the pilot (per query a key, score then row, that at least k rows
+//     reach; rows with exactly its score pass only up to its row, so copies of one row cannot flood a list).
 //     A tile's 65,536 scores are compared 16 at a time (max, then one compare); a lane whose 16
 //     scores reach the threshold copies them to an LDS list, the workgroup then tests those few
 //     blocks exactly, one score per thread, and parks what passes (about 17 candidates per tile)
@@ -55,7 +56,7 @@
 //     queries is flagged and redone by the streaming scan, so the result stays exact whatever the data.
 //   * Pilot launches (PILOT = true) run the same pipeline over a strided sample of the rows (every
 //     row_stride-th row; a tile takes 256 of them spread evenly over the whole store) and keep, per
-//     query and slice, only the best score.
+//     query and slice, only the best key: the best score and the row it belongs to.
 //   * Row-maximum launches (ROWMAX = true) turn the selection around: for every cached row the
 //     best of the "queries" (with ties to the lowest query id), as one 64-bit key per row.  This
 //     is the assignment step of K-Means (Sec. 4.1): the queries are the centroids.
@@ -86,7 +87,8 @@ struct GemmArgs {
     const uint8_t *qbuf;     // prepared queries, [nqb*256] rows
     const float *q_scale;    // fp8: per prepared query
     int Q;                   // real queries
-    const uint64_t *thr_init;  // [Q] key of a score that >= k rows reach (or of kNoThresholdScore: every row with a score passes)
+    const uint64_t *thr_init;  // [Q] a key that >= k rows reach, as this kernel computes their scores (or the key of
+                               // kNoThresholdScore: every row with a score passes)
     uint64_t *glist;         // [Q][gcap] candidate keys
     int gcap;
     int32_t *gcount;         // [Q] candidates appended (may exceed gcap: the list overflowed)
@@ -96,7 +98,7 @@ struct GemmArgs {
     uint32_t over_cap;
     int nqb;                 // query blocks of 256
     int64_t ntiles;          // row tiles of 256
-    uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over the slice so far, id = slice)
+    uint64_t *pilot_out;     // pilot launches: [Q][pilot_stride] keys (best score over the slice so far, and the row it belongs to)
     int pilot_stride;
     int64_t row_stride;      // PILOT: the launch scores rows 0, row_stride, 2 * row_stride, ... only.  Row r of its
                              // t-th tile is row r * ntiles + t of that sample, so every tile, and with it every
@@ -677,17 +679,21 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
             continue;
         }
         if (PILOT) {
-            // Pilot launch: the best score of every query over this tile's 256 sampled rows, combined
-            // into the query's slice (tile of the sample modulo pilot_stride) with a 64-bit atomic maximum.
-            uint32_t *pmax = reinterpret_cast<uint32_t *>(hits);  // [kGemmTile] order-preserving score bits
+            // Pilot launch: the best key (score, then row) of every query over this tile's 256 sampled rows,
+            // combined into the query's slice (tile of the sample modulo pilot_stride) with a 64-bit atomic
+            // maximum.  The key names the row the score belongs to, so that the k-th largest key of a query's
+            // slices is a key that k rows of the store reach, row ids included: among rows with exactly the
+            // threshold's score (copies of one row) only those up to that id pass the selection.
+            uint64_t *pmax = reinterpret_cast<uint64_t *>(hits);  // [kGemmTile] best key per query
             if (tid < 64) {
                 *reinterpret_cast<f32x4 *>(bias_t + tid * 4) = bias_r;
                 if (ET == 1) *reinterpret_cast<f32x4 *>(scale_t + tid * 4) = scale_r;
                 if (DOM) *reinterpret_cast<i32x4 *>(dom_t + tid * 4) = dom_r;
             }
-            if (tid < kGemmTile) pmax[tid] = 0u;
+            if (tid < kGemmTile) pmax[tid] = 0ull;
             lds_barrier();
             float best[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            int brow[4] = {0, 0, 0, 0};   // row of the best score within the lane's rows: i * 32 + 8 * (v / 4) + v % 4
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 f32x4 bs[4], rs[4];
@@ -706,18 +712,26 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                         float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
                                             : acc[i][j][v];   // bf16: the bias is in it from the start
                         if (DOM && ds[v >> 2][v & 3] != 0 && ds[v >> 2][v & 3] != qd[j]) x = -INFINITY;
-                        best[j] = fmaxf(best[j], x);
+                        if (x > best[j]) {
+                            best[j] = x;
+                            brow[j] = i * 32 + 8 * (v >> 2) + (v & 3);
+                        }
                     }
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) atomicMax(pmax + wn * 128 + j * 32 + r32, ord_of_score(best[j]));
+            for (int j = 0; j < 4; ++j) {
+                // row r of the tile is row r * ntiles + row0 of the sample, which is every row_stride-th row
+                const int64_t sampled = (int64_t)(wm * 64 + 4 * h + brow[j]) * a.ntiles + row0;
+                atomicMax(reinterpret_cast<unsigned long long *>(pmax) + wn * 128 + j * 32 + r32,
+                          (unsigned long long)make_key(best[j], (uint32_t)(sampled * a.row_stride)));
+            }
             lds_barrier();
             if (tid < kGemmTile) {
                 const int q = qb * kGemmTile + tid;
                 const uint32_t slice = (uint32_t)(row0 % a.pilot_stride);
                 if (q < a.Q)
                     atomicMax(reinterpret_cast<unsigned long long *>(a.pilot_out) + (size_t)q * a.pilot_stride + slice,
-                              ((unsigned long long)pmax[tid] << 32) | (unsigned long long)(0xFFFFFFFFu - slice));
+                              (unsigned long long)pmax[tid]);
             }
             continue;  // the K-loop barriers of the next tile separate these reads from the next reset
         }
@@ -790,7 +804,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                     const int q = qb * kGemmTile + wn * 128 + j * 32 + r32;
                     if (q >= a.Q) continue;
                     const uint64_t t0 = thr_raw[j];
-                    const uint64_t thr_k = t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
+                    const uint64_t thr_k = t0 > kKeyFloor ? t0 - 1ull : kKeyFloor;   // the pilot's key itself passes
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const float x = (ET == 1) ? acc[i][j][v] * (rs[v >> 2][v & 3] * qs[j]) + bs[v >> 2][v & 3]
@@ -863,7 +877,7 @@ __global__ __launch_bounds__(kGemmThreads) void scan_gemm(const GemmArgs a) {
                 const HitEntry &he = hits[e];
                 const float x = he.sc[v >> 2][v & 3];
                 const uint64_t t0 = he.thr;
-                const uint64_t thr_k = t0 > kKeyFloor ? ((t0 >> 32) << 32) - 1ull : kKeyFloor;
+                const uint64_t thr_k = t0 > kKeyFloor ? t0 - 1ull : kKeyFloor;   // the pilot's key itself passes
                 const uint32_t row = he.row + 8 * (v >> 2) + (v & 3);
                 const uint64_t key = make_key(x, row);
                 if (key > thr_k && x > -INFINITY) {

@@ -178,9 +178,11 @@ def test_large_batch_list_overflow_is_redone_exactly(pkg, oracle):
 @pytest.mark.parametrize("store", ["bf16", "fp8"])
 def test_large_batch_with_a_row_stored_thousands_of_times(pkg, oracle, store):
     """14,000 copies of one row (a request that keeps coming back), three queries of a batch of 1,100 next
-    to it: every copy reaches those queries' thresholds, their candidate lists (4,096 keys) overflow, and
-    their blocks of 64 queries are redone by the streaming scan, with lists at their normal size and the
-    slices the library chooses.  The result is the copies with the lowest ids; the other blocks are not redone."""
+    to it.  Every copy has the score of those queries' thresholds; the pilot's threshold is a key that names
+    a row, so only the copies up to that row pass and no candidate list (4,096 keys) overflows: nothing is
+    redone, and the result is the copies with the lowest ids.  Then the same search with lists of 8 keys:
+    all 18 blocks of 64 queries are redone by the streaming scan, on the slices the library chooses for
+    a batch of this size, with the same result."""
     _say(f"tiled scan, one row stored 14,000 times, {store}")
     N, d, Q, k = 70000, 96, 1100, 16
     cfg = workloads.Config("G", N=N, d=d, clusters=16, Q=Q, k=k, store=store, zipf=1.1, seed=8170)
@@ -193,16 +195,19 @@ def test_large_batch_with_a_row_stored_thousands_of_times(pkg, oracle, store):
         Qm[q] = E[7] + 0.01 * Qm[q]
     ix = pkg.Index(d, N, pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3, Q, 128, DEV)
     ix.append(E.to(DEV))
-    s, i = ix.search(Qm.to(DEV), k, 0.0, None)
-    torch.cuda.synchronize()
-    again, redone = ix.tiled_scan_counts()
+    for list_cap, blocks in ((None, 0), (8, (Q + 63) // 64)):
+        if list_cap is not None:
+            ix.set_tuning(list_keys=list_cap)
+        s, i = ix.search(Qm.to(DEV), k, 0.0, None)
+        torch.cuda.synchronize()
+        again, redone = ix.tiled_scan_counts()
+        s, i = s.cpu().numpy(), i.cpu().numpy()
+        assert redone == blocks, (list_cap, again, redone)
+        for q in near:
+            assert list(i[q]) == [7] + list(range(100, 100 + 5 * (k - 1), 5)), (list_cap, q)
+        parity.check_batch(store, s, i, E.numpy(), None, None, Qm.numpy(), k, 0.0, f"copies {store} {list_cap}",
+                           queries=sorted(set(near + list(range(3, Q, 97)))))
     ix.close()
-    s, i = s.cpu().numpy(), i.cpu().numpy()
-    assert 3 <= redone <= 6, (again, redone)   # the three blocks, and at most those of queries that happen to lie as close
-    for q in near:
-        assert list(i[q]) == [7] + list(range(100, 100 + 5 * (k - 1), 5)), q
-    parity.check_batch(store, s, i, E.numpy(), None, None, Qm.numpy(), k, 0.0, f"copies {store}",
-                       queries=sorted(set(near + list(range(3, Q, 97)))))
 
 
 @pytest.mark.parametrize("lam", [50.0, 2000.0])
