@@ -205,3 +205,51 @@ def test_c5_full_with_appends(pkg, oracle):
     assert torch.equal(i2[100], i3[0]) and torch.equal(s2[100], s3[0])
     # the tiled half of the sweep, up to the largest batch the layout allows
     _tiled_batch_check(pkg, run, ref, "C5 (tiled, fp8)", Qs=(128, 256, 512, 1024, 2048, 4096, 8192))
+
+
+def test_store_of_100_million_short_rows(pkg, oracle):
+    """Row ids past 2^26 and a store (row-major and step-major copies) of 12.8 GB each made of 128-byte
+    rows, the shortest there are: the tiled scan (256 queries) and the streaming scan (the first 64 of
+    them) against the reference on four queries, two of which sit next to the last rows of the store;
+    then a tenth of the rows is evicted and squeezed out and the searches are repeated."""
+    cfg = workloads.Config("L", N=100_000_001, d=64, clusters=64, Q=256, k=10, store="fp8", zipf=1.1, lam=0.1,
+                           util="uniform", p_valid=0.9, seed=126890 + 6)
+    _say(f"{cfg}")
+    sample = [0, 1, 63, 255]
+    run = _Run(pkg, oracle, cfg, sample)
+    # queries 0 and 1 are (nearly) the last two rows; the reference gets the same queries
+    tail, _, _ = run.wl.rows(cfg.N - 2, 2)
+    run.Qd[:2] = tail + 0.01 * run.Qd[:2]
+    run.Qm = run.Qd.cpu().numpy()
+    run.scan = oracle.Scan(run.Qm[sample], run.kk, cfg.lam)
+    run.feed(cfg.N)
+    ref = run.reference()
+    s, i = _search(run)
+    print(f"   tiles done again, blocks redone: {run.ix.tiled_scan_counts()}", flush=True)
+    run.check(s, i, ref, "100 M rows, tiled")
+    s64, i64 = _search(run, 64)
+    run.check(s64, i64, ref, "100 M rows, streaming")
+    assert int(i.max()) >= cfg.N - 2 or int(i64.max()) >= cfg.N - 2 or not bool(run.M[cfg.N - 2:].any())
+    # evict every tenth row but the sampled queries' neighbours' chances stay as the reference sees them:
+    # the reference is run again over the surviving rows
+    g = torch.Generator(device=DEV)
+    g.manual_seed(6)
+    gone = torch.randperm(cfg.N, device=DEV, generator=g)[: cfg.N // 10]
+    run.ix.invalidate(gone)
+    id_map = run.ix.compact()
+    keep = id_map >= 0
+    assert int(keep.sum()) == len(run.ix) == cfg.N - gone.numel()
+    run.E, run.U, run.M = run.E[keep], run.U[keep], run.M[keep]
+    scan2 = oracle.Scan(run.Qm[sample], run.kk, cfg.lam)
+    n2 = len(run.ix)
+    run.n_valid = 0
+    for lo in range(0, n2, CHUNK):
+        hi = min(n2, lo + CHUNK)
+        Mh = run.M[lo:hi].cpu().numpy()
+        scan2.scan(run.E[lo:hi].cpu().numpy(), run.U[lo:hi].cpu().numpy(), Mh)
+        run.n_valid += int(Mh.sum())
+    _, ids2, s2 = scan2.finish()
+    s, i = _search(run)
+    run.check(s, i, (ids2, s2), "90 M rows after compaction, tiled")
+    s64, i64 = _search(run, 64)
+    run.check(s64, i64, (ids2, s2), "90 M rows after compaction, streaming")
