@@ -134,6 +134,20 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
     return true;
 }
 
+// 64-byte chunks of a row per wavefront of the streaming scan.  An even number lets a wavefront fetch whole
+// 128-byte lines, so rows of 12, 18 or 20 chunks (768, 1152, 1280 bytes) are dealt 4, 6 and 6 to a wavefront
+// instead of 3, 5 and 5 (the last wavefront gets fewer or none and multiplies its surplus by zeros).  Measured
+// on stores of 6 GB: 7-10 % faster for up to 32 queries at the three lengths, 4-8 % faster for 64 queries at
+// 1152 and 1280 bytes, 4-5 % slower for 64 queries at 768 bytes.  Rows of 10, 26 and 28 chunks keep the odd
+// deal: the even one costs 64 queries 4-17 % there (and gains nothing at 10 chunks).  The deal depends on the
+// row length only, because it fixes the order in which a row's products are added: a query's scores must not
+// depend on the batch it came in, nor on whether the search was pruned by clusters.
+inline int chunks_per_wavefront(int nchunks) {
+    int cpw = (nchunks + ic::kScanWaves - 1) / ic::kScanWaves;
+    if (nchunks == 12 || nchunks == 18 || nchunks == 20) cpw += 1;
+    return cpw;
+}
+
 // 64 zero bytes: the score bias of a search that has neither utility weight nor mask.
 __global__ void init_consts(uint32_t *c) {
     if (threadIdx.x < 16) c[threadIdx.x] = 0u;
@@ -726,16 +740,7 @@ ic_status search_impl(ic_index *index, const Workspace &W, int64_t Q, int32_t k_
     const Layout &L = index->L;
     const int et = (index->store == IC_STORE_BF16) ? 0 : 1;
     const int nchunks = L.row_bytes / 64;
-    // 64-byte chunks of a row per wavefront of the streaming scan.  An even number lets a wavefront fetch whole
-    // 128-byte lines, so rows of 12, 18 or 20 chunks (768, 1152, 1280 bytes) are dealt 4, 6 and 6 to a wavefront
-    // instead of 3, 5 and 5 (the last wavefront gets fewer or none and multiplies its surplus by zeros).  Measured
-    // on stores of 6 GB: 7-10 % faster for up to 32 queries at the three lengths, 4-8 % faster for 64 queries at
-    // 1152 and 1280 bytes, 4-5 % slower for 64 queries at 768 bytes.  Rows of 10, 26 and 28 chunks keep the odd
-    // deal: the even one costs 64 queries 4-17 % there (and gains nothing at 10 chunks).  The deal depends on the
-    // row length only, because it fixes the order in which a row's products are added: a query's scores must not
-    // depend on the batch it came in.
-    int cpw = (nchunks + ic::kScanWaves - 1) / ic::kScanWaves;
-    if (nchunks == 12 || nchunks == 18 || nchunks == 20) cpw += 1;
+    const int cpw = chunks_per_wavefront(nchunks);
     const int64_t n = index->n;
     const int64_t ntiles = (n + 15) / 16;
     hipStream_t st = index->stream;
@@ -1394,7 +1399,7 @@ ic_status ic_ivf_search(ic_ivf *ivf, const float *q_dev, int64_t Q, int32_t k, i
     s->stream = st;
     const Layout &L = s->L;
     const int et = (s->store == IC_STORE_BF16) ? 0 : 1;
-    const int cpw = (L.row_bytes / 64 + ic::kScanWaves - 1) / ic::kScanWaves;
+    const int cpw = chunks_per_wavefront(L.row_bytes / 64);
     const int cap = region_cap_for(k, 0);
     const int64_t n = s->n;
     if (!s->consts_ready) {
