@@ -135,16 +135,17 @@ bool make_layout(int32_t d, ic_dtype store, int64_t capacity, int64_t max_q, int
 }
 
 // 64-byte chunks of a row per wavefront of the streaming scan.  An even number lets a wavefront fetch whole
-// 128-byte lines, so rows of 12, 18 or 20 chunks (768, 1152, 1280 bytes) are dealt 4, 6 and 6 to a wavefront
-// instead of 3, 5 and 5 (the last wavefront gets fewer or none and multiplies its surplus by zeros).  Measured
-// on stores of 6 GB: 7-10 % faster for up to 32 queries at the three lengths, 4-8 % faster for 64 queries at
-// 1152 and 1280 bytes, 4-5 % slower for 64 queries at 768 bytes.  Rows of 10, 26 and 28 chunks keep the odd
-// deal: the even one costs 64 queries 4-17 % there (and gains nothing at 10 chunks).  The deal depends on the
-// row length only, because it fixes the order in which a row's products are added: a query's scores must not
-// depend on the batch it came in, nor on whether the search was pruned by clusters.
+// 128-byte lines, so rows of 18 or 20 chunks (1152, 1280 bytes) are dealt 6 to a wavefront instead of 5 (the last
+// wavefront gets 0 or 2 and multiplies its surplus by zeros).  Measured on stores of 1 M rows and of 6 GB: 4-10 %
+// faster for every batch size (on 100 k rows, which the caches hold: the same up to 32 queries, 7 % slower for 64).
+// Rows of 10, 12, 26 and 28 chunks keep the odd deal: the even one gains 7-10 % for up to 32 queries on large
+// stores at 12, 26 and 28 chunks but costs 64 queries 5-13 % there, and on 100 k rows of 12 chunks it costs every
+// batch size 2-3 us.  The deal depends on the row length only, because it fixes the order in which a row's
+// products are added: a query's scores must not depend on the batch it came in, nor on whether the search was
+// pruned by clusters.
 inline int chunks_per_wavefront(int nchunks) {
     int cpw = (nchunks + ic::kScanWaves - 1) / ic::kScanWaves;
-    if (nchunks == 12 || nchunks == 18 || nchunks == 20) cpw += 1;
+    if (nchunks == 18 || nchunks == 20) cpw += 1;
     return cpw;
 }
 

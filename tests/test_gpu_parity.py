@@ -200,8 +200,8 @@ CASES = [
     ("fp8", 7000, 2048, 16, 64, 40, 0.0, "none", 1.0),
     ("fp8", 6000, 1536, 8, 57, 8, 0.2, "beta25", 1.0),
     ("fp8", 6000, 1280, 8, 64, 16, 0.0, "none", 0.9),
-    # rows of 12, 18 and 20 chunks are dealt 4, 6 and 6 chunks to a wavefront (whole 128-byte lines), so the
-    # last wavefront has none or two of its own; 10 and 26 chunks keep 3 and 7
+    # rows of 18 and 20 chunks are dealt 6 chunks to a wavefront (whole 128-byte lines), so the last
+    # wavefront has none or two of its own; 10, 12 and 26 chunks keep 3, 3 and 7
     ("fp8", 9000, 768, 16, 17, 24, 0.1, "uniform", 0.9),
     ("bf16", 7000, 576, 8, 64, 16, 0.0, "none", 1.0),
     ("fp8", 7000, 1152, 8, 9, 40, 0.2, "beta25", 0.9),
