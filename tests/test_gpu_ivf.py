@@ -306,6 +306,29 @@ def test_pruned_search_does_not_depend_on_the_batch(pkg, oracle, store):
     ivf.close(); ix.close()
 
 
+@pytest.mark.parametrize("store,d", [("bf16", 384), ("bf16", 576), ("fp8", 1280), ("bf16", 768), ("fp8", 1024)])
+def test_pruned_search_over_all_lists_equals_the_full_scan(pkg, store, d):
+    """With every list probed the pruned search sees every row, through the same kernel arithmetic as the
+    full scan (the same deal of a row's chunks to the wavefronts, whatever the row length): same ids, same
+    score bits."""
+    _say(f"pruned search over all lists against the full scan, {store} d={d}")
+    N, K, Q, k = 60000, 16, 40, 20
+    cfg = workloads.Config("V", N=N, d=d, clusters=K, Q=Q, k=k, store=store, zipf=1.1, lam=0.1, util="uniform", seed=9900 + d)
+    wl = workloads.Workload(cfg, DEV)
+    E, U, _ = wl.rows(0, N)
+    ix = pkg.Index(d, N, pkg.STORE_BF16 if store == "bf16" else pkg.STORE_FP8_E4M3, 64, 64, DEV)
+    ix.append(E, U)
+    ivf = pkg.Ivf(ix, K, K)
+    ivf.train(3)
+    qd = wl.queries(Q)
+    s1, i1 = ix.search(qd, k, 0.1, None)
+    s2, i2 = ivf.search(qd, k, K, 0.1)
+    torch.cuda.synchronize()
+    ivf.close()
+    ix.close()
+    assert torch.equal(i1, i2) and torch.equal(s1, s2)
+
+
 def test_many_centroids_and_a_large_batch_take_the_tiled_scan(pkg, oracle):
     """With 16,400 centroids and 200 queries the probe step (nearest centroids of every query) is a
     batch large enough for the MFMA-tiled scan over the centroid index, whose step-major copy is
